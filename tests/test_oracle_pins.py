@@ -1,0 +1,397 @@
+"""Pins for the CPU oracle: what the paper prints, closed forms, invariants,
+brute force on tiny inputs.  None of these calls the HIP path."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import qgnn, bitplane as bp
+from conftest import load_golden
+
+
+# ---------------------------------------------------------------- brute force
+def py_matmul(L, R):
+    """Textbook triple loop on Python integers (no wrap)."""
+    n, k, m = len(L), len(R), len(R[0])
+    return [[sum(int(L[i][x]) * int(R[x][j]) for x in range(k))
+             for j in range(m)] for i in range(n)]
+
+
+def py_bit_matmul(L, R, lb, rb):
+    """sum_i sum_j 2^(i+j) popcnt(plane_i(L row) & plane_j(R col)), Python ints."""
+    n, k, m = len(L), len(R), len(R[0])
+    out = [[0] * m for _ in range(n)]
+    for r in range(n):
+        for c in range(m):
+            acc = 0
+            for i in range(lb):
+                lw = sum(((int(L[r][x]) >> i) & 1) << x for x in range(k))
+                for j in range(rb):
+                    rw = sum(((int(R[x][c]) >> j) & 1) << x for x in range(k))
+                    acc += bin(lw & rw).count("1") << (i + j)
+            out[r][c] = acc
+    return out
+
+
+# ------------------------------------------------------- the paper's examples
+def test_paper_popcnt_example():
+    g = load_golden("paper_examples.txt")
+    assert bp.popcnt(g["popcnt_arg"][0]) == g["popcnt_val"][0]
+    assert g["popcnt_arg"][0] == 0b1011
+
+
+def test_paper_eq5_expansion_exhaustive():
+    """Eq. (5): the printed 3-bit x 2-bit expansion equals a*b for all 32 pairs,
+    and so do the oracle's product and the literal bit-plane product."""
+    terms = load_golden("paper_examples.txt")["eq5_terms"]
+    for a, b in itertools.product(range(8), range(4)):
+        printed = sum(((a >> ai) & 1) * ((b >> bi) & 1) << sh
+                      for ai, bi, sh in terms)
+        assert printed == a * b
+        L = np.array([[a]], dtype=np.uint32)
+        R = np.array([[b]], dtype=np.uint32)
+        assert int(qgnn.matmul_mod32(L, R)[0, 0]) == a * b
+        assert int(bp.any_bit_matmul(L, R, 3, 2)[0, 0]) == a * b
+
+
+def test_eq6_vector_form():
+    """Eq. (6)/(7): 3-bit . 2-bit vectors of length k via shifted popcounts."""
+    rng = np.random.default_rng(1)
+    for k in (1, 5, 33, 70):
+        vi = rng.integers(0, 8, size=(1, k))
+        vj = rng.integers(0, 4, size=(k, 1))
+        want = int((vi.astype(np.int64) @ vj.astype(np.int64))[0, 0])
+        assert py_bit_matmul(vi.tolist(), vj.tolist(), 3, 2)[0][0] == want
+        assert int(bp.any_bit_matmul(vi, vj, 3, 2)[0, 0]) == want
+        assert int(qgnn.matmul_mod32(vi, vj)[0, 0]) == want
+
+
+# -------------------------------------------------------- hand-computed layer
+def test_hand_computed_layer():
+    g = load_golden("layer_4x4.txt")
+    A = np.array(g["A"], dtype=np.uint8)
+    X = np.array(g["X"], dtype=np.uint32)
+    W = np.array(g["W"], dtype=np.uint32)
+    Y = qgnn.aggregate(A, X)
+    assert Y.tolist() == g["Y"]
+    assert qgnn.aggregate(A, X, self_term=True).tolist() == g["Y_gin"]
+    assert qgnn.update(Y, W).tolist() == g["Z"]
+    assert qgnn.degrees(A).tolist() == g["deg"]
+    # sparse adjacency input gives the same
+    import scipy.sparse as sp
+    assert qgnn.aggregate(sp.csr_matrix(A), X).tolist() == g["Y"]
+    # Algorithm 1 taken literally
+    xn, z = bp.algorithm1_layer(A, X, W, g["s"][0], g["t"][0])
+    assert xn.tolist() == g["Y"] and z.tolist() == g["Z"]
+    # requantize
+    inv = qgnn.inv_scale(g["rq_lo"][0], g["rq_hi"][0], g["rq_bits"][0])
+    assert float(inv) == 0.25
+    assert qgnn.requantize(Y, g["rq_lo"][0], inv, g["rq_bits"][0]).tolist() == g["Yq2"]
+    # dequantize the aggregation
+    sx = qgnn.scale(g["lo_x"][0], g["hi_x"][0], g["s"][0])
+    yh = qgnn.dequantize(Y, cc=sx, rs=g["lo_x"][0], row_i=g["deg"])
+    assert yh.tolist() == g["Yhat"]
+
+
+# ------------------------------------------------ brute force on tiny inputs
+@pytest.mark.parametrize("s,t", [(s, t) for s in range(1, 9) for t in range(1, 9)])
+def test_layer_vs_brute_force_small_bits(s, t):
+    rng = np.random.default_rng([7, s, t])
+    n, d, h = 9, 7, 5
+    A = (rng.random((n, n)) < 0.35).astype(np.uint8)
+    X = rng.integers(0, 2 ** s, size=(n, d)).astype(np.uint32)
+    W = rng.integers(0, 2 ** t, size=(d, h)).astype(np.uint32)
+    Yb = py_matmul(A.tolist(), X.tolist())
+    assert py_bit_matmul(A.tolist(), X.tolist(), 1, s) == Yb
+    Y = qgnn.aggregate(A, X)
+    assert Y.tolist() == Yb
+    # exact chain (identity requant): (A.Xq).Wq
+    Zb = py_matmul(Yb, W.tolist())
+    assert qgnn.update(Y, W).tolist() == Zb
+    _, z1 = bp.algorithm1_layer(A, X, W, s, t)
+    assert z1.tolist() == Zb
+    # requantized chain, s-bit Yq
+    Yr, Yq, Z, rq = qgnn.layer(A, X, W, s)
+    assert Yr.tolist() == Yb and int(Yq.max()) < 2 ** s
+    assert Z.tolist() == py_bit_matmul(Yq.tolist(), W.tolist(), s, t)
+
+
+@pytest.mark.parametrize("bits", [16, 32])
+def test_wrap_mod_2_32_vs_bigints(bits):
+    rng = np.random.default_rng([9, bits])
+    n, d, h = 6, 40, 4
+    A = (rng.random((n, n)) < 0.6).astype(np.uint8)
+    X = rng.integers(0, 2 ** bits, size=(n, d), dtype=np.uint64).astype(np.uint32)
+    W = rng.integers(0, 2 ** bits, size=(d, h), dtype=np.uint64).astype(np.uint32)
+    # force extreme values too
+    X[0, :] = 2 ** bits - 1
+    W[:, 0] = 2 ** bits - 1
+    Yb = py_matmul(A.tolist(), X.tolist())
+    Y = qgnn.aggregate(A, X)
+    assert Y.tolist() == [[v % 2 ** 32 for v in r] for r in Yb]
+    Z = qgnn.update(X, W)
+    Zb = py_matmul(X.tolist(), W.tolist())
+    assert max(max(r) for r in Zb) >= 2 ** 32 or bits == 16
+    assert Z.tolist() == [[v % 2 ** 32 for v in r] for r in Zb]
+    # shifted popcounts, truncated to 32 bits, agree (terms with i+j >= 32 vanish)
+    Zp = py_bit_matmul(X.tolist(), W.tolist(), bits, bits)
+    assert [[v % 2 ** 32 for v in r] for r in Zp] == Z.tolist()
+
+
+def test_matmul_float64_and_uint64_paths_agree():
+    rng = np.random.default_rng(3)
+    L = rng.integers(0, 2 ** 32, size=(5, 33), dtype=np.uint64).astype(np.uint32)
+    R = rng.integers(0, 2 ** 32, size=(33, 4), dtype=np.uint64).astype(np.uint32)
+    want = [[v % 2 ** 32 for v in r] for r in py_matmul(L.tolist(), R.tolist())]
+    assert qgnn.matmul_mod32(L, R).tolist() == want            # uint64 path
+    Ls, Rs = L >> 20, R >> 20                                   # float64 path
+    want = [[v % 2 ** 32 for v in r] for r in py_matmul(Ls.tolist(), Rs.tolist())]
+    assert qgnn.matmul_mod32(Ls, Rs).tolist() == want
+
+
+# ------------------------------------------------------ aggregation invariants
+def _rand_graph(rng, n, p, sym=True):
+    u = rng.random((n, n)) < p
+    if sym:
+        u = np.triu(u, 1)
+        u = u | u.T
+    return u.astype(np.uint8)
+
+
+def test_one_bit_all_ones_gives_degrees():
+    rng = np.random.default_rng(4)
+    A = _rand_graph(rng, 50, 0.2)
+    X = np.ones((50, 3), dtype=np.uint32)
+    Y = qgnn.aggregate(A, X)
+    assert (Y == A.sum(axis=1, dtype=np.int64)[:, None]).all()
+    assert (qgnn.degrees(A) == Y[:, 0]).all()
+
+
+def test_identity_and_all_ones_adjacency():
+    rng = np.random.default_rng(5)
+    X = rng.integers(0, 16, size=(20, 6)).astype(np.uint32)
+    assert (qgnn.aggregate(np.eye(20, dtype=np.uint8), X) == X).all()
+    Y = qgnn.aggregate(np.ones((20, 20), dtype=np.uint8), X)
+    assert (Y == X.sum(axis=0, dtype=np.int64)[None, :]).all()
+
+
+def test_symmetric_sum_identity_and_permutation_equivariance():
+    rng = np.random.default_rng(6)
+    n = 40
+    A = _rand_graph(rng, n, 0.15)
+    X = rng.integers(0, 256, size=(n, 5)).astype(np.uint32)
+    Y = qgnn.aggregate(A, X).astype(np.int64)
+    deg = A.sum(axis=1, dtype=np.int64)
+    assert (Y.sum(axis=0) == (deg[:, None] * X).sum(axis=0)).all()
+    p = rng.permutation(n)
+    Yp = qgnn.aggregate(A[np.ix_(p, p)], X[p])
+    assert (Yp == Y[p]).all()
+
+
+def test_transposed_operand_would_fail():
+    """A directed (asymmetric) example: row v sums in-row neighbours only."""
+    A = np.array([[0, 1, 1], [0, 0, 0], [1, 0, 0]], dtype=np.uint8)
+    X = np.array([[1], [10], [100]], dtype=np.uint32)
+    assert qgnn.aggregate(A, X).ravel().tolist() == [110, 0, 1]
+
+
+def test_extra_zero_planes_change_nothing():
+    rng = np.random.default_rng(8)
+    A = _rand_graph(rng, 12, 0.3)
+    X = rng.integers(0, 8, size=(12, 4)).astype(np.uint32)
+    a = bp.any_bit_matmul(A, X, 1, 3)
+    b = bp.any_bit_matmul(A, X, 1, 7)
+    assert (a == b).all()
+
+
+# ------------------------------------------------------------- quantization
+def test_quantize_hand_grid():
+    g = load_golden("quantize_2bit.txt")
+    q = qgnn.quantize(np.array(g["x"], dtype=np.float32), g["lo"][0], g["hi"][0],
+                      g["bits"][0])
+    assert q.tolist() == g["q"]
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5, 8, 12, 16, 24])
+def test_quantize_closed_form_on_grid(bits):
+    """x = lo + (k + 1/2) * scale quantizes to k when lo and scale are powers of
+    two (every operation is then exact in fp32)."""
+    lo, hi = -4.0, 4.0
+    sc = 8.0 / 2 ** bits
+    ks = np.unique(np.linspace(0, 2 ** bits - 1, 97).astype(np.int64))
+    half = 0.5 if bits <= 20 else 0.0      # keep x exactly representable in fp32
+    x64 = lo + (ks + half) * sc
+    x = x64.astype(np.float32)
+    assert (x.astype(np.float64) == x64).all()
+    assert qgnn.quantize(x, lo, hi, bits).tolist() == ks.tolist()
+    assert int(qgnn.quantize(np.float32(hi), lo, hi, bits)) == 2 ** bits - 1
+    assert int(qgnn.quantize(np.float32(lo), lo, hi, bits)) == 0
+    assert int(qgnn.quantize(np.float32(-100), lo, hi, bits)) == 0
+    assert int(qgnn.quantize(np.float32(100), lo, hi, bits)) == 2 ** bits - 1
+
+
+@pytest.mark.parametrize("bits", [1, 2, 4, 8, 16, 32])
+def test_quantize_monotone_bounded_and_close(bits):
+    rng = np.random.default_rng([10, bits])
+    x = np.sort(rng.standard_normal(4000).astype(np.float32))
+    lo, hi = float(x.min()), float(x.max())
+    q = qgnn.quantize(x, lo, hi, bits).astype(np.int64)
+    assert (np.diff(q) >= 0).all() and q.min() == 0 and q.max() <= 2 ** bits - 1
+    # above 24 bits fp32 cannot hit the top code exactly
+    assert q.max() == 2 ** bits - 1 if bits <= 16 else q.max() >= (2 ** bits - 1) * (1 - 1e-6)
+    xh = qgnn.dequantize_values(q, lo, hi, bits)
+    sx = qgnn.scale(lo, hi, bits)
+    err = x.astype(np.float64) - xh
+    # floor: the value lies in [xh, xh + sx) up to fp32 rounding; the top code
+    # also absorbs x = hi
+    tol = 1e-6 * (hi - lo)
+    assert (err > -tol).all() and (err <= sx + tol).all()
+
+
+def test_requantize_rule():
+    c = np.array([[0, 1, 5, 6, 11, 12, 2 ** 31 - 1, 2 ** 32 - 3]], dtype=np.uint32)
+    inv = np.float32(0.5)
+    # signed reading: 2^32-3 is -3 -> below rq_lo -> 0 ; big value clamps
+    assert qgnn.requantize(c, 1, inv, 3).tolist() == [[0, 0, 2, 2, 5, 5, 7, 0]]
+    assert qgnn.requantize(c, -4, inv, 3, relu=True).tolist() == [[2, 2, 4, 5, 7, 7, 7, 2]]
+    assert qgnn.requantize(c, -4, inv, 3, relu=False).tolist() == [[2, 2, 4, 5, 7, 7, 7, 0]]
+    # identity requant reproduces the value when it fits
+    v = np.array([[0, 3, 200, 65535]], dtype=np.uint32)
+    assert (qgnn.requantize(v, 0, np.float32(1.0), 16) == v).all()
+    # 32 bits: no overflow at the top
+    big = np.array([[2 ** 31 - 1]], dtype=np.uint32)
+    assert int(qgnn.requantize(big, 0, np.float32(4.0), 32)[0, 0]) == 2 ** 32 - 1
+
+
+# --------------------------------------------------------------- dequantize
+@pytest.mark.parametrize("self_term", [False, True])
+def test_dequantized_layer_equals_real_product(self_term):
+    """The affine-corrected fp32 outputs equal the products of the dequantized
+    operands taken directly in float64."""
+    rng = np.random.default_rng([11, int(self_term)])
+    n, d, h, s, t = 60, 24, 7, 5, 4
+    A = _rand_graph(rng, n, 0.1)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    W = rng.uniform(-0.1, 0.1, size=(d, h)).astype(np.float32)
+    lox, hix = float(X.min()), float(X.max())
+    low, hiw = float(W.min()), float(W.max())
+    Xq = qgnn.quantize(X, lox, hix, s)
+    Wq = qgnn.quantize(W, low, hiw, t)
+    sx, sw = qgnn.scale(lox, hix, s), qgnn.scale(low, hiw, t)
+    Xh = lox + sx * Xq.astype(np.float64)
+    Wh = low + sw * Wq.astype(np.float64)
+    Ad = A.astype(np.float64) + (np.eye(n) if self_term else 0.0)
+    deg = Ad.sum(axis=1)
+    Y, Yq, Z, (rq_lo, rq_inv) = qgnn.layer(A, Xq, Wq, s, self_term=self_term)
+    # aggregation output
+    yh = qgnn.dequantize(Y, cc=sx, rs=lox, row_i=deg)
+    ref = Ad @ Xh
+    assert np.allclose(yh, ref, rtol=0, atol=1e-6 * np.abs(ref).max())
+    # update output: Yq stands for y ~ rq_lo + Yq / rq_inv in accumulator units
+    sl = sx / float(rq_inv)
+    l0 = sx * rq_lo + lox * deg               # per-row offset of the left operand
+    Yqh = l0[:, None] + sl * Yq.astype(np.float64)
+    ref = Yqh @ Wh
+    zh = qgnn.dequantize(Z, cc=sl * sw, rs=sl * low, row_i=Yq.sum(axis=1, dtype=np.int64),
+                         l0a=sx * rq_lo, l0b=lox, row_l=deg,
+                         ck=low * d, cs=sw, col_i=Wq.sum(axis=0, dtype=np.int64))
+    assert np.allclose(zh, ref, rtol=0, atol=2e-6 * np.abs(ref).max())
+    # ReLU on the real value
+    zr = qgnn.dequantize(Z, cc=sl * sw, rs=sl * low, row_i=Yq.sum(axis=1, dtype=np.int64),
+                         l0a=sx * rq_lo, l0b=lox, row_l=deg,
+                         ck=low * d, cs=sw, col_i=Wq.sum(axis=0, dtype=np.int64), relu=True)
+    assert (zr == np.maximum(zh, 0)).all()
+
+
+# ------------------------------------------------------------------ packing
+def test_pack_hand_vector_and_sizes():
+    g = load_golden("quantize_2bit.txt")
+    v = np.zeros((1, 64), dtype=np.uint32)
+    v[0, g["ones_at"]] = 1
+    assert bp.pack(v, 1, bp.LEFT)[0, 0].tolist() == g["words"]
+    assert bp.pack(v.T, 1, bp.RIGHT)[0, :, 0].tolist() == g["words"]
+    q = np.zeros((13, 70), dtype=np.uint32)
+    assert bp.pack(q, 3, bp.LEFT).shape == (3, 13, 3)      # ceil(70/32) words per row
+    assert bp.pack(q, 3, bp.RIGHT).shape == (3, 1, 70)     # ceil(13/32) word rows
+
+
+@pytest.mark.parametrize("layout", [bp.LEFT, bp.RIGHT])
+@pytest.mark.parametrize("bits", [1, 3, 8, 17, 32])
+def test_pack_roundtrip_and_zero_padding(layout, bits):
+    rng = np.random.default_rng([12, layout, bits])
+    q = rng.integers(0, 2 ** bits, size=(45, 77), dtype=np.uint64).astype(np.uint32)
+    w = bp.pack(q, bits, layout)
+    assert (bp.unpack(w, 45, 77, layout) == q).all()
+    if layout == bp.LEFT:      # bits past column 77 in the last word are zero
+        assert (w[:, :, -1] >> np.uint32(77 - 64) == 0).all()
+    else:                      # bits past row 45 in the last word row are zero
+        assert (w[:, -1, :] >> np.uint32(45 - 32) == 0).all()
+    # plane i really is bit i
+    plane0 = bp.unpack(w[:1], 45, 77, layout)
+    assert (plane0 == (q & 1)).all()
+
+
+def test_packed_popcount_product_equals_matmul():
+    """AND + popcount on the packed words reproduces the integer product."""
+    rng = np.random.default_rng(13)
+    n, k, m, lb, rb = 10, 75, 6, 2, 3
+    L = rng.integers(0, 2 ** lb, size=(n, k)).astype(np.uint32)
+    R = rng.integers(0, 2 ** rb, size=(k, m)).astype(np.uint32)
+    lw = bp.pack(L, lb, bp.LEFT)
+    rw = bp.pack(R, rb, bp.RIGHT)
+    out = np.zeros((n, m), dtype=np.int64)
+    for i in range(lb):
+        for j in range(rb):
+            for r in range(n):
+                for c in range(m):
+                    cnt = sum(bin(int(lw[i, r, w]) & int(rw[j, w, c])).count("1")
+                              for w in range(lw.shape[2]))
+                    out[r, c] += cnt << (i + j)
+    assert (out == L.astype(np.int64) @ R.astype(np.int64)).all()
+    assert (qgnn.matmul_mod32(L, R) == out).all()
+
+
+# ----------------------------------------------------------------- tile map
+def test_tile_map_brute_force_and_block_structure():
+    from workloads import make_workload
+    w = make_workload(1)
+    A = w.graph.dense()
+    lists, deg = qgnn.tile_map(A, 8, 128)
+    assert (deg == w.graph.degrees()).all()
+    for tr, nz in enumerate(lists):
+        for tc in range(2):
+            want = bool(A[tr * 8:(tr + 1) * 8, tc * 128:(tc + 1) * 128].any())
+            assert (tc in nz) == want
+    # 64-node blocks aligned to 16 x 64 tiles: non-zero tiles lie on the diagonal
+    lists, _ = qgnn.tile_map(A, 16, 64)
+    for tr, nz in enumerate(lists):
+        assert nz == [tr * 16 // 64]
+    # the product does not depend on skipping zero tiles
+    X = w.X
+    Y = qgnn.aggregate(A, X)
+    Yt = np.zeros_like(Y, dtype=np.int64)
+    for tr, nz in enumerate(lists):
+        for tc in nz:
+            Yt[tr * 16:(tr + 1) * 16] += A[tr * 16:(tr + 1) * 16, tc * 64:(tc + 1) * 64].astype(np.int64) \
+                @ X[tc * 64:(tc + 1) * 64].astype(np.int64)
+    assert (Yt == Y).all()
+
+
+# -------------------------------------------------------------- multi-layer
+def test_forward_chain_is_layerwise_consistent():
+    from workloads import make_workload
+    w = make_workload(4, n_blocks=1)
+    A = w.graph.scipy_csr()
+    xr = (float(w.X.min()), float(w.X.max()))
+    wr = [(float(W.min()), float(W.max())) for W in w.W]
+    trace, rqs = qgnn.forward(A, w.X, xr, w.W, wr, w.s, w.t, self_term=True)
+    assert len(trace) == 5
+    for l, tr in enumerate(trace):
+        Y = qgnn.aggregate(A, tr["Xq"], self_term=True)
+        assert (Y == tr["Y"]).all()
+        assert int(tr["Yq"].max()) == 2 ** w.s - 1     # calibrated range is used fully
+        if l + 1 < len(trace):
+            assert (trace[l + 1]["Xq"] == tr["Xq_next"]).all()
+    # giving the calibrated ranges back reproduces the same integers
+    trace2, _ = qgnn.forward(A, w.X, xr, w.W, wr, w.s, w.t, True, rqs=rqs)
+    assert all((a["Z"] == b["Z"]).all() for a, b in zip(trace, trace2))
