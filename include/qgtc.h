@@ -1,0 +1,256 @@
+/*
+ * qgtc.h - C ABI of the any-bitwidth quantized GNN layer for AMD MI355X (gfx950).
+ *
+ * The layer follows QGTC (arXiv 2111.09547): neighbour aggregation Y = A.X of a
+ * binary adjacency with s-bit node embeddings, then the node update Y.W with
+ * t-bit weights (Algorithm 1, Section 3.2).  Both products are sums of 1-bit
+ * products, sum_i sum_j 2^(i+j) popcnt(plane_i & plane_j) (Section 3.1,
+ * Eq. 3-7), taken over bit planes packed into 32-bit words (Section 4.2).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or keeps them.  Descriptor structs (qgtc_bits,
+ *     qgtc_tile_map, qgtc_epilogue, qgtc_quant) are HOST structs read during
+ *     the call only.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; no entry point synchronizes.
+ *   - Arguments are validated on the host before anything is launched; a
+ *     failed call launches nothing and returns a status other than QGTC_OK.
+ *   - Integer results are defined modulo 2^32 (32-bit accumulators,
+ *     Sections 2.3 and 3.2).
+ */
+#ifndef QGTC_H
+#define QGTC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  QGTC_OK = 0,
+  QGTC_ERR_NULL = 1,        /* a required pointer is NULL */
+  QGTC_ERR_SHAPE = 2,       /* shapes of the operands do not fit each other */
+  QGTC_ERR_BITWIDTH = 3,    /* nbits outside [1, 32] (adjacency: != 1) */
+  QGTC_ERR_ALIGN = 4,       /* pointer or leading dimension not aligned as required */
+  QGTC_ERR_LAYOUT = 5,      /* operand packed in the wrong layout */
+  QGTC_ERR_WORKSPACE = 6,   /* workspace too small */
+  QGTC_ERR_UNSUPPORTED = 7, /* valid request this build has no kernel for */
+  QGTC_ERR_HIP = 8          /* the HIP runtime reported an error on launch */
+} qgtc_status;
+
+const char* qgtc_status_string(qgtc_status s);
+
+/* ---------------------------------------------------------------------------
+ * Packed bit planes ("3D-stacked bit compression", Section 4.2 and Figure 4).
+ *
+ * An nbits-bit unsigned matrix is stored as nbits stacked 1-bit matrices; 32
+ * consecutive entries along the contraction dimension K share one 32-bit word,
+ * entry 32*w + b in bit b of word w (least significant bit = lowest index),
+ * zero fill past the end of the matrix.
+ *
+ *   QGTC_LEFT  (left operands A, Y; rows x K):  word(p, r, w) =
+ *              data[p*plane_stride_words + r*ld_words + w],  w < ceil(cols/32)
+ *   QGTC_RIGHT (right operands X, W; K x cols): word(p, w, c) =
+ *              data[p*plane_stride_words + w*ld_words + c],  w < ceil(rows/32)
+ *
+ * LEFT buffers: ld_words is a multiple of 4 and every word in [ceil(cols/32),
+ * ld_words) of a row is zero (the paper pads K to 128 bits for its 8x128
+ * tiles; the kernels here read adjacency rows 128 bits at a time as well).
+ * data must be 16-byte aligned.
+ *
+ * block_rows (LEFT, adjacency only): 0 for an ordinary rows x cols matrix.  A
+ * positive value describes a block-diagonal matrix of batched subgraphs
+ * (Section 4.1) stored without its all-zero off-diagonal blocks: row r keeps
+ * only the cols == block_rows entries of its own diagonal block, entry j
+ * standing for column (r / block_rows) * block_rows + j.  block_rows must be a
+ * multiple of 32.
+ * ------------------------------------------------------------------------- */
+enum { QGTC_LEFT = 0, QGTC_RIGHT = 1 };
+
+typedef struct qgtc_bits {
+  uint32_t* data;
+  int32_t nbits;
+  int32_t rows;
+  int32_t cols;
+  int32_t layout;
+  int32_t block_rows;
+  int32_t reserved;
+  int64_t ld_words;
+  int64_t plane_stride_words;
+} qgtc_bits;
+
+/* Fills ld_words / plane_stride_words (and the scalar fields) with the default
+ * strides and returns the number of 32-bit words the buffer needs:
+ *   LEFT : ld = 4*ceil(cols/128), plane stride = rows*ld
+ *   RIGHT: ld = cols,             plane stride = ceil(rows/32)*ld
+ * d->data is left untouched.  Returns 0 on invalid arguments. */
+size_t qgtc_describe(qgtc_bits* d, int32_t rows, int32_t cols, int32_t nbits,
+                     int32_t layout, int32_t block_rows);
+
+/* ---------------------------------------------------------------------------
+ * Eq. (2): code = floor((x - lo) / scale), scale = (hi - lo) / 2^nbits.
+ * The result is clamped to [0, 2^nbits - 1] (x = hi would need nbits+1 bits).
+ * Arithmetic: lo is rounded to fp32; inv_scale = fp32(2^nbits / (hi - lo)) is
+ * formed in double; (x - lo) and the multiplication are single fp32 operations.
+ * ------------------------------------------------------------------------- */
+typedef struct qgtc_quant {
+  double lo;
+  double hi;
+  int32_t nbits;
+} qgtc_quant;
+
+enum { QGTC_SRC_F32 = 0, QGTC_SRC_U8 = 1, QGTC_SRC_I32 = 2 };
+
+/* Quantize (fp32 source, q != NULL) or take integers as they are (u8 / i32
+ * source, q == NULL; bits above dst->nbits are dropped), decompose into bit
+ * planes and pack into dst ("Tensor.to_bit", Sections 4.2 and 5).
+ * src: device, row-major rows x cols with leading dimension ld_src (elements).
+ * dst: descriptor filled by the caller (qgtc_describe) with rows/cols equal to
+ * the arguments; every word of the packed matrix, padding included, is written. */
+qgtc_status qgtc_pack_bits(const void* src, int32_t src_dtype, int32_t rows,
+                           int32_t cols, int64_t ld_src, const qgtc_quant* q,
+                           const qgtc_bits* dst, void* stream);
+
+/* Decode packed planes back to one uint32 per entry ("Tensor.to_val",
+ * Section 5).  dst: device, row-major rows x cols, leading dimension ld_dst. */
+qgtc_status qgtc_unpack_bits(const qgtc_bits* src, uint32_t* dst, int64_t ld_dst,
+                             void* stream);
+
+/* Value sums of a packed matrix, sum_p 2^p * popcnt, modulo 2^32:
+ * per row of a LEFT operand (out: rows entries) or per column of a RIGHT
+ * operand (out: cols entries).  They feed the dequantizing epilogue below. */
+qgtc_status qgtc_row_sums(const qgtc_bits* m, int32_t* out, void* stream);
+qgtc_status qgtc_col_sums(const qgtc_bits* m, int32_t* out, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Zero-tile map (zero-tile jumping, Section 4.3).  The paper tests every 8x128
+ * tile of A inside the product kernel; here the test is done once per
+ * adjacency (A is reused by every layer, end of Section 3.2) and kept as, per
+ * row of tiles, the ascending list of tile columns that hold at least one edge.
+ *   row_cnt[tr]                      number of non-zero tiles in tile row tr
+ *   col_idx[tr*n_tile_cols + i]      their tile-column indices, i < row_cnt[tr]
+ *   nnz_tiles[0]                     total number of non-zero tiles
+ *   deg[r]                           popcount of row r of A (node degree)
+ * Any tile shape with tile_rows in {8, 16, 32, 64} and tile_kbits in {32, 64,
+ * 128, 256, 512} can be built (8 x 128 reproduces the statistic of the paper's
+ * Figure 8); qgtc_aggregate takes tile_rows == 16 and tile_kbits in
+ * {32, 64, 128}.
+ * ------------------------------------------------------------------------- */
+typedef struct qgtc_tile_map {
+  int32_t tile_rows;
+  int32_t tile_kbits;
+  int32_t n_tile_rows;  /* ceil(A.rows / tile_rows) */
+  int32_t n_tile_cols;  /* ceil(A.cols / tile_kbits) */
+  int32_t* row_cnt;     /* [n_tile_rows] */
+  int32_t* col_idx;     /* [n_tile_rows * n_tile_cols] */
+  int32_t* nnz_tiles;   /* [1] */
+  int32_t* deg;         /* [A.rows] */
+} qgtc_tile_map;
+
+/* Bytes of one device buffer large enough for all four arrays of a map. */
+size_t qgtc_tile_map_bytes(int32_t rows, int32_t kbits, int32_t tile_rows,
+                           int32_t tile_kbits);
+/* Sets the scalar fields and points the four arrays into `buffer` (device,
+ * 16-byte aligned, qgtc_tile_map_bytes long).  Host-only; launches nothing. */
+qgtc_status qgtc_tile_map_carve(qgtc_tile_map* map, void* buffer, int32_t rows,
+                                int32_t kbits, int32_t tile_rows,
+                                int32_t tile_kbits);
+/* Scans the packed adjacency A (LEFT, 1 bit) and fills the map. */
+qgtc_status qgtc_build_tile_map(const qgtc_bits* A, const qgtc_tile_map* map,
+                                void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Epilogue fused into the product kernels (inter-layer kernel fusion,
+ * Section 4.5).  C is the 32-bit accumulator of entry (i, j), read as signed.
+ *
+ *   QGTC_OUT_I32  ("bitMM2Int", Section 5): out[i*ld_out + j] = C
+ *                 (max(C, 0) with relu).  out: int32_t*.
+ *   QGTC_OUT_F32  (last layer, Section 4.5): the real product of the two
+ *                 dequantized operands.  With left operand l0[i] + sl*L and
+ *                 right operand r0 + sr*R,
+ *                   t1  = cc*C + rs*row_i[i]
+ *                   t2  = (l0a + l0b*row_l[i]) * (ck + cs*col_i[j])
+ *                   out = fp32(t1 + t2)           (max(., 0) first with relu)
+ *                 evaluated in fp64 in exactly this order, where the caller
+ *                 sets cc = sl*sr, rs = sl*r0, ck = r0*K, cs = sr, row_i =
+ *                 row sums of L, col_i = column sums of R and l0[i] = l0a +
+ *                 l0b*row_l[i].  NULL vectors read as zeros.  out: float*.
+ *   QGTC_OUT_BITS ("bitMM2Bit", Section 5): requantize to rq_nbits bits and
+ *                 emit packed planes for the next product:
+ *                   d = C - rq_lo (64-bit; C -> max(C, 0) first with relu)
+ *                   code = min(floor(fp32(max(d, 0)) * rq_inv_scale), 2^rq_nbits - 1)
+ *                 out: const qgtc_bits* describing the destination
+ *                 (qgtc_aggregate: LEFT; qgtc_update: RIGHT; nbits == rq_nbits).
+ *
+ * self_term (qgtc_aggregate only): adds X[i, j] itself to C, i.e. the GIN
+ * aggregation (1 + eps).X + A.X with eps = 0; needs a square adjacency.
+ * ------------------------------------------------------------------------- */
+enum { QGTC_OUT_I32 = 0, QGTC_OUT_F32 = 1, QGTC_OUT_BITS = 2 };
+
+typedef struct qgtc_epilogue {
+  int32_t mode;
+  int32_t relu;
+  int32_t self_term;
+  int32_t rq_nbits;
+  int32_t rq_lo;
+  float rq_inv_scale;
+  double cc, rs, l0a, l0b, ck, cs;
+  const int32_t* row_i; /* [rows] or NULL */
+  const int32_t* row_l; /* [rows] or NULL */
+  const int32_t* col_i; /* [cols] or NULL */
+} qgtc_epilogue;
+
+/* Neighbour aggregation C = A.X (first half of Algorithm 1; zero-tile jumping
+ * and non-zero tile reuse, Sections 4.3 and 4.4).
+ * A: LEFT, 1 bit, rows x K (or block-diagonal, see block_rows).
+ * map: tile map of A, or NULL to visit every tile.
+ * X: RIGHT, s bits, K x cols.  X must span less than 4 GiB.
+ * out / ld_out: per epilogue mode (ld_out in elements; ignored for BITS). */
+qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* map,
+                           const qgtc_bits* X, const qgtc_epilogue* ep,
+                           void* out, int64_t ld_out, void* stream);
+
+/* Node update C = Y.W (second half of Algorithm 1).
+ * Y: LEFT, s bits, rows x K.  W: RIGHT, t bits, K x cols. */
+qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W,
+                        const qgtc_epilogue* ep, void* out, int64_t ld_out,
+                        void* stream);
+
+/* One layer: aggregate with agg_ep (must be QGTC_OUT_BITS) into packed planes
+ * held in `workspace`, then update with upd_ep into out.
+ * workspace: device, 16-byte aligned, at least qgtc_layer_workspace_bytes. */
+size_t qgtc_layer_workspace_bytes(int32_t rows, int32_t cols, int32_t nbits);
+qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map,
+                       const qgtc_bits* X, const qgtc_bits* W,
+                       const qgtc_epilogue* agg_ep, const qgtc_epilogue* upd_ep,
+                       void* workspace, size_t workspace_bytes, void* out,
+                       int64_t ld_out, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Optional per-kernel timing.  While enabled, every kernel launch is bracketed
+ * by HIP events recorded on the launch stream.  qgtc_prof_read synchronizes
+ * with the recorded events and returns, for one kernel kind, the summed
+ * duration in milliseconds and the number of launches since the last reset.
+ * ------------------------------------------------------------------------- */
+enum {
+  QGTC_KERNEL_PACK = 0,
+  QGTC_KERNEL_TILE_MAP = 1,
+  QGTC_KERNEL_AGGREGATE = 2,
+  QGTC_KERNEL_UPDATE = 3,
+  QGTC_KERNEL_SUMS = 4,
+  QGTC_KERNEL_KINDS = 5
+};
+qgtc_status qgtc_prof_enable(int32_t on);
+qgtc_status qgtc_prof_reset(void);
+qgtc_status qgtc_prof_read(int32_t kind, double* total_ms, int64_t* launches);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t qgtc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QGTC_H */

@@ -1,0 +1,255 @@
+// Quantize + bit-decompose + pack ("Tensor.to_bit"), decode ("Tensor.to_val")
+// and the value sums of packed operands.  Eq. (2) and the 3D-stacked bit
+// compression of Section 4.2 of the paper, for gfx950.  All of these are
+// streaming kernels bound by HBM bandwidth.
+#include "qgtc_internal.h"
+
+namespace qgtc {
+namespace {
+
+struct PackParams {
+  const void* src;
+  int64_t ld_src;
+  int32_t rows, cols;
+  int32_t nbits;
+  uint32_t* dst;
+  int64_t ld, ps;       // words
+  float lo, inv;        // Eq. (2), fp32 sources only
+  uint32_t qmax;
+  float qmaxf;
+};
+
+template <int SRC>
+__device__ __forceinline__ uint32_t fetch(const PackParams& p, int64_t idx) {
+  if constexpr (SRC == QGTC_SRC_F32) {
+    return quantize_f32(reinterpret_cast<const float*>(p.src)[idx], p.lo, p.inv, p.qmax, p.qmaxf);
+  } else if constexpr (SRC == QGTC_SRC_U8) {
+    return (uint32_t) reinterpret_cast<const uint8_t*>(p.src)[idx] & p.qmax;
+  } else {
+    return reinterpret_cast<const uint32_t*>(p.src)[idx] & p.qmax;
+  }
+}
+
+// RIGHT layout: 32 consecutive ROWS of one column share a word.
+// thread <-> (column c, word row w); the 32 loads of a thread are each
+// coalesced across the threads of the wave (consecutive columns).
+template <int SRC>
+__global__ __launch_bounds__(256) void pack_right_kernel(const PackParams p) {
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int w = blockIdx.y * 4 + (threadIdx.x >> 6);
+  const int n_wr = (p.rows + 31) >> 5;
+  if (c >= p.cols || w >= n_wr) return;
+  for (int p0 = 0; p0 < p.nbits; p0 += 8) {
+    uint32_t out[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = 0u;
+#pragma unroll 8
+    for (int b = 0; b < 32; ++b) {
+      const int r = w * 32 + b;
+      uint32_t q = 0u;
+      if (r < p.rows) q = fetch<SRC>(p, (int64_t)r * p.ld_src + c) >> p0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) out[i] |= ((q >> i) & 1u) << b;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (p0 + i < p.nbits) p.dst[(int64_t)(p0 + i) * p.ps + (int64_t)w * p.ld + c] = out[i];
+  }
+}
+
+// LEFT layout: 32 consecutive COLUMNS of one row share a word.
+// One wave per row; lane <-> column inside a 64-column chunk, so the loads are
+// coalesced and a ballot over the lanes yields two finished words.  The words
+// of 32 chunks are gathered lane by lane and stored 256 bytes at a time.
+// Every word up to ld (the zero padding included) is written.
+template <int SRC>
+__global__ __launch_bounds__(256) void pack_left_kernel(const PackParams p) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= p.rows) return;                       // whole wave
+  const int n_words = (int)p.ld;
+  for (int pl = 0; pl < p.nbits; ++pl) {
+    uint32_t* drow = p.dst + (int64_t)pl * p.ps + (int64_t)r * p.ld;
+    for (int w0 = 0; w0 < n_words; w0 += 64) {   // 64 words = 2048 columns per pass
+      uint32_t mine = 0u;
+      const int n_chunks = min(32, (n_words - w0 + 1) >> 1);
+      for (int ch = 0; ch < n_chunks; ++ch) {
+        const int c = (w0 + 2 * ch) * 32 + lane;
+        uint32_t bit = 0u;
+        if (c < p.cols) bit = (fetch<SRC>(p, (int64_t)r * p.ld_src + c) >> pl) & 1u;
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(bit != 0u);
+        if (lane == 2 * ch) mine = (uint32_t)m;
+        if (lane == 2 * ch + 1) mine = (uint32_t)(m >> 32);
+      }
+      if (w0 + lane < n_words) drow[w0 + lane] = mine;
+    }
+  }
+}
+
+struct UnpackParams {
+  const uint32_t* src;
+  int64_t ld, ps;
+  int32_t rows, cols, nbits, layout;
+  uint32_t* dst;
+  int64_t ld_dst;
+};
+
+__global__ __launch_bounds__(256) void unpack_kernel(const UnpackParams p) {
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int r = blockIdx.y * 4 + (threadIdx.x >> 6);
+  if (c >= p.cols || r >= p.rows) return;
+  uint32_t v = 0u;
+  for (int i = 0; i < p.nbits; ++i) {
+    uint32_t word, bit;
+    if (p.layout == QGTC_LEFT) {
+      word = p.src[(int64_t)i * p.ps + (int64_t)r * p.ld + (c >> 5)];
+      bit = c & 31;
+    } else {
+      word = p.src[(int64_t)i * p.ps + (int64_t)(r >> 5) * p.ld + c];
+      bit = r & 31;
+    }
+    v |= ((word >> bit) & 1u) << i;
+  }
+  p.dst[(int64_t)r * p.ld_dst + c] = v;
+}
+
+// sum_p 2^p popcount(row r of plane p): one wave per row, lanes stride over words.
+__global__ __launch_bounds__(256) void row_sums_kernel(const UnpackParams p, int32_t* out) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= p.rows) return;
+  const int n_words = (p.cols + 31) >> 5;
+  uint32_t acc = 0u;
+  for (int i = 0; i < p.nbits; ++i) {
+    const uint32_t* row = p.src + (int64_t)i * p.ps + (int64_t)r * p.ld;
+    uint32_t cnt = 0u;
+    for (int w = lane; w < n_words; w += 64) cnt += __builtin_popcount(row[w]);
+    acc += cnt << i;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  if (lane == 0) out[r] = (int32_t)acc;
+}
+
+// sum_p 2^p popcount(column c of plane p): thread per column.
+__global__ __launch_bounds__(256) void col_sums_kernel(const UnpackParams p, int32_t* out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= p.cols) return;
+  const int n_wr = (p.rows + 31) >> 5;
+  uint32_t acc = 0u;
+  for (int i = 0; i < p.nbits; ++i) {
+    uint32_t cnt = 0u;
+    for (int w = 0; w < n_wr; ++w) cnt += __builtin_popcount(p.src[(int64_t)i * p.ps + (int64_t)w * p.ld + c]);
+    acc += cnt << i;
+  }
+  out[c] = (int32_t)acc;
+}
+
+template <int SRC>
+qgtc_status launch_pack(const PackParams& p, int layout, hipStream_t s) {
+  if (layout == QGTC_RIGHT) {
+    dim3 grid((unsigned)cdiv(p.cols, 64), (unsigned)cdiv(cdiv(p.rows, 32), 4));
+    hipLaunchKernelGGL((pack_right_kernel<SRC>), grid, dim3(256), 0, s, p);
+  } else {
+    hipLaunchKernelGGL((pack_left_kernel<SRC>), dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p);
+  }
+  return launch_status();
+}
+
+UnpackParams unpack_params(const qgtc_bits* m) {
+  UnpackParams p{};
+  p.src = m->data;
+  p.ld = m->ld_words;
+  p.ps = m->plane_stride_words;
+  p.rows = m->rows;
+  p.cols = m->cols;
+  p.nbits = m->nbits;
+  p.layout = m->layout;
+  return p;
+}
+
+}  // namespace
+}  // namespace qgtc
+
+using namespace qgtc;
+
+extern "C" qgtc_status qgtc_pack_bits(const void* src, int32_t src_dtype, int32_t rows, int32_t cols,
+                                      int64_t ld_src, const qgtc_quant* q, const qgtc_bits* dst,
+                                      void* stream) {
+  if (!src || !dst) return QGTC_ERR_NULL;
+  qgtc_status st = check_bits(dst, dst->layout);
+  if (st != QGTC_OK) return st;
+  if (rows != dst->rows || cols != dst->cols || ld_src < cols) return QGTC_ERR_SHAPE;
+  if (src_dtype != QGTC_SRC_F32 && src_dtype != QGTC_SRC_U8 && src_dtype != QGTC_SRC_I32)
+    return QGTC_ERR_UNSUPPORTED;
+  if (src_dtype == QGTC_SRC_F32) {
+    if (!q) return QGTC_ERR_NULL;
+    if (q->nbits != dst->nbits) return QGTC_ERR_BITWIDTH;
+    if (!(q->hi > q->lo)) return QGTC_ERR_SHAPE;
+  }
+  if (dst->layout == QGTC_RIGHT && dst->ld_words < cols) return QGTC_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return QGTC_OK;
+
+  PackParams p{};
+  p.src = src;
+  p.ld_src = ld_src;
+  p.rows = rows;
+  p.cols = cols;
+  p.nbits = dst->nbits;
+  p.dst = dst->data;
+  p.ld = dst->ld_words;
+  p.ps = dst->plane_stride_words;
+  p.qmax = dst->nbits >= 32 ? 0xffffffffu : ((1u << dst->nbits) - 1u);
+  p.qmaxf = (float)p.qmax;
+  if (src_dtype == QGTC_SRC_F32) {
+    p.lo = (float)q->lo;
+    p.inv = (float)((double)(1ull << q->nbits) / (q->hi - q->lo));
+  }
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  ProfScope prof(QGTC_KERNEL_PACK, s);
+  switch (src_dtype) {
+    case QGTC_SRC_F32: return launch_pack<QGTC_SRC_F32>(p, dst->layout, s);
+    case QGTC_SRC_U8: return launch_pack<QGTC_SRC_U8>(p, dst->layout, s);
+    default: return launch_pack<QGTC_SRC_I32>(p, dst->layout, s);
+  }
+}
+
+extern "C" qgtc_status qgtc_unpack_bits(const qgtc_bits* src, uint32_t* dst, int64_t ld_dst, void* stream) {
+  if (!src || !dst) return QGTC_ERR_NULL;
+  qgtc_status st = check_bits(src, src->layout);
+  if (st != QGTC_OK) return st;
+  if (ld_dst < src->cols) return QGTC_ERR_SHAPE;
+  if (src->rows == 0 || src->cols == 0) return QGTC_OK;
+  UnpackParams p = unpack_params(src);
+  p.dst = dst;
+  p.ld_dst = ld_dst;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  ProfScope prof(QGTC_KERNEL_PACK, s);
+  dim3 grid((unsigned)cdiv(p.cols, 64), (unsigned)cdiv(p.rows, 4));
+  hipLaunchKernelGGL(unpack_kernel, grid, dim3(256), 0, s, p);
+  return launch_status();
+}
+
+extern "C" qgtc_status qgtc_row_sums(const qgtc_bits* m, int32_t* out, void* stream) {
+  if (!m || !out) return QGTC_ERR_NULL;
+  qgtc_status st = check_bits(m, QGTC_LEFT);
+  if (st != QGTC_OK) return st;
+  if (m->rows == 0) return QGTC_OK;
+  UnpackParams p = unpack_params(m);
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  ProfScope prof(QGTC_KERNEL_SUMS, s);
+  hipLaunchKernelGGL(row_sums_kernel, dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p, out);
+  return launch_status();
+}
+
+extern "C" qgtc_status qgtc_col_sums(const qgtc_bits* m, int32_t* out, void* stream) {
+  if (!m || !out) return QGTC_ERR_NULL;
+  qgtc_status st = check_bits(m, QGTC_RIGHT);
+  if (st != QGTC_OK) return st;
+  if (m->cols == 0) return QGTC_OK;
+  UnpackParams p = unpack_params(m);
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  ProfScope prof(QGTC_KERNEL_SUMS, s);
+  hipLaunchKernelGGL(col_sums_kernel, dim3((unsigned)cdiv(p.cols, 256)), dim3(256), 0, s, p, out);
+  return launch_status();
+}

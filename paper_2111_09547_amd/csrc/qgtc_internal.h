@@ -1,0 +1,111 @@
+// Shared host/device helpers of the library (not part of the public ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qgtc.h"
+
+namespace qgtc {
+
+constexpr int kWave = 64;
+
+// ---- host side -------------------------------------------------------------
+inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// Common checks on a packed-planes descriptor.
+qgtc_status check_bits(const qgtc_bits* b, int want_layout);
+// Stricter checks for an adjacency operand (1 bit, LEFT, 128-bit row padding).
+qgtc_status check_adjacency(const qgtc_bits* A);
+// Number of 32-bit words spanned by the descriptor (last addressed word + 1).
+int64_t span_words(const qgtc_bits* b);
+
+// Status of the launch that was just issued.
+inline qgtc_status launch_status() {
+  return hipGetLastError() == hipSuccess ? QGTC_OK : QGTC_ERR_HIP;
+}
+
+// Brackets the launches of one entry point with HIP events while profiling is on.
+class ProfScope {
+ public:
+  ProfScope(int kind, hipStream_t stream);
+  ~ProfScope();
+
+ private:
+  int slot_;
+  hipStream_t stream_;
+};
+
+// Grid size padded to a multiple of the 8 XCDs, see xcd_remap().
+inline unsigned xcd_grid(unsigned nblocks) { return (nblocks + 7u) / 8u * 8u; }
+
+// Epilogue parameters as the kernels take them (device-visible copy).
+struct EpiParams {
+  int32_t mode, relu, self_term, rq_nbits;
+  int32_t rq_lo;
+  float rq_inv_scale;
+  double cc, rs, l0a, l0b, ck, cs;
+  const int32_t* row_i;
+  const int32_t* row_l;
+  const int32_t* col_i;
+  void* out;           // int32_t* / float* / planes base (uint32_t*)
+  int64_t ld_out;      // elements (I32/F32) or words (BITS)
+  int64_t ps_out;      // BITS: plane stride in words
+};
+
+qgtc_status make_epilogue(const qgtc_epilogue* ep, void* out, int64_t ld_out,
+                          int rows, int cols, int bits_layout, bool allow_self,
+                          EpiParams* p);
+
+// ---- device side -------------------------------------------------------------
+#if defined(__HIPCC__)
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  This
+// maps the hardware block id to a logical id such that consecutive logical ids
+// run on the same XCD, so neighbouring tiles share that XCD's L2.  The grid
+// must be xcd_grid(nblocks) wide; ids >= nblocks are to be dropped.
+__device__ __forceinline__ unsigned xcd_remap(unsigned bid, unsigned grid) {
+  return (bid & 7u) * (grid >> 3) + (bid >> 3);
+}
+
+// Eq. (2) with the clamp; see qgtc_quant in qgtc.h.
+__device__ __forceinline__ uint32_t quantize_f32(float x, float lo, float inv,
+                                                 uint32_t qmax, float qmaxf) {
+  const float d = x - lo;
+  const float t = floorf(d * inv);
+  if (!(t > 0.0f)) return 0u;
+  if (t >= qmaxf) return qmax;
+  return (uint32_t)t;
+}
+
+// Requantization of a 32-bit accumulator; see QGTC_OUT_BITS in qgtc.h.
+__device__ __forceinline__ uint32_t requantize_i32(uint32_t c_u32, const EpiParams& e,
+                                                   uint32_t qmax, float qmaxf) {
+  int32_t c = (int32_t)c_u32;
+  if (e.relu && c < 0) c = 0;
+  const int64_t d = (int64_t)c - (int64_t)e.rq_lo;
+  const uint32_t du = d > 0 ? (uint32_t)d : 0u;   // d < 2^32
+  const float f = (float)du;                      // round to nearest even
+  const float t = floorf(f * e.rq_inv_scale);
+  if (t >= qmaxf) return qmax;
+  return (uint32_t)t;
+}
+
+// fp32 output of the dequantizing epilogue; see QGTC_OUT_F32 in qgtc.h.
+__device__ __forceinline__ float dequantize_f64(uint32_t c_u32, int row, int col,
+                                                const EpiParams& e) {
+  const double c = (double)(int32_t)c_u32;
+  const double ri = e.row_i ? (double)e.row_i[row] : 0.0;
+  const double rl = e.row_l ? (double)e.row_l[row] : 0.0;
+  const double ci = e.col_i ? (double)e.col_i[col] : 0.0;
+  const double t1 = e.cc * c + e.rs * ri;
+  const double l0 = e.l0a + e.l0b * rl;
+  const double t2 = l0 * (e.ck + e.cs * ci);
+  double v = t1 + t2;
+  if (e.relu && v < 0.0) v = 0.0;
+  return (float)v;
+}
+
+#endif  // __HIPCC__
+
+}  // namespace qgtc

@@ -1,0 +1,160 @@
+// Zero-tile map of a packed adjacency (zero-tile jumping, Section 4.3 of the
+// paper).  The paper ORs the words of each 8x128 tile inside the product kernel
+// and skips the tile when the result is zero; the adjacency is the same for all
+// layers, so here the test runs once and leaves, per row of tiles, the list of
+// tile columns that hold an edge.  HBM-bound: A is read once for the map and
+// once for the degrees.
+#include "qgtc_internal.h"
+
+namespace qgtc {
+namespace {
+
+struct MapParams {
+  const uint32_t* A;
+  int64_t lda;
+  int32_t rows;
+  int32_t n_words;        // data words per row, ceil(cols/32)
+  int32_t tile_rows, tile_words;
+  int32_t n_tile_rows, n_tile_cols;
+  int32_t* row_cnt;
+  int32_t* col_idx;
+  int32_t* nnz;
+  int32_t* deg;
+};
+
+// One wave per tile row.  lane <-> tile column inside a group of 64; the OR over
+// the tile's words decides, a ballot and a prefix count over the lanes compact
+// the surviving tile columns in ascending order.
+__global__ __launch_bounds__(256) void tile_list_kernel(const MapParams p) {
+  const int lane = threadIdx.x & 63;
+  const int tr = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tr >= p.n_tile_rows) return;               // whole wave
+  const int r0 = tr * p.tile_rows;
+  const int r1 = min(r0 + p.tile_rows, p.rows);
+  int32_t* list = p.col_idx + (int64_t)tr * p.n_tile_cols;
+  int count = 0;
+  for (int tc0 = 0; tc0 < p.n_tile_cols; tc0 += 64) {
+    const int tc = tc0 + lane;
+    uint32_t any = 0u;
+    if (tc < p.n_tile_cols) {
+      const int w0 = tc * p.tile_words;
+      const int w1 = min(w0 + p.tile_words, p.n_words);
+      for (int r = r0; r < r1; ++r) {
+        const uint32_t* row = p.A + (int64_t)r * p.lda;
+        for (int w = w0; w < w1; ++w) any |= row[w];
+      }
+    }
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(any != 0u);
+    const int before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    if (any != 0u) list[count + before] = tc;
+    count += __builtin_popcountll(m);
+  }
+  if (lane == 0) p.row_cnt[tr] = count;
+}
+
+// Total number of non-zero tiles: one workgroup, no atomics.
+__global__ __launch_bounds__(256) void tile_total_kernel(const MapParams p) {
+  __shared__ int part[256];
+  int acc = 0;
+  for (int i = threadIdx.x; i < p.n_tile_rows; i += 256) acc += p.row_cnt[i];
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) p.nnz[0] = part[0];
+}
+
+// deg[r] = popcount of row r: one wave per row.
+__global__ __launch_bounds__(256) void degree_kernel(const MapParams p) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= p.rows) return;
+  const uint32_t* row = p.A + (int64_t)r * p.lda;
+  int cnt = 0;
+  for (int w = lane; w < p.n_words; w += 64) cnt += __builtin_popcount(row[w]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
+  if (lane == 0) p.deg[r] = cnt;
+}
+
+bool tile_shape_ok(int tile_rows, int tile_kbits) {
+  const bool r = tile_rows == 8 || tile_rows == 16 || tile_rows == 32 || tile_rows == 64;
+  const bool k = tile_kbits == 32 || tile_kbits == 64 || tile_kbits == 128 || tile_kbits == 256 ||
+                 tile_kbits == 512;
+  return r && k;
+}
+
+size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
+
+}  // namespace
+}  // namespace qgtc
+
+using namespace qgtc;
+
+extern "C" size_t qgtc_tile_map_bytes(int32_t rows, int32_t kbits, int32_t tile_rows, int32_t tile_kbits) {
+  if (rows < 0 || kbits < 0 || !tile_shape_ok(tile_rows, tile_kbits)) return 0;
+  const size_t ntr = (size_t)cdiv(rows, tile_rows), ntc = (size_t)cdiv(kbits, tile_kbits);
+  return align16(ntr * 4) + align16(ntr * ntc * 4) + 16 + align16((size_t)rows * 4) + 16;
+}
+
+extern "C" qgtc_status qgtc_tile_map_carve(qgtc_tile_map* map, void* buffer, int32_t rows, int32_t kbits,
+                                           int32_t tile_rows, int32_t tile_kbits) {
+  if (!map || !buffer) return QGTC_ERR_NULL;
+  if (rows < 0 || kbits < 0) return QGTC_ERR_SHAPE;
+  if (!tile_shape_ok(tile_rows, tile_kbits)) return QGTC_ERR_UNSUPPORTED;
+  if (((uintptr_t)buffer & 15u) != 0) return QGTC_ERR_ALIGN;
+  const size_t ntr = (size_t)cdiv(rows, tile_rows), ntc = (size_t)cdiv(kbits, tile_kbits);
+  char* b = reinterpret_cast<char*>(buffer);
+  map->tile_rows = tile_rows;
+  map->tile_kbits = tile_kbits;
+  map->n_tile_rows = (int32_t)ntr;
+  map->n_tile_cols = (int32_t)ntc;
+  map->row_cnt = reinterpret_cast<int32_t*>(b);
+  b += align16(ntr * 4);
+  map->col_idx = reinterpret_cast<int32_t*>(b);
+  b += align16(ntr * ntc * 4);
+  map->nnz_tiles = reinterpret_cast<int32_t*>(b);
+  b += 16;
+  map->deg = reinterpret_cast<int32_t*>(b);
+  return QGTC_OK;
+}
+
+extern "C" qgtc_status qgtc_build_tile_map(const qgtc_bits* A, const qgtc_tile_map* map, void* stream) {
+  if (!A || !map) return QGTC_ERR_NULL;
+  qgtc_status st = check_adjacency(A);
+  if (st != QGTC_OK) return st;
+  if (!map->row_cnt || !map->col_idx || !map->nnz_tiles || !map->deg) return QGTC_ERR_NULL;
+  if (!tile_shape_ok(map->tile_rows, map->tile_kbits)) return QGTC_ERR_UNSUPPORTED;
+  if (map->n_tile_rows != cdiv(A->rows, map->tile_rows) || map->n_tile_cols != cdiv(A->cols, map->tile_kbits))
+    return QGTC_ERR_SHAPE;
+
+  MapParams p{};
+  p.A = A->data;
+  p.lda = A->ld_words;
+  p.rows = A->rows;
+  p.n_words = cdiv(A->cols, 32);
+  p.tile_rows = map->tile_rows;
+  p.tile_words = map->tile_kbits / 32;
+  p.n_tile_rows = map->n_tile_rows;
+  p.n_tile_cols = map->n_tile_cols;
+  p.row_cnt = map->row_cnt;
+  p.col_idx = map->col_idx;
+  p.nnz = map->nnz_tiles;
+  p.deg = map->deg;
+
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  ProfScope prof(QGTC_KERNEL_TILE_MAP, s);
+  if (p.n_tile_rows > 0 && p.n_tile_cols > 0) {
+    hipLaunchKernelGGL(tile_list_kernel, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p);
+    if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
+  }
+  hipLaunchKernelGGL(tile_total_kernel, dim3(1), dim3(256), 0, s, p);
+  if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
+  if (p.rows > 0) {
+    hipLaunchKernelGGL(degree_kernel, dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p);
+    if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
+  }
+  return QGTC_OK;
+}

@@ -1,0 +1,144 @@
+"""Host-side driver of the layer path: packs the operands once, then runs the
+layers of a quantized GCN / GIN through the library (Algorithm 1 of the paper
+per layer; hidden layers hand low-bit planes to the next layer, the last one
+emits fp32, Section 4.5).  Only argument set-up happens here; the arithmetic is
+in the kernels."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+
+from . import binding as B
+
+
+def inv_scale(lo: float, hi: float, nbits: int) -> float:
+    """fp32(2^nbits / (hi - lo)) as the library forms it for Eq. (2)."""
+    return float(torch.tensor(float(2 ** nbits) / (float(hi) - float(lo)),
+                              dtype=torch.float64).to(torch.float32))
+
+
+@dataclass
+class LayerRanges:
+    agg_hi: int          # requantization range [0, agg_hi) of the aggregation result
+    out_hi: int | None   # range [0, out_hi) of the update result (hidden layers)
+
+
+class QuantGNN:
+    """A stack of quantized layers on one batch of subgraphs.
+
+    A:   packed adjacency (LEFT, 1 bit; block_rows > 0 for compact batches)
+    Ws:  list of fp32 device tensors [D_l, H_l]; quantized to t bits by min-max
+    """
+
+    def __init__(self, A: B.Bits, Ws, s: int, t: int, self_term: bool,
+                 tile_kbits: int = 128, use_map: bool = True):
+        self.A = A
+        self.s, self.t = s, t
+        self.self_term = self_term
+        self.map = B.qgtc_build_tile_map(A, 16, tile_kbits) if use_map else None
+        self.deg = (self.map.deg if self.map is not None
+                    else B.qgtc_row_sums(A))
+        self.w_ranges = [(float(W.min()), float(W.max())) for W in Ws]
+        self.W = [B.qgtc_pack_bits(W.contiguous(), t, B.RIGHT, quant=r)
+                  for W, r in zip(Ws, self.w_ranges)]
+        self.w_colsum = [B.qgtc_col_sums(w) for w in self.W]
+        self.dims = [(W.shape[0], W.shape[1]) for W in Ws]
+        n = A.rows
+        dmax = max(d for d, _ in self.dims)
+        ws_bytes = B.lib().qgtc_layer_workspace_bytes(n, dmax, s)
+        self.workspace = torch.empty(ws_bytes // 4 + 1, dtype=torch.int32, device=A.words.device)
+        # ping-pong buffers for the low-bit activations between layers
+        hmax = max(h for _, h in self.dims)
+        self.x_bufs = [B.alloc_bits(n, max(dmax, hmax), s, B.RIGHT) for _ in range(2)]
+        self.y_last = None
+
+    # -- helpers -----------------------------------------------------------------
+    def _x_view(self, which: int, cols: int) -> B.Bits:
+        """A [N, cols] RIGHT-packed view on one of the activation buffers."""
+        buf = self.x_bufs[which]
+        d, _ = B.describe(self.A.rows, cols, self.s, B.RIGHT)
+        d.data = buf.words.data_ptr()
+        return B.Bits(buf.words, d)
+
+    def pack_input(self, X: torch.Tensor, x_range) -> B.Bits:
+        return B.qgtc_pack_bits(X, self.s, B.RIGHT, quant=x_range,
+                                out=self._x_view(0, X.shape[1]))
+
+    def _agg_ep(self, agg_hi: int) -> B.Epilogue:
+        return B.Epilogue(mode=B.OUT_BITS, rq_nbits=self.s, rq_lo=0,
+                          rq_inv_scale=inv_scale(0.0, float(agg_hi), self.s),
+                          self_term=self.self_term)
+
+    # -- calibration: integer maxima per layer, from int32 outputs ---------------------
+    def calibrate(self, X: torch.Tensor, x_range):
+        """Runs the stack once with int32 outputs and returns LayerRanges per
+        layer (range = [0, max observed accumulator], at least 1)."""
+        ranges = []
+        xb = self.pack_input(X, x_range)
+        for l, W in enumerate(self.W):
+            y32 = B.qgtc_aggregate(self.A, self.map, xb,
+                                   B.Epilogue(mode=B.OUT_I32, self_term=self.self_term))
+            agg_hi = max(1, int(y32.max()))
+            yb = B.qgtc_aggregate(self.A, self.map, xb, self._agg_ep(agg_hi))
+            z32 = B.qgtc_update(yb, W, B.Epilogue(mode=B.OUT_I32))
+            last = l == len(self.W) - 1
+            out_hi = None if last else max(1, int(z32.max()))
+            ranges.append(LayerRanges(agg_hi, out_hi))
+            if not last:
+                ep = B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0,
+                                rq_inv_scale=inv_scale(0.0, float(out_hi), self.s))
+                xb = B.qgtc_update(yb, W, ep, out=self._x_view((l + 1) & 1, self.dims[l][1]))
+        return ranges
+
+    # -- forward ---------------------------------------------------------------------
+    def last_layer_dequant(self, l: int, x_lo: float, x_scale: float, agg_hi: int,
+                           yq_rowsum: torch.Tensor) -> B.Epilogue:
+        """Epilogue that turns the last update's accumulators into the real
+        product of the dequantized operands: Y^ = l0[v] + sl*Yq, W^ = lo_w + sw*Wq."""
+        d = self.dims[l][0]
+        lo_w, hi_w = self.w_ranges[l]
+        sw = (hi_w - lo_w) / float(2 ** self.t)
+        inv = inv_scale(0.0, float(agg_hi), self.s)
+        sl = x_scale / inv
+        return B.Epilogue(mode=B.OUT_F32, cc=sl * sw, rs=sl * lo_w, row_i=yq_rowsum,
+                          l0a=(x_lo if self.self_term else 0.0), l0b=x_lo, row_l=self.deg,
+                          ck=lo_w * d, cs=sw, col_i=self.w_colsum[l])
+
+    def forward(self, X: torch.Tensor, x_range, ranges, out: torch.Tensor | None = None,
+                want_int: bool = False):
+        """fp32 [N, H_last] (or the last int32 accumulators when want_int)."""
+        xb = self.pack_input(X, x_range)
+        n_layers = len(self.W)
+        x_lo = float(x_range[0])
+        x_scale = (float(x_range[1]) - float(x_range[0])) / float(2 ** self.s)
+        for l, W in enumerate(self.W):
+            r = ranges[l]
+            agg_ep = self._agg_ep(r.agg_hi)
+            if l < n_layers - 1:
+                ep = B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0,
+                                rq_inv_scale=inv_scale(0.0, float(r.out_hi), self.s))
+                xb = B.qgtc_layer(self.A, self.map, xb, W, agg_ep, ep, self.workspace,
+                                  out=self._x_view((l + 1) & 1, self.dims[l][1]))
+                # hidden activations are read as pure scales: x^ = Xq * step
+                lo_w, hi_w = self.w_ranges[l]
+                sw = (hi_w - lo_w) / float(2 ** self.t)
+                x_scale = (x_scale / inv_scale(0.0, float(r.agg_hi), self.s)) * sw \
+                    / inv_scale(0.0, float(r.out_hi), self.s)
+                x_lo = 0.0
+            elif want_int:
+                return B.qgtc_layer(self.A, self.map, xb, W, agg_ep, B.Epilogue(mode=B.OUT_I32),
+                                    self.workspace, out=out)
+            else:
+                yb = B.qgtc_aggregate(self.A, self.map, xb, agg_ep,
+                                      out=self._y_bits(self.dims[l][0]))
+                rs = B.qgtc_row_sums(yb)
+                ep = self.last_layer_dequant(l, x_lo, x_scale, r.agg_hi, rs)
+                return B.qgtc_update(yb, W, ep, out=out)
+
+    def _y_bits(self, cols: int) -> B.Bits:
+        d, _ = B.describe(self.A.rows, cols, self.s, B.LEFT)
+        d.ld_words = -(-cols // 32)
+        d.plane_stride_words = self.A.rows * d.ld_words
+        d.data = self.workspace.data_ptr()
+        return B.Bits(self.workspace, d)

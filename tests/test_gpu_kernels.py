@@ -1,0 +1,245 @@
+"""GPU parity: each entry point of the C ABI against the CPU oracle, element by
+element, on seeded inputs that span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qgnn, bitplane as bp
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+q = pytest.importorskip("paper_2111_09547_amd")
+from gpu_util import dev, as_u32, pack_adjacency, words_np, sync  # noqa: E402
+
+
+def rand_graph(rng, n, k, p):
+    return (rng.random((n, k)) < p).astype(np.uint8)
+
+
+# ------------------------------------------------------------------ pack / unpack
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("bits", [1, 2, 3, 8, 13, 32])
+@pytest.mark.parametrize("shape", [(1, 1), (45, 77), (130, 64), (64, 2100)])
+def test_pack_integers_roundtrip(layout, bits, shape):
+    rng = np.random.default_rng([1, layout, bits, shape[0]])
+    v = rng.integers(0, 2 ** bits, size=shape, dtype=np.uint64).astype(np.uint32)
+    b = q.qgtc_pack_bits(dev(v.view(np.int32)), bits, layout)
+    sync()
+    want = bp.pack(v, bits, layout)
+    assert (words_np(b) == want).all()
+    if layout == q.LEFT:                      # padding words up to ld are zero
+        w = b.words.cpu().numpy().view(np.uint32)[:b.c.plane_stride_words * bits]
+        w = w.reshape(bits, shape[0], b.c.ld_words)
+        assert (w[:, :, want.shape[2]:] == 0).all()
+    assert (as_u32(q.qgtc_unpack_bits(b)) == v).all()
+
+
+def test_pack_u8_masks_high_bits():
+    rng = np.random.default_rng(2)
+    v = rng.integers(0, 256, size=(70, 40)).astype(np.uint8)
+    b = q.qgtc_pack_bits(dev(v), 3, q.RIGHT)
+    assert (as_u32(q.qgtc_unpack_bits(b)) == (v & 7)).all()
+
+
+@pytest.mark.parametrize("bits", [1, 2, 4, 8, 16, 24, 32])
+def test_pack_quantizes_like_eq2(bits):
+    rng = np.random.default_rng([3, bits])
+    x = rng.standard_normal((333, 50)).astype(np.float32)
+    x[0, 0], x[1, 1] = 1e30, -1e30            # far outside the range: clamped
+    lo, hi = -2.5, 3.25
+    b = q.qgtc_pack_bits(dev(x), bits, q.RIGHT, quant=(lo, hi))
+    want = qgnn.quantize(x, lo, hi, bits)
+    assert (as_u32(q.qgtc_unpack_bits(b)) == want).all()
+    # min-max range of the data itself
+    lo, hi = float(x[2:].min()), float(x[2:].max())
+    b = q.qgtc_pack_bits(dev(x[2:]), bits, q.LEFT, quant=(lo, hi))
+    assert (as_u32(q.qgtc_unpack_bits(b)) == qgnn.quantize(x[2:], lo, hi, bits)).all()
+
+
+def test_row_and_col_sums():
+    rng = np.random.default_rng(4)
+    v = rng.integers(0, 64, size=(150, 90)).astype(np.uint32)
+    bl = q.qgtc_pack_bits(dev(v.view(np.int32)), 6, q.LEFT)
+    br = q.qgtc_pack_bits(dev(v.view(np.int32)), 6, q.RIGHT)
+    assert (q.qgtc_row_sums(bl).cpu().numpy() == v.sum(axis=1)).all()
+    assert (q.qgtc_col_sums(br).cpu().numpy() == v.sum(axis=0)).all()
+
+
+# ----------------------------------------------------------------------- tile map
+@pytest.mark.parametrize("tile", [(8, 128), (16, 128), (16, 64), (16, 32), (32, 256), (64, 512)])
+def test_tile_map_matches_brute_force(tile):
+    rng = np.random.default_rng([5, tile[0], tile[1]])
+    n, k = 203, 1000
+    A = rand_graph(rng, n, k, 0.0008)
+    A[40:60] = 0                                 # some all-zero rows of tiles
+    Ab = pack_adjacency(A)
+    m = q.qgtc_build_tile_map(Ab, tile[0], tile[1])
+    sync()
+    lists, deg = qgnn.tile_map(A, tile[0], tile[1])
+    cnt = m.row_cnt.cpu().numpy()
+    idx = m.col_idx.cpu().numpy()
+    assert cnt.tolist() == [len(l) for l in lists]
+    for tr, l in enumerate(lists):
+        assert idx[tr, :len(l)].tolist() == l
+    assert int(m.nnz_tiles.cpu()[0]) == sum(len(l) for l in lists)
+    assert (m.deg.cpu().numpy() == deg).all()
+
+
+# ---------------------------------------------------------------------- aggregate
+def run_aggregate(A, X, s, tile_kbits=None, block=0, ep=None):
+    if block:
+        n = A.shape[0]
+        compact = np.zeros((n, block), dtype=np.uint8)
+        for r in range(n):
+            b0 = (r // block) * block
+            seg = A[r, b0:b0 + block]
+            compact[r, :seg.size] = seg
+        Ab = q.qgtc_pack_bits(dev(compact), 1, q.LEFT, block_rows=block)
+    else:
+        Ab = pack_adjacency(A)
+    Xb = q.qgtc_pack_bits(dev(X.view(np.int32)), s, q.RIGHT)
+    m = q.qgtc_build_tile_map(Ab, 16, tile_kbits) if tile_kbits else None
+    return q.qgtc_aggregate(Ab, m, Xb, ep or q.Epilogue(mode=q.OUT_I32)), m
+
+
+def test_config1_tiny_aggregation():
+    w = make_workload(1)
+    A = w.graph.dense()
+    want = qgnn.aggregate(A, w.X)
+    for kb in (None, 128, 64, 32):
+        got, _ = run_aggregate(A, w.X, w.s, kb)
+        assert (as_u32(got) == want).all(), kb
+    # 1-bit all-ones features give the node degrees
+    ones = np.ones((A.shape[0], 16), dtype=np.uint32)
+    got, m = run_aggregate(A, ones, 1, 128)
+    assert (as_u32(got) == w.graph.degrees()[:, None]).all()
+    assert (m.deg.cpu().numpy() == w.graph.degrees()).all()
+
+
+@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8, 11, 16, 32])
+@pytest.mark.parametrize("shape", [(100, 100, 70), (257, 257, 16), (96, 300, 33), (40, 40, 130)])
+def test_aggregate_int32_ragged(s, shape):
+    n, k, d = shape
+    rng = np.random.default_rng([6, s, n, d])
+    A = rand_graph(rng, n, k, 0.05)
+    X = rng.integers(0, 2 ** s, size=(k, d), dtype=np.uint64).astype(np.uint32)
+    want = qgnn.aggregate(A, X)
+    for kb in (None, 128, 32):
+        got, _ = run_aggregate(A, X, s, kb)
+        assert (as_u32(got) == want).all(), kb
+
+
+@pytest.mark.parametrize("d", [16, 32, 64, 200])
+def test_aggregate_block_diagonal_compact_and_self_term(d):
+    rng = np.random.default_rng([7, d])
+    n, block, s = 330, 96, 5
+    A = np.zeros((n, n), dtype=np.uint8)
+    for b0 in range(0, n, block):
+        b1 = min(n, b0 + block)
+        A[b0:b1, b0:b1] = rand_graph(rng, b1 - b0, b1 - b0, 0.08)
+    X = rng.integers(0, 2 ** s, size=(n, d)).astype(np.uint32)
+    for self_term in (False, True):
+        want = qgnn.aggregate(A, X, self_term)
+        ep = q.Epilogue(mode=q.OUT_I32, self_term=self_term)
+        for kb in (None, 128, 64):
+            got, _ = run_aggregate(A, X, s, kb, block=block, ep=ep)
+            assert (as_u32(got) == want).all(), (self_term, kb)
+        got, _ = run_aggregate(A, X, s, 128, ep=ep)          # same graph, dense storage
+        assert (as_u32(got) == want).all()
+
+
+@pytest.mark.parametrize("d", [16, 24, 64, 100])
+@pytest.mark.parametrize("rq_bits", [1, 3, 8, 12])
+def test_aggregate_bits_and_f32_epilogues(d, rq_bits):
+    rng = np.random.default_rng([8, d, rq_bits])
+    n, s = 150, 4
+    A = rand_graph(rng, n, n, 0.1)
+    X = rng.integers(0, 2 ** s, size=(n, d)).astype(np.uint32)
+    Y = qgnn.aggregate(A, X)
+    rq_lo, inv = 3, qgnn.inv_scale(3.0, float(Y.max()), rq_bits)
+    ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=rq_bits, rq_lo=rq_lo, rq_inv_scale=float(inv))
+    got, _ = run_aggregate(A, X, s, 128, ep=ep)
+    want = qgnn.requantize(Y, rq_lo, inv, rq_bits)
+    assert (words_np(got) == bp.pack(want, rq_bits, bp.LEFT)).all()
+    assert (as_u32(q.qgtc_unpack_bits(got)) == want).all()
+    # fp32: sx * Y + lo_x * deg
+    deg = A.sum(axis=1).astype(np.int32)
+    ep = q.Epilogue(mode=q.OUT_F32, cc=0.37, rs=-1.25, row_i=dev(deg))
+    got, _ = run_aggregate(A, X, s, 128, ep=ep)
+    ref = qgnn.dequantize(Y, cc=0.37, rs=-1.25, row_i=deg)
+    assert np.allclose(got.cpu().numpy(), ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+    # int32 with ReLU on the signed accumulator (wrapped values count as negative)
+    Xbig = np.full((n, d), 2 ** 31 - 1, dtype=np.uint32)
+    ep = q.Epilogue(mode=q.OUT_I32, relu=True)
+    got, _ = run_aggregate(A, Xbig, 32, 128, ep=ep)
+    assert (got.cpu().numpy() == qgnn.int_output(qgnn.aggregate(A, Xbig), relu=True)).all()
+
+
+# ------------------------------------------------------------------------- update
+@pytest.mark.parametrize("st", [(1, 1), (2, 3), (4, 4), (8, 8), (8, 2), (3, 7), (16, 16), (32, 32), (12, 5)])
+@pytest.mark.parametrize("shape", [(100, 64, 64), (257, 128, 16), (70, 40, 5), (1000, 512, 16), (64, 300, 70)])
+def test_update_int32(st, shape):
+    s, t = st
+    n, d, h = shape
+    rng = np.random.default_rng([9, s, t, n])
+    Yq = rng.integers(0, 2 ** s, size=(n, d), dtype=np.uint64).astype(np.uint32)
+    Wq = rng.integers(0, 2 ** t, size=(d, h), dtype=np.uint64).astype(np.uint32)
+    Yb = q.qgtc_pack_bits(dev(Yq.view(np.int32)), s, q.LEFT)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    got = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_I32))
+    assert (as_u32(got) == qgnn.update(Yq, Wq)).all()
+
+
+@pytest.mark.parametrize("rq_bits", [1, 4, 8, 10])
+def test_update_bits_and_f32_epilogues(rq_bits):
+    rng = np.random.default_rng([10, rq_bits])
+    n, d, h, s, t = 300, 64, 24, 4, 3
+    Yq = rng.integers(0, 2 ** s, size=(n, d)).astype(np.uint32)
+    Wq = rng.integers(0, 2 ** t, size=(d, h)).astype(np.uint32)
+    Yb = q.qgtc_pack_bits(dev(Yq.view(np.int32)), s, q.LEFT)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    Z = qgnn.update(Yq, Wq)
+    inv = qgnn.inv_scale(0.0, float(Z.max()), rq_bits)
+    ep = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=rq_bits, rq_lo=0, rq_inv_scale=float(inv))
+    got = q.qgtc_update(Yb, Wb, ep)
+    want = qgnn.requantize(Z, 0, inv, rq_bits, relu=True)
+    assert (words_np(got) == bp.pack(want, rq_bits, bp.RIGHT)).all()
+    rs = Yq.sum(axis=1).astype(np.int32)
+    cs = Wq.sum(axis=0).astype(np.int32)
+    rl = rng.integers(1, 30, size=n).astype(np.int32)
+    kw = dict(cc=1.7e-3, rs=-0.031, l0a=0.4, l0b=-0.9, ck=-6.4, cs=0.0125)
+    for relu in (False, True):
+        ep = q.Epilogue(mode=q.OUT_F32, relu=relu, row_i=dev(rs), row_l=dev(rl), col_i=dev(cs), **kw)
+        got = q.qgtc_update(Yb, Wb, ep).cpu().numpy()
+        ref = qgnn.dequantize(Z, row_i=rs, row_l=rl, col_i=cs, relu=relu, **kw)
+        assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+
+
+# -------------------------------------------------------------------------- layer
+@pytest.mark.parametrize("cfg,bits,nb", [(2, 4, None), (3, 1, 2), (3, 3, 2), (3, 8, 2), (3, 16, 1), (3, 32, 1)])
+def test_layer_matches_oracle(cfg, bits, nb):
+    w = make_workload(cfg, bits=bits, n_blocks=nb)
+    A = w.graph.dense()
+    xr = (float(w.X.min()), float(w.X.max()))
+    wr = (float(w.W[0].min()), float(w.W[0].max()))
+    Xq = qgnn.quantize(w.X, xr[0], xr[1], w.s)
+    Wq = qgnn.quantize(w.W[0], wr[0], wr[1], w.t)
+    Y, Yq, Z, (rq_lo, rq_inv) = qgnn.layer(A, Xq, Wq, w.s)
+    Ab = pack_adjacency(A)
+    m = q.qgtc_build_tile_map(Ab)
+    Xb = q.qgtc_pack_bits(dev(w.X), w.s, q.RIGHT, quant=xr)
+    Wb = q.qgtc_pack_bits(dev(w.W[0]), w.t, q.RIGHT, quant=wr)
+    assert (as_u32(q.qgtc_unpack_bits(Xb)) == Xq).all()
+    assert (as_u32(q.qgtc_unpack_bits(Wb)) == Wq).all()
+    agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=w.s, rq_lo=rq_lo, rq_inv_scale=float(rq_inv))
+    got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32))
+    assert (as_u32(got) == Z).all()
+    # the two halves on their own
+    y32 = q.qgtc_aggregate(Ab, m, Xb, q.Epilogue(mode=q.OUT_I32))
+    assert (as_u32(y32) == Y).all()
+    yb = q.qgtc_aggregate(Ab, m, Xb, agg_ep)
+    assert (as_u32(q.qgtc_unpack_bits(yb)) == Yq).all()
+    # running twice gives the same bytes (no races)
+    again = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32))
+    assert torch.equal(got, again)
