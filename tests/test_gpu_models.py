@@ -1,0 +1,116 @@
+"""GPU parity of whole models (configs 4 and 5) against the CPU oracle:
+layer by layer with the oracle fed the same integers ("teacher forced") and end
+to end, at reduced and at full size."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qgnn
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+q = pytest.importorskip("paper_2111_09547_amd")
+from paper_2111_09547_amd.model import QuantGNN, LayerRanges  # noqa: E402
+from gpu_util import dev, as_u32, pack_adjacency  # noqa: E402
+
+
+def oracle_ranges(rqs, s):
+    """(rq_lo, inv) pairs of the oracle's calibration -> integer range ends."""
+    out = []
+    for (agg, o) in rqs:
+        out.append((agg, o))
+    return out
+
+
+def run_model(w, tile_kbits=128):
+    """Runs the HIP path with ranges calibrated by the HIP path itself and
+    checks every layer against the oracle fed the same ranges."""
+    g = w.graph
+    Ab = pack_adjacency(g, w.storage)
+    Ws = [dev(W) for W in w.W]
+    self_term = w.model == "gin"
+    net = QuantGNN(Ab, Ws, w.s, w.t, self_term, tile_kbits=tile_kbits)
+    X = dev(w.X)
+    xr = (float(w.X.min()), float(w.X.max()))
+    ranges = net.calibrate(X, xr)
+
+    # the oracle, given the same user-set ranges
+    A = g.scipy_csr()
+    wr = [(float(W.min()), float(W.max())) for W in w.W]
+    rqs = []
+    for r in ranges:
+        agg = (0, qgnn.inv_scale(0.0, float(r.agg_hi), w.s))
+        out = None if r.out_hi is None else (0, qgnn.inv_scale(0.0, float(r.out_hi), w.s))
+        rqs.append((agg, out))
+    trace, _ = qgnn.forward(A, w.X, xr, w.W, wr, w.s, w.t, self_term, rqs=rqs)
+    # the calibration the HIP path made equals what the oracle would calibrate
+    for r, tr in zip(ranges, trace):
+        assert r.agg_hi == max(1, int(qgnn.as_signed(tr["Y"]).max()))
+
+    # end to end: last int32 accumulators and the fp32 output
+    z = net.forward(X, xr, ranges, want_int=True)
+    assert (as_u32(z) == trace[-1]["Z"]).all()
+    out = net.forward(X, xr, ranges)
+    torch.cuda.synchronize()
+
+    # fp32 reference from the oracle with the same scalars
+    L = len(w.W) - 1
+    x_lo, x_scale = xr[0], (xr[1] - xr[0]) / 2.0 ** w.s
+    for l in range(L):
+        sw = (wr[l][1] - wr[l][0]) / 2.0 ** w.t
+        x_scale = (x_scale / float(rqs[l][0][1])) * sw / float(rqs[l][1][1])
+        x_lo = 0.0
+    sw = (wr[L][1] - wr[L][0]) / 2.0 ** w.t
+    sl = x_scale / float(rqs[L][0][1])
+    deg = g.degrees()
+    ref = qgnn.dequantize(trace[L]["Z"], cc=sl * sw, rs=sl * wr[L][0],
+                          row_i=trace[L]["Yq"].sum(axis=1, dtype=np.int64),
+                          l0a=(x_lo if self_term else 0.0), l0b=x_lo, row_l=deg,
+                          ck=wr[L][0] * w.W[L].shape[0], cs=sw,
+                          col_i=trace[L]["Wq"].sum(axis=0, dtype=np.int64))
+    got = out.cpu().numpy()
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+
+    # layer by layer, teacher forced: feed the oracle's integers to each HIP layer
+    for l, tr in enumerate(trace):
+        xb = q.qgtc_pack_bits(dev(tr["Xq"].view(np.int32)), w.s, q.RIGHT)
+        ep = q.Epilogue(mode=q.OUT_I32, self_term=self_term)
+        y32 = q.qgtc_aggregate(net.A, net.map, xb, ep)
+        assert (as_u32(y32) == tr["Y"]).all(), l
+        zz = q.qgtc_layer(net.A, net.map, xb, net.W[l], net._agg_ep(ranges[l].agg_hi),
+                          q.Epilogue(mode=q.OUT_I32))
+        assert (as_u32(zz) == tr["Z"]).all(), l
+    return net, ranges
+
+
+@pytest.mark.parametrize("nb", [2, None])
+def test_config4_gin_five_layers(nb):
+    w = make_workload(4, n_blocks=nb)
+    run_model(w)
+
+
+@pytest.mark.parametrize("bits,nb,kb", [(1, 4, 128), (2, 4, 64), (4, 4, 32), (8, 4, 128), (8, None, 128), (4, None, 32)])
+def test_config5_gcn_two_layers(bits, nb, kb):
+    w = make_workload(5, bits=bits, n_blocks=nb)
+    run_model(w, tile_kbits=kb)
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5, 6, 7, 8, 16, 32])
+def test_config3_full_size_bit_sweep(bits):
+    w = make_workload(3, bits=bits)
+    A = w.graph.scipy_csr()
+    xr = (float(w.X.min()), float(w.X.max()))
+    wr = (float(w.W[0].min()), float(w.W[0].max()))
+    Xq = qgnn.quantize(w.X, xr[0], xr[1], w.s)
+    Wq = qgnn.quantize(w.W[0], wr[0], wr[1], w.t)
+    Y, Yq, Z, (rq_lo, rq_inv) = qgnn.layer(A, Xq, Wq, w.s)
+    Ab = pack_adjacency(w.graph, "dense")
+    m = q.qgtc_build_tile_map(Ab)
+    Xb = q.qgtc_pack_bits(dev(w.X), w.s, q.RIGHT, quant=xr)
+    Wb = q.qgtc_pack_bits(dev(w.W[0]), w.t, q.RIGHT, quant=wr)
+    agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=w.s, rq_lo=rq_lo, rq_inv_scale=float(rq_inv))
+    got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32))
+    assert (as_u32(got) == Z).all()
+    # the tile map keeps exactly the diagonal blocks (8 blocks of 1024: 8 of 64 tile columns)
+    assert int(m.nnz_tiles.cpu()[0]) == 512 * 8
