@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized GNN layer path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that
+is already resident in HBM: pack the adjacency into bit planes, build its
+zero-tile map, quantize and pack the weights, quantize and pack the features,
+then run every layer (aggregate -> requantize -> update -> ReLU + requantize;
+the last layer emits fp32).  The workload is the 5-layer GIN of the benchmark
+description (65,536 nodes in 64 subgraphs of 1024, hidden 64, s = t = 8).
+
+Prints ONE JSON line.  `value` counts executed bit-operations (2 per 1-bit
+multiply-accumulate, only on tiles the zero-tile map keeps) per second of
+step time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X vector-ALU ceiling for AND + popcount-accumulate: 256 CUs x 64 lanes per
+# clock x 2.4 GHz 32-bit lane operations per second; two lane operations (v_and,
+# v_bcnt) cover 32 one-bit multiply-accumulates = 64 bit-operations.
+VALU_LANE_OPS = 256 * 64 * 2.4e9
+PEAK_BITOPS = VALU_LANE_OPS / 2 * 64          # 1.258e15 bit-op/s
+
+
+def workload_bitops(net, n_nodes, tile_kbits):
+    """Executed bit-operations of one forward pass, per kernel family."""
+    nnz = int(net.map.nnz_tiles.cpu()[0])
+    agg = [2.0 * nnz * 16 * tile_kbits * d * net.s for d, _ in net.dims]
+    upd = [2.0 * n_nodes * d * h * net.s * net.t for d, h in net.dims]
+    return agg, upd, nnz
+
+
+def cpu_baseline(w, ranges, total_bitops, sample_blocks=8):
+    """The CPU oracle, as it stands, on the first `sample_blocks` subgraphs."""
+    import numpy as np
+    from oracle import qgnn
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    g = w.graph
+    n = sample_blocks * g.block
+    A = g.scipy_csr()[:n, :n]
+    X = w.X[:n]
+    xr = (float(w.X.min()), float(w.X.max()))
+    wr = [(float(W.min()), float(W.max())) for W in w.W]
+    rqs = [((0, qgnn.inv_scale(0.0, float(r.agg_hi), w.s)),
+            None if r.out_hi is None else (0, qgnn.inv_scale(0.0, float(r.out_hi), w.s)))
+           for r in ranges]
+    best = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        trace, _ = qgnn.forward(A, X, xr, w.W, wr, w.s, w.t, w.model == "gin", rqs=rqs)
+        z = trace[-1]["Z"]
+        best = min(best, time.perf_counter() - t0)
+    frac = n / g.n_nodes
+    return {"value": total_bitops * frac / best / 1e12, "unit": "Tbit-op/s",
+            "cores": int(threads), "kind": "oracle",
+            "sample": f"{sample_blocks} of {g.n_blocks} subgraphs, all layers, best of 3 "
+                      f"({best * 1e3:.1f} ms); numpy/scipy integer products",
+            "ms": best * 1e3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="workload (4 or 5)")
+    ap.add_argument("--bits", type=int, default=8)
+    ap.add_argument("--tile-kbits", type=int, default=128)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path "
+              "(subgraph batches would be sharded with no collective); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2111_09547_amd as q
+    from paper_2111_09547_amd.model import QuantGNN
+    from workloads import make_workload
+
+    torch.cuda.set_device(0)
+    w = make_workload(args.config, bits=args.bits)
+    g = w.graph
+    A_src = torch.from_numpy(g.dense_compact() if w.storage == "compact" else g.dense()).cuda()
+    block_rows = g.block if w.storage == "compact" else 0
+    Ws = [torch.from_numpy(W).cuda() for W in w.W]
+    X = torch.from_numpy(w.X).cuda()
+    xr = (float(w.X.min()), float(w.X.max()))
+    self_term = w.model == "gin"
+    net = QuantGNN(A_src, Ws, w.s, w.t, self_term, tile_kbits=args.tile_kbits,
+                   block_rows=block_rows)
+    ranges = net.calibrate(X, xr)          # user-set requantization ranges, outside the timing
+    out = torch.empty((g.n_nodes, net.dims[-1][1]), dtype=torch.float32, device="cuda")
+
+    def step():
+        net.pack_static()
+        net.forward(X, xr, ranges, out=out)
+
+    def layers_only():
+        net.forward(X, xr, ranges, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # features-to-output only (adjacency, map and weights cached, as the paper does)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        layers_only()
+    torch.cuda.synchronize()
+    ms_layers = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # the same steps again with HIP events around every kernel launch
+    q.qgtc_prof_enable(True)
+    q.qgtc_prof_reset()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    kinds = {"pack": q.KERNEL_PACK, "tile_map": q.KERNEL_TILE_MAP, "aggregate": q.KERNEL_AGGREGATE,
+             "update": q.KERNEL_UPDATE, "sums": q.KERNEL_SUMS}
+    prof = {k: q.qgtc_prof_read(v) for k, v in kinds.items()}
+    q.qgtc_prof_enable(False)
+    q.qgtc_prof_reset()
+
+    agg_ops, upd_ops, nnz = workload_bitops(net, g.n_nodes, args.tile_kbits)
+    total_ops = sum(agg_ops) + sum(upd_ops)
+    agg_ms, agg_n = prof["aggregate"]
+    upd_ms, upd_n = prof["update"]
+    agg_rate = sum(agg_ops) * args.steps / (agg_ms * 1e-3)          # bit-op/s over all launches
+    upd_rate = sum(upd_ops) * args.steps / (upd_ms * 1e-3)
+    n_layers = len(net.dims)
+    dense_macs = sum(2.0 * g.n_nodes * g.block * d + 2.0 * g.n_nodes * d * h for d, h in net.dims)
+
+    rec = {
+        "metric": "quantized GNN layer bit-ops/s (TOPS-equiv) + ms/layer, vs VALU/HBM roofline",
+        "value": total_ops / (ms_step * 1e-3) / 1e12,
+        "unit": "Tbit-op/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": f"config {w.cfg}: {w.name}", "nodes": g.n_nodes,
+                   "subgraphs": g.n_blocks, "layers": n_layers, "s_bits": w.s, "t_bits": w.t,
+                   "dims": net.dims, "tile": [16, args.tile_kbits],
+                   "nonzero_tiles": nnz,
+                   "nonzero_tile_ratio": nnz / float(net.map.c.n_tile_rows * net.map.c.n_tile_cols),
+                   "step": "pack A + tile map + pack W + pack X + all layers"},
+        "ms_per_layer": ms_layers / n_layers,
+        "ms_layers_only": ms_layers,
+        "tops_equiv_dense": dense_macs / (ms_layers * 1e-3) / 1e12,
+        "roofline": {"bound": "alu", "kernel": "aggregate_kernel",
+                     "achieved": agg_rate / 1e12, "peak": PEAK_BITOPS / 1e12,
+                     "unit": "Tbit-op/s", "frac": agg_rate / PEAK_BITOPS,
+                     "avg_launch_ms": agg_ms / max(agg_n, 1), "launches": agg_n,
+                     "traffic": None},
+        "kernels": {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps}
+                    for k, v in prof.items()},
+        "update_roofline": {"bound": "alu", "achieved": upd_rate / 1e12,
+                            "peak": PEAK_BITOPS / 1e12, "frac": upd_rate / PEAK_BITOPS},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(w, ranges, total_ops)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

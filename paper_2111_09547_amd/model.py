@@ -27,31 +27,51 @@ class LayerRanges:
 class QuantGNN:
     """A stack of quantized layers on one batch of subgraphs.
 
-    A:   packed adjacency (LEFT, 1 bit; block_rows > 0 for compact batches)
-    Ws:  list of fp32 device tensors [D_l, H_l]; quantized to t bits by min-max
+    A_src: uint8 0/1 device tensor, [N, N] (block_rows = 0) or [N, block_rows]
+           (one row of diagonal blocks, see qgtc_bits.block_rows), or an already
+           packed adjacency (Bits)
+    Ws:    list of fp32 device tensors [D_l, H_l]; quantized to t bits by min-max
     """
 
-    def __init__(self, A: B.Bits, Ws, s: int, t: int, self_term: bool,
-                 tile_kbits: int = 128, use_map: bool = True):
-        self.A = A
+    def __init__(self, A_src, Ws, s: int, t: int, self_term: bool,
+                 tile_kbits: int = 128, use_map: bool = True, block_rows: int = 0):
         self.s, self.t = s, t
         self.self_term = self_term
-        self.map = B.qgtc_build_tile_map(A, 16, tile_kbits) if use_map else None
-        self.deg = (self.map.deg if self.map is not None
-                    else B.qgtc_row_sums(A))
+        self.tile_kbits = tile_kbits
+        self.use_map = use_map
+        self.Ws = [W.contiguous() for W in Ws]
         self.w_ranges = [(float(W.min()), float(W.max())) for W in Ws]
-        self.W = [B.qgtc_pack_bits(W.contiguous(), t, B.RIGHT, quant=r)
-                  for W, r in zip(Ws, self.w_ranges)]
-        self.w_colsum = [B.qgtc_col_sums(w) for w in self.W]
         self.dims = [(W.shape[0], W.shape[1]) for W in Ws]
-        n = A.rows
+        if isinstance(A_src, B.Bits):
+            self.A_src, self.A = None, A_src
+        else:
+            self.A_src = A_src
+            self.A = B.alloc_bits(A_src.shape[0], A_src.shape[1], 1, B.LEFT, block_rows)
+        self.map = None
+        self.W = [B.alloc_bits(d, h, t, B.RIGHT) for d, h in self.dims]
+        n = self.A.rows
         dmax = max(d for d, _ in self.dims)
         ws_bytes = B.lib().qgtc_layer_workspace_bytes(n, dmax, s)
-        self.workspace = torch.empty(ws_bytes // 4 + 1, dtype=torch.int32, device=A.words.device)
+        self.workspace = torch.empty(ws_bytes // 4 + 1, dtype=torch.int32, device=self.A.words.device)
         # ping-pong buffers for the low-bit activations between layers
         hmax = max(h for _, h in self.dims)
         self.x_bufs = [B.alloc_bits(n, max(dmax, hmax), s, B.RIGHT) for _ in range(2)]
-        self.y_last = None
+        self.pack_static()
+
+    def pack_static(self):
+        """Everything that does not depend on the features: pack A, build its
+        zero-tile map, quantize and pack the weights (the paper caches these
+        across layers and subgraphs, end of Section 3.2)."""
+        if self.A_src is not None:
+            B.qgtc_pack_bits(self.A_src, 1, B.LEFT, out=self.A)
+        if self.use_map:
+            self.map = B.qgtc_build_tile_map(self.A, 16, self.tile_kbits, out=self.map)
+            self.deg = self.map.deg
+        else:
+            self.deg = B.qgtc_row_sums(self.A)
+        for W, r, dst in zip(self.Ws, self.w_ranges, self.W):
+            B.qgtc_pack_bits(W, self.t, B.RIGHT, quant=r, out=dst)
+        self.w_colsum = [B.qgtc_col_sums(w) for w in self.W]
 
     # -- helpers -----------------------------------------------------------------
     def _x_view(self, which: int, cols: int) -> B.Bits:

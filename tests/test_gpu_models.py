@@ -27,10 +27,13 @@ def run_model(w, tile_kbits=128):
     """Runs the HIP path with ranges calibrated by the HIP path itself and
     checks every layer against the oracle fed the same ranges."""
     g = w.graph
-    Ab = pack_adjacency(g, w.storage)
     Ws = [dev(W) for W in w.W]
     self_term = w.model == "gin"
-    net = QuantGNN(Ab, Ws, w.s, w.t, self_term, tile_kbits=tile_kbits)
+    if w.storage == "dense":
+        net = QuantGNN(dev(g.dense()), Ws, w.s, w.t, self_term, tile_kbits=tile_kbits)
+    else:
+        net = QuantGNN(dev(g.dense_compact()), Ws, w.s, w.t, self_term, tile_kbits=tile_kbits,
+                       block_rows=g.block)
     X = dev(w.X)
     xr = (float(w.X.min()), float(w.X.max()))
     ranges = net.calibrate(X, xr)
