@@ -139,45 +139,55 @@ __device__ __forceinline__ Step4 load_steps(const AggParams& p, const uint32_t* 
   return r;
 }
 
-// v = value for lane L only (value wave-uniform, in an SGPR).
-template <int L>
-__device__ __forceinline__ void write_lane(uint32_t& v, uint32_t value) {
-  asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(value), "n"(L));
-}
-
-// Packs up to 8 planes (pg .. pg+7) of the requantized row J of the wave into
-// the gather registers ow[]: a ballot of bit i over the 64 lanes is 64
-// consecutive column bits of plane i; lane 4*J + k keeps word k of row J
-// (CW = 64: k = 0, 1 are the two words of the column group; CW = 32 / 16: k is
-// the row group and each row has one word).
-template <int J>
-__device__ __forceinline__ void gather_row_bits(uint32_t q, uint32_t (&ow)[8], int pg, int qbits,
-                                                int cw_shift) {
+// The words that the ballots of bit (p0 + i) of q, i < S, give for one output
+// row of the wave.  CWS >= 5: the two halves of the 64-bit ballot (CW = 64: two
+// consecutive words of the row; CW = 32: the words of the two row groups);
+// CWS == 4: its four 16-bit fields (the words of the four row groups).
+template <int S, int CWS>
+__device__ __forceinline__ void ballot_words(uint32_t q, int p0, uint32_t (&w)[S][4]) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    if (pg + i >= qbits) continue;                 // wave-uniform
-    const unsigned long long m = __builtin_amdgcn_ballot_w64(((q >> (pg + i)) & 1u) != 0u);
-    if (cw_shift >= 5) {
-      write_lane<4 * J>(ow[i], (uint32_t)m);
-      write_lane<4 * J + 1>(ow[i], (uint32_t)(m >> 32));
+  for (int i = 0; i < S; ++i) {
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(((q >> (p0 + i)) & 1u) != 0u);
+    if constexpr (CWS >= 5) {
+      w[i][0] = (uint32_t)m;
+      w[i][1] = (uint32_t)(m >> 32);
+      w[i][2] = 0u;
+      w[i][3] = 0u;
     } else {
-      write_lane<4 * J>(ow[i], (uint32_t)(m & 0xffffull));
-      write_lane<4 * J + 1>(ow[i], (uint32_t)((m >> 16) & 0xffffull));
-      write_lane<4 * J + 2>(ow[i], (uint32_t)((m >> 32) & 0xffffull));
-      write_lane<4 * J + 3>(ow[i], (uint32_t)((m >> 48) & 0xffffull));
+      w[i][0] = (uint32_t)(m & 0xffffull);
+      w[i][1] = (uint32_t)((m >> 16) & 0xffffull);
+      w[i][2] = (uint32_t)((m >> 32) & 0xffffull);
+      w[i][3] = (uint32_t)((m >> 48) & 0xffffull);
     }
   }
 }
 
-template <int J>
-__device__ __forceinline__ void gather_rows(const uint32_t (&q)[16], uint32_t (&ow)[8], int pg, int qbits,
-                                            int cw_shift, int km, int wave) {
-  if ((J & km) == wave) gather_row_bits<J>(q[J], ow, pg, qbits, cw_shift);
-  if constexpr (J + 1 < 16) gather_rows<J + 1>(q, ow, pg, qbits, cw_shift, km, wave);
+// Generic path: planes pg .. pg+7 of the rows the wave owns; lane 4*J + k keeps
+// word k of row J.  Planes past qbits give q >> plane == 0 and are not stored.
+template <int J, int CWS>
+__device__ __forceinline__ void gather_rows(const uint32_t (&q)[16], uint32_t (&ow)[8], int pg,
+                                            int km, int wave) {
+  if ((J & km) == wave) {
+    uint32_t w[8][4];
+    ballot_words<8, CWS>(pg < 32 ? q[J] : 0u, pg, w);
+    lane_pack<8, (CWS >= 5 ? 2 : 4)>::template run<4 * J>(w, ow);
+  }
+  if constexpr (J + 1 < 16) gather_rows<J + 1, CWS>(q, ow, pg, km, wave);
 }
 
-template <int S, bool UNI, bool MULTI>
+// Fast path of the requantize-and-pack epilogue: as many output planes as
+// feature planes (the layer case), one wave per workgroup, everything unrolled.
+template <int J, int S, int CWS>
+__device__ __forceinline__ void pack_rows_fast(const uint32_t (&q)[16], uint32_t (&ow)[S]) {
+  uint32_t w[S][4];
+  ballot_words<S, CWS>(q[J], 0, w);
+  lane_pack<S, (CWS >= 5 ? 2 : 4)>::template run<4 * J>(w, ow);
+  if constexpr (J + 1 < 16) pack_rows_fast<J + 1, S, CWS>(q, ow);
+}
+
+template <int S, int CWS, bool MULTI>
 __global__ __launch_bounds__(256) void aggregate_kernel(const AggParams p) {
+  constexpr bool UNI = CWS == 6;
   extern __shared__ uint32_t lds[];   // [ksplit][16][64] partial sums when ksplit > 1
 
   const unsigned grid = gridDim.x;
@@ -186,11 +196,11 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggParams p) {
   const int rt = (int)(bid / (unsigned)p.n_cg);
   const int cg = (int)(bid % (unsigned)p.n_cg);
 
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int lane = threadIdx.x & 63;
-  const int cw = 1 << p.cw_shift;
-  const int rg = UNI ? 0 : (lane >> p.cw_shift);
-  const int rgs = 64 >> p.cw_shift;                 // row tiles per wave
+  constexpr int cw = 1 << CWS;
+  const int rg = UNI ? 0 : (lane >> CWS);
+  constexpr int rgs = 64 >> CWS;                 // row tiles per wave
   const int tr = rt * rgs + rg;                     // this lane's tile row
   const bool tr_ok = tr < p.n_tile_rows;
   const int c = cg * cw + (lane & (cw - 1));        // this lane's output column
@@ -324,6 +334,32 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggParams p) {
       const bool ok = tr_ok && c_ok && (out_row0 + j) < p.rows;
       y[j] = ok ? requantize_i32(y[j], e, qmax, qmaxf) : 0u;
     }
+    if (!MULTI && qbits == S && p.ksplit == 1) {
+      uint32_t ow[S];
+#pragma unroll
+      for (int i = 0; i < S; ++i) ow[i] = 0u;
+      pack_rows_fast<0, S, CWS>(y, ow);
+      const int sj = lane >> 2;
+      const int sk = lane & 3;
+      int srow_out, sword;
+      bool mine;
+      if constexpr (CWS == 6) {
+        srow_out = rt * 16 + sj;
+        sword = cg * 2 + sk;
+        mine = sk < 2;
+      } else {
+        srow_out = (rt * rgs + sk) * 16 + sj;
+        sword = 0;
+        mine = sk < rgs;
+      }
+      mine = mine && srow_out < p.rows && sword < ((p.cols + 31) >> 5);
+      if (mine) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(e.out) + (int64_t)srow_out * e.ld_out + sword;
+#pragma unroll
+        for (int i = 0; i < S; ++i) dst[(int64_t)i * e.ps_out] = ow[i];
+      }
+      return;
+    }
     // lane 4*j + k will store word k of row j.  CW = 64: k = 0, 1 are the two
     // words of the column group; CW = 32 / 16: k is the row group and every
     // row has a single word.
@@ -331,7 +367,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggParams p) {
     const int sk = lane & 3;
     bool mine = (sj & km) == wave;
     int srow_out, sword;
-    if (p.cw_shift == 6) {
+    if (CWS == 6) {
       srow_out = rt * 16 + sj;
       sword = cg * 2 + sk;
       mine = mine && sk < 2;
@@ -347,7 +383,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggParams p) {
       uint32_t ow[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) ow[i] = 0u;
-      gather_rows<0>(y, ow, pg, qbits, p.cw_shift, km, wave);
+      gather_rows<0, CWS>(y, ow, pg, km, wave);
 #pragma unroll
       for (int i = 0; i < 8; ++i)
         if (mine && pg + i < qbits) dst[(int64_t)(pg + i) * e.ps_out] = ow[i];
@@ -355,26 +391,26 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggParams p) {
   }
 }
 
-template <int S, bool UNI, bool MULTI>
+template <int S, int CWS, bool MULTI>
 qgtc_status launch(const AggParams& p, hipStream_t stream) {
   const unsigned grid = xcd_grid(p.nblocks);
   const size_t lds = p.ksplit > 1 ? (size_t)p.ksplit * 16 * 64 * sizeof(uint32_t) : 0;
-  hipLaunchKernelGGL((aggregate_kernel<S, UNI, MULTI>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
+  hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
   return launch_status();
 }
 
-template <bool UNI>
+template <int CWS>
 qgtc_status dispatch(const AggParams& p, hipStream_t stream) {
   switch (p.s) {
-    case 1: return launch<1, UNI, false>(p, stream);
-    case 2: return launch<2, UNI, false>(p, stream);
-    case 3: return launch<3, UNI, false>(p, stream);
-    case 4: return launch<4, UNI, false>(p, stream);
-    case 5: return launch<5, UNI, false>(p, stream);
-    case 6: return launch<6, UNI, false>(p, stream);
-    case 7: return launch<7, UNI, false>(p, stream);
-    case 8: return launch<8, UNI, false>(p, stream);
-    default: return launch<8, UNI, true>(p, stream);
+    case 1: return launch<1, CWS, false>(p, stream);
+    case 2: return launch<2, CWS, false>(p, stream);
+    case 3: return launch<3, CWS, false>(p, stream);
+    case 4: return launch<4, CWS, false>(p, stream);
+    case 5: return launch<5, CWS, false>(p, stream);
+    case 6: return launch<6, CWS, false>(p, stream);
+    case 7: return launch<7, CWS, false>(p, stream);
+    case 8: return launch<8, CWS, false>(p, stream);
+    default: return launch<8, CWS, true>(p, stream);
   }
 }
 
@@ -445,5 +481,6 @@ extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* m
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_AGGREGATE, s);
-  return p.cw_shift == 6 ? dispatch<true>(p, s) : dispatch<false>(p, s);
+  if (p.cw_shift == 6) return dispatch<6>(p, s);
+  return p.cw_shift == 5 ? dispatch<5>(p, s) : dispatch<4>(p, s);
 }

@@ -83,8 +83,9 @@ __device__ __forceinline__ uint32_t requantize_i32(uint32_t c_u32, const EpiPara
                                                    uint32_t qmax, float qmaxf) {
   int32_t c = (int32_t)c_u32;
   if (e.relu && c < 0) c = 0;
-  const int64_t d = (int64_t)c - (int64_t)e.rq_lo;
-  const uint32_t du = d > 0 ? (uint32_t)d : 0u;   // d < 2^32
+  // max(c - rq_lo, 0) as an exact 64-bit difference: it is below 2^32, and when
+  // c > rq_lo the wrapped 32-bit subtraction is that difference
+  const uint32_t du = c > e.rq_lo ? (uint32_t)c - (uint32_t)e.rq_lo : 0u;
   const float f = (float)du;                      // round to nearest even
   const float t = floorf(f * e.rq_inv_scale);
   if (t >= qmaxf) return qmax;
