@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--bits", type=int, default=8)
     ap.add_argument("--tile-kbits", type=int, default=128)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a 1 GiB device-to-device copy 5 times (reference point for "
+                         "the FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path "
@@ -92,6 +95,15 @@ def main():
     from workloads import make_workload
 
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": src.numel() * 4, "copies": 5}))
+        return
     w = make_workload(args.config, bits=args.bits)
     g = w.graph
     A_src = torch.from_numpy(g.dense_compact() if w.storage == "compact" else g.dense()).cuda()
