@@ -39,17 +39,22 @@ __global__ __launch_bounds__(256) void pack_right_kernel(const PackParams p) {
   const int w = blockIdx.y * 4 + (threadIdx.x >> 6);
   const int n_wr = (p.rows + 31) >> 5;
   if (c >= p.cols || w >= n_wr) return;
+  // all 32 loads of the word are issued before the first one is used
+  uint32_t q[32];
+#pragma unroll
+  for (int b = 0; b < 32; ++b) {
+    const int r = w * 32 + b;
+    q[b] = r < p.rows ? fetch<SRC>(p, (int64_t)r * p.ld_src + c) : 0u;
+  }
   for (int p0 = 0; p0 < p.nbits; p0 += 8) {
     uint32_t out[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) out[i] = 0u;
-#pragma unroll 8
-    for (int b = 0; b < 32; ++b) {
-      const int r = w * 32 + b;
-      uint32_t q = 0u;
-      if (r < p.rows) q = fetch<SRC>(p, (int64_t)r * p.ld_src + c) >> p0;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) out[i] |= ((q >> i) & 1u) << b;
+    for (int b = 0; b < 32; ++b) {
+      const uint32_t v = q[b] >> p0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) out[i] |= ((v >> i) & 1u) << b;
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -83,6 +88,37 @@ __global__ __launch_bounds__(256) void pack_left_kernel(const PackParams p) {
       }
       if (w0 + lane < n_words) drow[w0 + lane] = mine;
     }
+  }
+}
+
+// Fast path for a 0/1 byte matrix into one plane (the adjacency): every lane
+// loads 16 consecutive bytes, squeezes them into 16 bits, neighbouring lanes
+// merge their halves with a DPP shift, and the even lanes store finished words.
+// Needs cols and ld_src multiples of 16 and a 16-byte aligned source.
+__device__ __forceinline__ uint32_t squeeze4(uint32_t d) {
+  uint32_t t = d & 0x01010101u;     // bit 0 of each byte
+  t |= t >> 7;                      // bytes 0,1 -> bits 0,1 ; bytes 2,3 -> bits 16,17
+  t |= t >> 14;                     // -> bits 0..3
+  return t & 0xfu;
+}
+
+__global__ __launch_bounds__(256) void pack_left_u8_kernel(const PackParams p) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= p.rows) return;                       // whole wave
+  const uint8_t* srow = reinterpret_cast<const uint8_t*>(p.src) + (int64_t)r * p.ld_src;
+  uint32_t* drow = p.dst + (int64_t)r * p.ld;
+  const int n_words = (int)p.ld;
+  for (int w0 = 0; w0 < n_words; w0 += 32) {     // 32 words = 1024 columns per pass
+    const int c = w0 * 32 + lane * 16;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (c < p.cols) v = *reinterpret_cast<const uint4*>(srow + c);
+    uint32_t h = squeeze4(v.x) | (squeeze4(v.y) << 4) | (squeeze4(v.z) << 8) | (squeeze4(v.w) << 12);
+    // odd lane's half moves down to the even lane (wave shift left by one lane)
+    const uint32_t up = (uint32_t)__shfl_down((int)h, 1, 64);
+    const uint32_t word = h | (up << 16);
+    const int w = w0 + (lane >> 1);
+    if ((lane & 1) == 0 && w < n_words) drow[w] = word;
   }
 }
 
@@ -131,6 +167,21 @@ __global__ __launch_bounds__(256) void row_sums_kernel(const UnpackParams p, int
   if (lane == 0) out[r] = (int32_t)acc;
 }
 
+// Same for short rows (a few words): one thread per row.
+__global__ __launch_bounds__(256) void row_sums_short_kernel(const UnpackParams p, int32_t* out) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= p.rows) return;
+  const int n_words = (p.cols + 31) >> 5;
+  uint32_t acc = 0u;
+  for (int i = 0; i < p.nbits; ++i) {
+    const uint32_t* row = p.src + (int64_t)i * p.ps + (int64_t)r * p.ld;
+    uint32_t cnt = 0u;
+    for (int w = 0; w < n_words; ++w) cnt += __builtin_popcount(row[w]);
+    acc += cnt << i;
+  }
+  out[r] = (int32_t)acc;
+}
+
 // sum_p 2^p popcount(column c of plane p): thread per column.
 __global__ __launch_bounds__(256) void col_sums_kernel(const UnpackParams p, int32_t* out) {
   const int c = blockIdx.x * 256 + threadIdx.x;
@@ -150,6 +201,9 @@ qgtc_status launch_pack(const PackParams& p, int layout, hipStream_t s) {
   if (layout == QGTC_RIGHT) {
     dim3 grid((unsigned)cdiv(p.cols, 64), (unsigned)cdiv(cdiv(p.rows, 32), 4));
     hipLaunchKernelGGL((pack_right_kernel<SRC>), grid, dim3(256), 0, s, p);
+  } else if (SRC == QGTC_SRC_U8 && p.nbits == 1 && (p.cols & 15) == 0 && (p.ld_src & 15) == 0 &&
+             ((uintptr_t)p.src & 15u) == 0) {
+    hipLaunchKernelGGL(pack_left_u8_kernel, dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p);
   } else {
     hipLaunchKernelGGL((pack_left_kernel<SRC>), dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p);
   }
@@ -238,7 +292,10 @@ extern "C" qgtc_status qgtc_row_sums(const qgtc_bits* m, int32_t* out, void* str
   UnpackParams p = unpack_params(m);
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_SUMS, s);
-  hipLaunchKernelGGL(row_sums_kernel, dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p, out);
+  if (p.cols <= 256)
+    hipLaunchKernelGGL(row_sums_short_kernel, dim3((unsigned)cdiv(p.rows, 256)), dim3(256), 0, s, p, out);
+  else
+    hipLaunchKernelGGL(row_sums_kernel, dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p, out);
   return launch_status();
 }
 

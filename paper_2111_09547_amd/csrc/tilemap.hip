@@ -52,6 +52,54 @@ __global__ __launch_bounds__(256) void tile_list_kernel(const MapParams p) {
   if (lane == 0) p.row_cnt[tr] = count;
 }
 
+// The shape the aggregation kernel uses (16 rows x 32/64/128 bits): one wave per
+// tile row, lane <-> (row = lane % 16, one of four consecutive tile columns =
+// lane / 16), each row read once, 4..16 bytes per load.  A ballot over the wave
+// tells which of the four tiles hold a bit; the same pass counts the degrees.
+__global__ __launch_bounds__(256) void tile_list16_kernel(const MapParams p) {
+  const int lane = threadIdx.x & 63;
+  const int tr = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tr >= p.n_tile_rows) return;               // whole wave
+  const int r = tr * 16 + (lane & 15);
+  const int g = lane >> 4;
+  const bool r_ok = r < p.rows;
+  const uint32_t* row = p.A + (int64_t)(r_ok ? r : 0) * p.lda;
+  int32_t* list = p.col_idx + (int64_t)tr * p.n_tile_cols;
+  int count = 0;
+  int deg = 0;
+  for (int tc0 = 0; tc0 < p.n_tile_cols; tc0 += 4) {
+    const int tc = tc0 + g;
+    uint32_t any = 0u;
+    if (r_ok && tc < p.n_tile_cols) {
+      const int w0 = tc * p.tile_words;
+      if (p.tile_words == 4) {                   // rows are padded to 128 bits
+        const uint4 v = *reinterpret_cast<const uint4*>(row + w0);
+        any = v.x | v.y | v.z | v.w;
+        deg += __builtin_popcount(v.x) + __builtin_popcount(v.y) + __builtin_popcount(v.z) +
+               __builtin_popcount(v.w);
+      } else {
+        for (int w = w0; w < w0 + p.tile_words; ++w) {
+          const uint32_t v = row[w];
+          any |= v;
+          deg += __builtin_popcount(v);
+        }
+      }
+    }
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(any != 0u);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (((m >> (16 * k)) & 0xffffull) != 0ull) {   // wave-uniform
+        if (lane == 0) list[count] = tc0 + k;
+        ++count;
+      }
+    }
+  }
+  deg += __shfl_xor(deg, 16, 64);
+  deg += __shfl_xor(deg, 32, 64);
+  if (lane < 16 && r_ok) p.deg[r] = deg;
+  if (lane == 0) p.row_cnt[tr] = count;
+}
+
 // Total number of non-zero tiles: one workgroup, no atomics.
 __global__ __launch_bounds__(256) void tile_total_kernel(const MapParams p) {
   __shared__ int part[256];
@@ -146,13 +194,17 @@ extern "C" qgtc_status qgtc_build_tile_map(const qgtc_bits* A, const qgtc_tile_m
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_TILE_MAP, s);
+  const bool fused = p.tile_rows == 16 && p.tile_words <= 4;
   if (p.n_tile_rows > 0 && p.n_tile_cols > 0) {
-    hipLaunchKernelGGL(tile_list_kernel, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p);
+    if (fused)
+      hipLaunchKernelGGL(tile_list16_kernel, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p);
+    else
+      hipLaunchKernelGGL(tile_list_kernel, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p);
     if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
   }
   hipLaunchKernelGGL(tile_total_kernel, dim3(1), dim3(256), 0, s, p);
   if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
-  if (p.rows > 0) {
+  if (p.rows > 0 && !(fused && p.n_tile_rows > 0 && p.n_tile_cols > 0)) {
     hipLaunchKernelGGL(degree_kernel, dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p);
     if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
   }

@@ -19,6 +19,8 @@
 namespace qgtc {
 namespace {
 
+#include "popc_blocks.inc"
+
 struct UpdParams {
   const uint32_t* Y;
   int64_t ldy, psy;       // words between rows / planes of Y
@@ -38,7 +40,7 @@ struct UpdParams {
 template <int B, int KC>
 __global__ __launch_bounds__(256) void update_kernel(const UpdParams p) {
   extern __shared__ uint32_t wl[];                  // [hc][n_wc*B][n_kc*KC], zero padded
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int lane = threadIdx.x & 63;
   const int rw = blockIdx.x * 4 + wave;             // 64-row group of this wave
   const int row0 = rw * 64;
@@ -85,6 +87,11 @@ __global__ __launch_bounds__(256) void update_kernel(const UpdParams p) {
   const int qbits = e.rq_nbits;
   const uint32_t qmax = qbits >= 32 ? 0xffffffffu : ((1u << qbits) - 1u);
   const float qmaxf = (float)qmax;
+  // low-bit output with at most B planes: ballot words are gathered in lanes
+  const bool fast_bits = e.mode == QGTC_OUT_BITS && qbits <= B;
+  uint32_t ow_lo[B], ow_hi[B];
+#pragma unroll
+  for (int i = 0; i < B; ++i) { ow_lo[i] = 0u; ow_hi[i] = 0u; }
 
   for (int h = h_begin; h < h_end; ++h) {
     const uint32_t* wcol = wl + (h - h_begin) * wp * wk;
@@ -127,13 +134,42 @@ __global__ __launch_bounds__(256) void update_kernel(const UpdParams p) {
       // RIGHT layout for the next aggregation: 32 consecutive rows per word, so a
       // ballot over the lanes is two finished words of column h.
       const uint32_t q = row_ok ? requantize_i32(z, e, qmax, qmaxf) : 0u;
-      const int wr = (row0 >> 5) + (lane & 1);
-      const bool st = lane < 2 && wr < ((p.rows + 31) >> 5);
-      uint32_t* dst = reinterpret_cast<uint32_t*>(e.out) + (st ? (int64_t)wr * e.ld_out + h : 0);
-      for (int i = 0; i < qbits; ++i) {
-        const unsigned long long m = __builtin_amdgcn_ballot_w64(((q >> i) & 1u) != 0u);
-        const uint32_t word = (lane & 1) ? (uint32_t)(m >> 32) : (uint32_t)m;
-        if (st) dst[(int64_t)i * e.ps_out] = word;
+      if (fast_bits) {
+        // keep them in lane (h - h_begin) until the whole column run is done
+        uint32_t lo[B], hi[B];
+#pragma unroll
+        for (int i = 0; i < B; ++i) {
+          const unsigned long long m = __builtin_amdgcn_ballot_w64(((q >> i) & 1u) != 0u);
+          lo[i] = (uint32_t)m;
+          hi[i] = (uint32_t)(m >> 32);
+        }
+        lane_pack_m0<B>::run(lo, hi, ow_lo, ow_hi, (h - h_begin) & 63);
+        if (((h - h_begin) & 63) == 63 || h + 1 == h_end) {
+          // flush: lane l holds the words of column h0 + l
+          const int h0 = h - ((h - h_begin) & 63);
+          const int hh = h0 + lane;
+          const int wr0 = row0 >> 5;
+          const int n_wr = (p.rows + 31) >> 5;
+          if (hh <= h) {
+            uint32_t* dst = reinterpret_cast<uint32_t*>(e.out) + (int64_t)wr0 * e.ld_out + hh;
+#pragma unroll
+            for (int i = 0; i < B; ++i) {
+              if (i < qbits) {
+                dst[(int64_t)i * e.ps_out] = ow_lo[i];
+                if (wr0 + 1 < n_wr) dst[(int64_t)i * e.ps_out + e.ld_out] = ow_hi[i];
+              }
+            }
+          }
+        }
+      } else {
+        const int wr = (row0 >> 5) + (lane & 1);
+        const bool st = lane < 2 && wr < ((p.rows + 31) >> 5);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(e.out) + (st ? (int64_t)wr * e.ld_out + h : 0);
+        for (int i = 0; i < qbits; ++i) {
+          const unsigned long long m = __builtin_amdgcn_ballot_w64(((q >> i) & 1u) != 0u);
+          const uint32_t word = (lane & 1) ? (uint32_t)(m >> 32) : (uint32_t)m;
+          if (st) dst[(int64_t)i * e.ps_out] = word;
+        }
       }
     }
   }

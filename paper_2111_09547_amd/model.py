@@ -71,7 +71,8 @@ class QuantGNN:
             self.deg = B.qgtc_row_sums(self.A)
         for W, r, dst in zip(self.Ws, self.w_ranges, self.W):
             B.qgtc_pack_bits(W, self.t, B.RIGHT, quant=r, out=dst)
-        self.w_colsum = [B.qgtc_col_sums(w) for w in self.W]
+        # only the last layer dequantizes, so only its column sums are needed
+        self.w_colsum = [None] * (len(self.W) - 1) + [B.qgtc_col_sums(self.W[-1])]
 
     # -- helpers -----------------------------------------------------------------
     def _x_view(self, which: int, cols: int) -> B.Bits:
