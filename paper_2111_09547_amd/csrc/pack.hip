@@ -19,15 +19,29 @@ struct PackParams {
   float qmaxf;
 };
 
+template <int SRC> struct src_type { using type = uint32_t; };
+template <> struct src_type<QGTC_SRC_F32> { using type = float; };
+template <> struct src_type<QGTC_SRC_U8> { using type = uint8_t; };
+
+// Raw element (the load) and its code (Eq. (2) or masking) are kept apart so
+// that many loads can be in flight before the first conversion.
+template <int SRC>
+__device__ __forceinline__ typename src_type<SRC>::type fetch_raw(const PackParams& p, int64_t idx) {
+  return reinterpret_cast<const typename src_type<SRC>::type*>(p.src)[idx];
+}
+
+template <int SRC>
+__device__ __forceinline__ uint32_t to_code(const PackParams& p, typename src_type<SRC>::type v) {
+  if constexpr (SRC == QGTC_SRC_F32) {
+    return quantize_f32(v, p.lo, p.inv, p.qmax, p.qmaxf);
+  } else {
+    return (uint32_t)v & p.qmax;
+  }
+}
+
 template <int SRC>
 __device__ __forceinline__ uint32_t fetch(const PackParams& p, int64_t idx) {
-  if constexpr (SRC == QGTC_SRC_F32) {
-    return quantize_f32(reinterpret_cast<const float*>(p.src)[idx], p.lo, p.inv, p.qmax, p.qmaxf);
-  } else if constexpr (SRC == QGTC_SRC_U8) {
-    return (uint32_t) reinterpret_cast<const uint8_t*>(p.src)[idx] & p.qmax;
-  } else {
-    return reinterpret_cast<const uint32_t*>(p.src)[idx] & p.qmax;
-  }
+  return to_code<SRC>(p, fetch_raw<SRC>(p, idx));
 }
 
 // RIGHT layout: 32 consecutive ROWS of one column share a word.
@@ -40,12 +54,15 @@ __global__ __launch_bounds__(256) void pack_right_kernel(const PackParams p) {
   const int n_wr = (p.rows + 31) >> 5;
   if (c >= p.cols || w >= n_wr) return;
   // all 32 loads of the word are issued before the first one is used
-  uint32_t q[32];
+  typename src_type<SRC>::type raw[32];
 #pragma unroll
   for (int b = 0; b < 32; ++b) {
-    const int r = w * 32 + b;
-    q[b] = r < p.rows ? fetch<SRC>(p, (int64_t)r * p.ld_src + c) : 0u;
+    const int r = min(w * 32 + b, p.rows - 1);          // clamped: no branch around the load
+    raw[b] = fetch_raw<SRC>(p, (int64_t)r * p.ld_src + c);
   }
+  uint32_t q[32];
+#pragma unroll
+  for (int b = 0; b < 32; ++b) q[b] = (w * 32 + b < p.rows) ? to_code<SRC>(p, raw[b]) : 0u;
   for (int p0 = 0; p0 < p.nbits; p0 += 8) {
     uint32_t out[8];
 #pragma unroll
