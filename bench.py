@@ -153,6 +153,21 @@ def main():
     q.qgtc_prof_enable(False)
     q.qgtc_prof_reset()
 
+    # the update alone on both of its kernels (popcount on the vector ALUs vs int8 matrix cores)
+    upd_paths = {}
+    for name, path in (("popcount", q.UPDATE_POPCOUNT), ("matrix_cores", q.UPDATE_MATRIX_CORES)):
+        q.qgtc_set_option(q.OPT_UPDATE_PATH, path)
+        layers_only()
+        q.qgtc_prof_enable(True)
+        q.qgtc_prof_reset()
+        for _ in range(20):
+            layers_only()
+        torch.cuda.synchronize()
+        upd_paths[name + "_ms_per_step"] = q.qgtc_prof_read(q.KERNEL_UPDATE)[0] / 20
+        q.qgtc_prof_enable(False)
+        q.qgtc_prof_reset()
+    q.qgtc_set_option(q.OPT_UPDATE_PATH, q.UPDATE_AUTO)
+
     agg_ops, upd_ops, nnz = workload_bitops(net, g.n_nodes, args.tile_kbits)
     total_ops = sum(agg_ops) + sum(upd_ops)
     agg_ms, agg_n = prof["aggregate"]
@@ -186,8 +201,9 @@ def main():
                      "traffic": None},
         "kernels": {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps}
                     for k, v in prof.items()},
-        "update_roofline": {"bound": "alu", "achieved": upd_rate / 1e12,
-                            "peak": PEAK_BITOPS / 1e12, "frac": upd_rate / PEAK_BITOPS},
+        "update": {"path": "int8 matrix cores (automatic choice for s*t >= 4, s,t <= 8)"
+                           if w.s * w.t >= 4 and w.s <= 8 and w.t <= 8 else "popcount",
+                   "bit_ops_equiv_rate": upd_rate / 1e12, "unit": "Tbit-op/s", **upd_paths},
     }
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w, ranges, total_ops)

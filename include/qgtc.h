@@ -247,6 +247,21 @@ qgtc_status qgtc_prof_enable(int32_t on);
 qgtc_status qgtc_prof_reset(void);
 qgtc_status qgtc_prof_read(int32_t kind, double* total_ms, int64_t* launches);
 
+/* ---------------------------------------------------------------------------
+ * Library options (process-wide, not thread-safe against running calls).
+ * QGTC_OPT_UPDATE_PATH: which kernel qgtc_update (and qgtc_layer) uses when both
+ * operands have at most 8 bits.  The paper composes every product from 1-bit
+ * products (Section 3.1) because its matrix unit is 1-bit; CDNA4's matrix cores
+ * start at int8, where one instruction covers up to 8 x 8 bit planes, so the
+ * update can re-assemble the planes into bytes in registers and run there.  Both
+ * paths give the same integers.
+ *   0  automatic: matrix cores where they were measured faster (default)
+ *   1  popcount kernel only
+ *   2  matrix cores whenever the operands fit
+ * ------------------------------------------------------------------------- */
+enum { QGTC_OPT_UPDATE_PATH = 0 };
+qgtc_status qgtc_set_option(int32_t option, int32_t value);
+
 /* Library version, major*10000 + minor*100 + patch. */
 int32_t qgtc_version(void);
 

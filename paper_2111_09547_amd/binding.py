@@ -90,6 +90,7 @@ def lib():
         "qgtc_layer_workspace_bytes": (sz, [i32, i32, i32]),
         "qgtc_layer": (C.c_int, [P(_BitsC), P(_TileMapC), P(_BitsC), P(_BitsC), P(_EpilogueC),
                                  P(_EpilogueC), vp, sz, vp, i64, vp]),
+        "qgtc_set_option": (C.c_int, [i32, i32]),
         "qgtc_prof_enable": (C.c_int, [i32]),
         "qgtc_prof_reset": (C.c_int, []),
         "qgtc_prof_read": (C.c_int, [i32, P(C.c_double), P(i64)]),
@@ -303,6 +304,14 @@ def qgtc_layer(A: Bits, tmap: TileMap | None, X: Bits, W: Bits, agg_ep: Epilogue
                             C.c_void_p(workspace.data_ptr()), workspace.numel() * 4, ptr, ld,
                             _stream()), "qgtc_layer")
     return res
+
+
+OPT_UPDATE_PATH = 0
+UPDATE_AUTO, UPDATE_POPCOUNT, UPDATE_MATRIX_CORES = 0, 1, 2
+
+
+def qgtc_set_option(option: int, value: int):
+    _check(lib().qgtc_set_option(option, value), "qgtc_set_option")
 
 
 def qgtc_prof_enable(on: bool):

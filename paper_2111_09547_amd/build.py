@@ -13,7 +13,7 @@ LIB_DIR = os.path.join(PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libqgtc.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["api.hip", "pack.hip", "tilemap.hip", "aggregate.hip", "update.hip"]
+SOURCES = ["api.hip", "pack.hip", "tilemap.hip", "aggregate.hip", "update.hip", "update_mfma.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
@@ -23,6 +23,7 @@ HIPCC_FLAGS = [
     # no compiler-generated packed fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    "-Wno-inline-asm",   # M0 (lane select of v_writelane) is named as clobbered on purpose
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

@@ -186,7 +186,7 @@ __device__ __forceinline__ void pack_rows_fast(const uint32_t (&q)[16], uint32_t
 }
 
 template <int S, int CWS, bool MULTI>
-__global__ __launch_bounds__(256) void aggregate_kernel(const AggParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void aggregate_kernel(const AggParams p) {
   constexpr bool UNI = CWS == 6;
   extern __shared__ uint32_t lds[];   // [ksplit][16][64] partial sums when ksplit > 1
 

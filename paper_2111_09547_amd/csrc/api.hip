@@ -88,6 +88,12 @@ qgtc_status make_epilogue(const qgtc_epilogue* ep, void* out, int64_t ld_out, in
   return QGTC_OK;
 }
 
+// ---- library options ---------------------------------------------------------------
+namespace {
+int g_update_path = 0;
+}
+int update_path_option() { return g_update_path; }
+
 // ---- event-based kernel timing ------------------------------------------------
 namespace {
 struct Span {
@@ -146,7 +152,16 @@ extern "C" const char* qgtc_status_string(qgtc_status s) {
   return "unknown status";
 }
 
-extern "C" int32_t qgtc_version(void) { return 100; }
+extern "C" int32_t qgtc_version(void) { return 101; }
+
+extern "C" qgtc_status qgtc_set_option(int32_t option, int32_t value) {
+  if (option == QGTC_OPT_UPDATE_PATH) {
+    if (value < 0 || value > 2) return QGTC_ERR_UNSUPPORTED;
+    g_update_path = value;
+    return QGTC_OK;
+  }
+  return QGTC_ERR_UNSUPPORTED;
+}
 
 extern "C" size_t qgtc_describe(qgtc_bits* d, int32_t rows, int32_t cols, int32_t nbits, int32_t layout,
                                 int32_t block_rows) {

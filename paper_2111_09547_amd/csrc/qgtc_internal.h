@@ -57,6 +57,29 @@ qgtc_status make_epilogue(const qgtc_epilogue* ep, void* out, int64_t ld_out,
                           int rows, int cols, int bits_layout, bool allow_self,
                           EpiParams* p);
 
+// Arguments of the update kernels (popcount and int8-MFMA variants).
+struct UpdParams {
+  const uint32_t* Y;
+  int64_t ldy, psy;       // words between rows / planes of Y
+  int32_t rows;           // rows of Y (= output rows)
+  int32_t s;              // planes of Y
+  int32_t kwords;         // 32-bit words along the contraction dimension
+  const uint32_t* W;
+  int64_t ldw, psw;       // words between word rows / planes of W
+  int32_t t;              // planes of W
+  int32_t cols;           // columns of W (= output columns)
+  int32_t hc;             // output columns per wave
+  int32_t n_row_waves;
+  EpiParams ep;
+};
+
+
+// int8 matrix-core variant of the update for s, t <= 8 (update_mfma.hip).
+bool update_mfma_eligible(const UpdParams& p);
+qgtc_status update_mfma_launch(const UpdParams& p, hipStream_t stream);
+// 0 = choose by measured crossover, 1 = popcount only, 2 = matrix cores whenever eligible
+int update_path_option();
+
 // ---- device side -------------------------------------------------------------
 #if defined(__HIPCC__)
 

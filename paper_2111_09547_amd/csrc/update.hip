@@ -21,21 +21,6 @@ namespace {
 
 #include "popc_blocks.inc"
 
-struct UpdParams {
-  const uint32_t* Y;
-  int64_t ldy, psy;       // words between rows / planes of Y
-  int32_t rows;           // rows of Y (= output rows)
-  int32_t s;              // planes of Y
-  int32_t kwords;         // 32-bit words along the contraction dimension
-  const uint32_t* W;
-  int64_t ldw, psw;       // words between word rows / planes of W
-  int32_t t;              // planes of W
-  int32_t cols;           // columns of W (= output columns)
-  int32_t hc;             // output columns per wave
-  int32_t n_row_waves;
-  EpiParams ep;
-};
-
 // B = planes handled per chunk (both operands), KC = words of K kept in registers.
 template <int B, int KC>
 __global__ __launch_bounds__(256) void update_kernel(const UpdParams p) {
@@ -237,6 +222,11 @@ extern "C" qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W, const
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_UPDATE, s);
+  // int8 matrix cores when the operands fit in bytes.  Measured on MI355X, they
+  // win from 2 x 2 bits upwards; 1-bit x 1-bit stays on the popcount kernel.
+  const int path = update_path_option();
+  if (path != 1 && update_mfma_eligible(p) && (path == 2 || Y->nbits * W->nbits >= 4))
+    return update_mfma_launch(p, s);
   const int b = Y->nbits > W->nbits ? Y->nbits : W->nbits;
   switch (b) {
     case 1: return dispatch_k<1>(p, hsplit, s);

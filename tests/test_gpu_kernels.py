@@ -243,3 +243,41 @@ def test_layer_matches_oracle(cfg, bits, nb):
     # running twice gives the same bytes (no races)
     again = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32))
     assert torch.equal(got, again)
+
+
+# ------------------------------------------------- update on the matrix cores
+@pytest.mark.parametrize("st", [(1, 1), (2, 3), (4, 4), (7, 7), (8, 8), (8, 2), (3, 8), (8, 7)])
+@pytest.mark.parametrize("shape", [(100, 64, 64), (257, 128, 16), (70, 40, 5), (1000, 512, 16), (64, 300, 70),
+                                   (4096, 64, 64), (33, 16, 130)])
+def test_update_matrix_core_path_equals_popcount_and_oracle(st, shape):
+    s, t = st
+    n, d, h = shape
+    rng = np.random.default_rng([11, s, t, n])
+    Yq = rng.integers(0, 2 ** s, size=(n, d), dtype=np.uint64).astype(np.uint32)
+    Wq = rng.integers(0, 2 ** t, size=(d, h), dtype=np.uint64).astype(np.uint32)
+    Yq[0, :] = 2 ** s - 1                      # extreme codes (top bit set at 8 bits)
+    Wq[:, 0] = 2 ** t - 1
+    Yb = q.qgtc_pack_bits(dev(Yq.view(np.int32)), s, q.LEFT)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    Z = qgnn.update(Yq, Wq)
+    inv = qgnn.inv_scale(0.0, float(Z.max()), 5)
+    rs = Yq.sum(axis=1).astype(np.int32)
+    cs = Wq.sum(axis=0).astype(np.int32)
+    kw = dict(cc=1.7e-3, rs=-0.031, l0a=0.4, l0b=-0.9, ck=-6.4, cs=0.0125)
+    outs = {}
+    try:
+        for path in (q.UPDATE_POPCOUNT, q.UPDATE_MATRIX_CORES):
+            q.qgtc_set_option(q.OPT_UPDATE_PATH, path)
+            z = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_I32))
+            bits = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=5, rq_lo=0,
+                                                    rq_inv_scale=float(inv)))
+            f = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_F32, row_i=dev(rs), row_l=dev(rs),
+                                                 col_i=dev(cs), **kw))
+            outs[path] = (as_u32(z), words_np(bits), f.cpu().numpy())
+    finally:
+        q.qgtc_set_option(q.OPT_UPDATE_PATH, q.UPDATE_AUTO)
+    for path, (z, bits, f) in outs.items():
+        assert (z == Z).all(), path
+        assert (bits == bp.pack(qgnn.requantize(Z, 0, inv, 5, relu=True), 5, bp.RIGHT)).all(), path
+        ref = qgnn.dequantize(Z, row_i=rs, row_l=rs, col_i=cs, **kw)
+        assert np.allclose(f, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max()), path
