@@ -258,8 +258,16 @@ qgtc_status qgtc_prof_read(int32_t kind, double* total_ms, int64_t* launches);
  *   0  automatic: matrix cores where they were measured faster (default)
  *   1  popcount kernel only
  *   2  matrix cores whenever the operands fit
+ * QGTC_OPT_AGG_XCD_RUN: how qgtc_aggregate deals its workgroups to the 8 XCDs
+ * (each with an L2 of its own).  Runs of `value` consecutive tile rows (all their
+ * column groups) go to one XCD, the next run to the next XCD.  Short runs balance
+ * graphs whose tiles are concentrated in a few subgraphs; long runs keep one
+ * subgraph's X panel in one L2.  Results do not depend on it.
+ *   0   default (8 tile rows)
+ *   >0  that many tile rows (rounded up to a power of two of workgroups)
+ *   <0  one contiguous range per XCD
  * ------------------------------------------------------------------------- */
-enum { QGTC_OPT_UPDATE_PATH = 0 };
+enum { QGTC_OPT_UPDATE_PATH = 0, QGTC_OPT_AGG_XCD_RUN = 1 };
 qgtc_status qgtc_set_option(int32_t option, int32_t value);
 
 /* Library version, major*10000 + minor*100 + patch. */

@@ -307,6 +307,7 @@ def qgtc_layer(A: Bits, tmap: TileMap | None, X: Bits, W: Bits, agg_ep: Epilogue
 
 
 OPT_UPDATE_PATH = 0
+OPT_AGG_XCD_RUN = 1
 UPDATE_AUTO, UPDATE_POPCOUNT, UPDATE_MATRIX_CORES = 0, 1, 2
 
 

@@ -45,6 +45,7 @@ struct AggParams {
   int32_t n_cg;           // column groups
   int32_t n_rt;           // groups of 64/CW row tiles
   int32_t ksplit;         // waves per workgroup
+  int32_t chunk_shift;    // log2 of the run of consecutive workgroups one XCD takes
   uint32_t nblocks;
   EpiParams ep;
 };
@@ -190,8 +191,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
   constexpr bool UNI = CWS == 6;
   extern __shared__ uint32_t lds[];   // [ksplit][16][64] partial sums when ksplit > 1
 
-  const unsigned grid = gridDim.x;
-  const unsigned bid = xcd_remap(blockIdx.x, grid);
+  const unsigned bid = xcd_deal(blockIdx.x, p.chunk_shift);
   if (bid >= p.nblocks) return;       // whole workgroup leaves together
   const int rt = (int)(bid / (unsigned)p.n_cg);
   const int cg = (int)(bid % (unsigned)p.n_cg);
@@ -393,7 +393,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
 
 template <int S, int CWS, bool MULTI>
 qgtc_status launch(const AggParams& p, hipStream_t stream) {
-  const unsigned grid = xcd_grid(p.nblocks);
+  const unsigned grid = xcd_deal_grid(p.nblocks, p.chunk_shift);
   const size_t lds = p.ksplit > 1 ? (size_t)p.ksplit * 16 * 64 * sizeof(uint32_t) : 0;
   hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
   return launch_status();
@@ -478,6 +478,20 @@ extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* m
   p.nblocks = (uint32_t)p.n_cg * (uint32_t)p.n_rt;
   // few waves: let the four waves of a workgroup split each tile list
   p.ksplit = p.nblocks >= 4096u ? 1 : 4;
+  // Each XCD takes runs of `chunk` consecutive workgroups, run k going to XCD
+  // k % 8.  A run covers all column groups of a few neighbouring tile rows, which
+  // read the same word rows of X from the XCD's L2 (with few tiles per row these
+  // are the diagonal tiles); dealing short runs round-robin spreads the rows of
+  // one subgraph over all XCDs, so a subgraph that holds far more tiles than the
+  // others (the hubs of a power-law graph) does not leave seven XCDs idle.
+  {
+    const int opt = agg_chunk_option();
+    int64_t chunk = (int64_t)(opt > 0 ? opt : 8) * p.n_cg;
+    if (opt < 0) chunk = (p.nblocks + 7u) / 8u;          // one run per XCD
+    int sh = 0;
+    while (((int64_t)1 << sh) < chunk && sh < 30) ++sh;
+    p.chunk_shift = sh;
+  }
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_AGGREGATE, s);

@@ -91,8 +91,10 @@ qgtc_status make_epilogue(const qgtc_epilogue* ep, void* out, int64_t ld_out, in
 // ---- library options ---------------------------------------------------------------
 namespace {
 int g_update_path = 0;
+int g_agg_chunk = 0;
 }
 int update_path_option() { return g_update_path; }
+int agg_chunk_option() { return g_agg_chunk; }
 
 // ---- event-based kernel timing ------------------------------------------------
 namespace {
@@ -158,6 +160,11 @@ extern "C" qgtc_status qgtc_set_option(int32_t option, int32_t value) {
   if (option == QGTC_OPT_UPDATE_PATH) {
     if (value < 0 || value > 2) return QGTC_ERR_UNSUPPORTED;
     g_update_path = value;
+    return QGTC_OK;
+  }
+  if (option == QGTC_OPT_AGG_XCD_RUN) {
+    if (value > 4096) return QGTC_ERR_UNSUPPORTED;
+    g_agg_chunk = value;
     return QGTC_OK;
   }
   return QGTC_ERR_UNSUPPORTED;

@@ -36,8 +36,12 @@ class ProfScope {
   hipStream_t stream_;
 };
 
-// Grid size padded to a multiple of the 8 XCDs, see xcd_remap().
-inline unsigned xcd_grid(unsigned nblocks) { return (nblocks + 7u) / 8u * 8u; }
+// Chunked dealing of workgroups to the XCDs: runs of 2^shift consecutive logical
+// ids share an XCD, run k lands on XCD k % 8.  Grid size for nblocks logical ids:
+inline unsigned xcd_deal_grid(unsigned nblocks, int shift) {
+  const unsigned runs = (nblocks + (1u << shift) - 1u) >> shift;
+  return ((runs + 7u) / 8u * 8u) << shift;
+}
 
 // Epilogue parameters as the kernels take them (device-visible copy).
 struct EpiParams {
@@ -79,16 +83,20 @@ bool update_mfma_eligible(const UpdParams& p);
 qgtc_status update_mfma_launch(const UpdParams& p, hipStream_t stream);
 // 0 = choose by measured crossover, 1 = popcount only, 2 = matrix cores whenever eligible
 int update_path_option();
+// tile rows per run of workgroups dealt to one XCD by the aggregation; 0 = default,
+// < 0 = one contiguous range per XCD
+int agg_chunk_option();
 
 // ---- device side -------------------------------------------------------------
 #if defined(__HIPCC__)
 
-// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  This
-// maps the hardware block id to a logical id such that consecutive logical ids
-// run on the same XCD, so neighbouring tiles share that XCD's L2.  The grid
-// must be xcd_grid(nblocks) wide; ids >= nblocks are to be dropped.
-__device__ __forceinline__ unsigned xcd_remap(unsigned bid, unsigned grid) {
-  return (bid & 7u) * (grid >> 3) + (bid >> 3);
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).
+// Logical id of hardware workgroup `bid` under xcd_deal_grid(); ids >= nblocks
+// are to be dropped.
+__device__ __forceinline__ unsigned xcd_deal(unsigned bid, int shift) {
+  const unsigned slot = bid >> 3;                    // position inside the XCD's queue
+  const unsigned run = ((slot >> shift) << 3) | (bid & 7u);
+  return (run << shift) | (slot & ((1u << shift) - 1u));
 }
 
 // Eq. (2) with the clamp; see qgtc_quant in qgtc.h.

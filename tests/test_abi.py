@@ -116,6 +116,17 @@ def test_argument_validation_happens_before_any_launch():
     assert l.qgtc_aggregate(C.byref(A), C.byref(m), C.byref(X), C.byref(ep), out, 16, None) == 7
 
 
+def test_options_are_range_checked():
+    import paper_2111_09547_amd.binding as b
+    l = b.lib()
+    assert l.qgtc_set_option(b.OPT_UPDATE_PATH, 3) == 7
+    assert l.qgtc_set_option(b.OPT_UPDATE_PATH, 0) == 0
+    assert l.qgtc_set_option(b.OPT_AGG_XCD_RUN, 5000) == 7
+    assert l.qgtc_set_option(b.OPT_AGG_XCD_RUN, -1) == 0
+    assert l.qgtc_set_option(b.OPT_AGG_XCD_RUN, 0) == 0
+    assert l.qgtc_set_option(99, 0) == 7
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     import paper_2111_09547_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)

@@ -130,6 +130,24 @@ def test_aggregate_int32_ragged(s, shape):
         assert (as_u32(got) == want).all(), kb
 
 
+@pytest.mark.parametrize("d", [16, 70, 200])
+def test_aggregate_does_not_depend_on_xcd_run(d):
+    """The way workgroups are dealt to the XCDs is a scheduling choice only."""
+    rng = np.random.default_rng([8, d])
+    n, s = 2100, 3                       # 132 tile rows: several runs per XCD and a ragged tail
+    A = rand_graph(rng, n, n, 0.01)
+    X = rng.integers(0, 2 ** s, size=(n, d)).astype(np.uint32)
+    want = qgnn.aggregate(A, X)
+    try:
+        for run in (-1, 0, 1, 3, 64, 4096):
+            q.qgtc_set_option(q.OPT_AGG_XCD_RUN, run)
+            for ep in (q.Epilogue(mode=q.OUT_I32), ):
+                got, _ = run_aggregate(A, X, s, 128, ep=ep)
+                assert (as_u32(got) == want).all(), run
+    finally:
+        q.qgtc_set_option(q.OPT_AGG_XCD_RUN, 0)
+
+
 @pytest.mark.parametrize("d", [16, 32, 64, 200])
 def test_aggregate_block_diagonal_compact_and_self_term(d):
     rng = np.random.default_rng([7, d])
