@@ -219,10 +219,22 @@ qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W,
                         const qgtc_epilogue* ep, void* out, int64_t ld_out,
                         void* stream);
 
-/* One layer: aggregate with agg_ep (must be QGTC_OUT_BITS) into packed planes
- * held in `workspace`, then update with upd_ep into out.
- * workspace: device, 16-byte aligned, at least qgtc_layer_workspace_bytes. */
-size_t qgtc_layer_workspace_bytes(int32_t rows, int32_t cols, int32_t nbits);
+/* One layer (Algorithm 1): aggregate, requantize the result to agg_ep->rq_nbits
+ * bits (agg_ep must be QGTC_OUT_BITS; its output is internal to the call), then
+ * update with upd_ep into out.
+ * When all operands have at most 8 bits, X has 33..1024 columns and W at most
+ * 256, the whole layer runs as ONE kernel (inter-layer fusion, Section 4.5,
+ * extended across the two products): the requantized aggregation tile goes
+ * through LDS as bytes straight into the int8 matrix cores.  Otherwise the
+ * call runs qgtc_aggregate into packed planes in `workspace`, then qgtc_update.
+ * Both give the same integers.
+ * upd_ep in QGTC_OUT_F32 mode: with row_i == NULL and rs != 0 the row sums of
+ * the requantized aggregation result (the left operand of the update, which only
+ * exists inside the call) are taken for row_i.
+ * workspace: device, 16-byte aligned, at least qgtc_layer_workspace_bytes(rows
+ * of A, columns of X, columns of W, agg_ep->rq_nbits) bytes. */
+size_t qgtc_layer_workspace_bytes(int32_t rows, int32_t in_cols, int32_t out_cols,
+                                  int32_t nbits);
 qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map,
                        const qgtc_bits* X, const qgtc_bits* W,
                        const qgtc_epilogue* agg_ep, const qgtc_epilogue* upd_ep,
@@ -241,7 +253,8 @@ enum {
   QGTC_KERNEL_AGGREGATE = 2,
   QGTC_KERNEL_UPDATE = 3,
   QGTC_KERNEL_SUMS = 4,
-  QGTC_KERNEL_KINDS = 5
+  QGTC_KERNEL_LAYER = 5, /* fused layer kernel (with its weight re-ordering) */
+  QGTC_KERNEL_KINDS = 6
 };
 qgtc_status qgtc_prof_enable(int32_t on);
 qgtc_status qgtc_prof_reset(void);
@@ -266,8 +279,17 @@ qgtc_status qgtc_prof_read(int32_t kind, double* total_ms, int64_t* launches);
  *   0   default (8 tile rows)
  *   >0  that many tile rows (rounded up to a power of two of workgroups)
  *   <0  one contiguous range per XCD
+ * QGTC_OPT_LAYER_PATH: 0 = qgtc_layer uses its fused kernel whenever it applies
+ * (default), 1 = always aggregate and update as two kernels.
+ * QGTC_OPT_LAYER_KSPLIT: waves of a workgroup of the fused kernel that split one
+ * tile list: 0 = automatic (more when the grid is small), 1, 2 or 4.
  * ------------------------------------------------------------------------- */
-enum { QGTC_OPT_UPDATE_PATH = 0, QGTC_OPT_AGG_XCD_RUN = 1 };
+enum {
+  QGTC_OPT_UPDATE_PATH = 0,
+  QGTC_OPT_AGG_XCD_RUN = 1,
+  QGTC_OPT_LAYER_PATH = 2,
+  QGTC_OPT_LAYER_KSPLIT = 3
+};
 qgtc_status qgtc_set_option(int32_t option, int32_t value);
 
 /* Library version, major*10000 + minor*100 + patch. */

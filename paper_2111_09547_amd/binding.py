@@ -15,7 +15,7 @@ import torch  # first: the HIP runtime PyTorch ships must be the one libqgtc bin
 LEFT, RIGHT = 0, 1
 SRC_F32, SRC_U8, SRC_I32 = 0, 1, 2
 OUT_I32, OUT_F32, OUT_BITS = 0, 1, 2
-KERNEL_PACK, KERNEL_TILE_MAP, KERNEL_AGGREGATE, KERNEL_UPDATE, KERNEL_SUMS = range(5)
+KERNEL_PACK, KERNEL_TILE_MAP, KERNEL_AGGREGATE, KERNEL_UPDATE, KERNEL_SUMS, KERNEL_LAYER = range(6)
 
 _STATUS = ["ok", "null pointer", "shape mismatch", "bit width out of range",
            "misaligned pointer or leading dimension", "wrong packed layout",
@@ -87,7 +87,7 @@ def lib():
         "qgtc_build_tile_map": (C.c_int, [P(_BitsC), P(_TileMapC), vp]),
         "qgtc_aggregate": (C.c_int, [P(_BitsC), P(_TileMapC), P(_BitsC), P(_EpilogueC), vp, i64, vp]),
         "qgtc_update": (C.c_int, [P(_BitsC), P(_BitsC), P(_EpilogueC), vp, i64, vp]),
-        "qgtc_layer_workspace_bytes": (sz, [i32, i32, i32]),
+        "qgtc_layer_workspace_bytes": (sz, [i32, i32, i32, i32]),
         "qgtc_layer": (C.c_int, [P(_BitsC), P(_TileMapC), P(_BitsC), P(_BitsC), P(_EpilogueC),
                                  P(_EpilogueC), vp, sz, vp, i64, vp]),
         "qgtc_set_option": (C.c_int, [i32, i32]),
@@ -295,7 +295,7 @@ def qgtc_update(Y: Bits, W: Bits, ep: Epilogue, out=None):
 def qgtc_layer(A: Bits, tmap: TileMap | None, X: Bits, W: Bits, agg_ep: Epilogue,
                upd_ep: Epilogue, workspace: torch.Tensor | None = None, out=None):
     if workspace is None:
-        nbytes = lib().qgtc_layer_workspace_bytes(A.rows, X.cols, max(agg_ep.rq_nbits, 1))
+        nbytes = lib().qgtc_layer_workspace_bytes(A.rows, X.cols, W.cols, max(agg_ep.rq_nbits, 1))
         workspace = torch.empty(nbytes // 4 + 1, dtype=torch.int32, device=X.words.device)
     res, ptr, ld = _out_arg(upd_ep, A.rows, W.cols, out, RIGHT, X.words.device)
     a, u = agg_ep.to_c(), upd_ep.to_c()
@@ -308,6 +308,9 @@ def qgtc_layer(A: Bits, tmap: TileMap | None, X: Bits, W: Bits, agg_ep: Epilogue
 
 OPT_UPDATE_PATH = 0
 OPT_AGG_XCD_RUN = 1
+OPT_LAYER_PATH = 2
+OPT_LAYER_KSPLIT = 3
+LAYER_FUSED, LAYER_TWO_KERNELS = 0, 1
 UPDATE_AUTO, UPDATE_POPCOUNT, UPDATE_MATRIX_CORES = 0, 1, 2
 
 

@@ -24,121 +24,7 @@
 namespace qgtc {
 namespace {
 
-#include "popc_blocks.inc"
-
-struct AggParams {
-  const uint32_t* A;
-  int64_t lda;            // words per row of A
-  int32_t rows;           // rows of A (= output rows)
-  int32_t block_rows;     // 0, or rows per diagonal block
-  const uint32_t* X;
-  uint32_t ldx4, psx4;    // bytes between word rows / planes of X
-  uint32_t x_bytes;       // bytes spanned by X
-  int32_t x_kwords;       // word rows of X
-  int32_t s;              // planes of X
-  int32_t cols;           // columns of X (= output columns)
-  const int32_t* row_cnt; // tile map (NULL: all tiles)
-  const int32_t* col_idx;
-  int32_t n_tile_rows, n_tile_cols;
-  int32_t tile_words;     // 1, 2 or 4 words (32/64/128 bits) per tile row
-  int32_t cw_shift;       // log2 of columns per wave: 4, 5 or 6
-  int32_t n_cg;           // column groups
-  int32_t n_rt;           // groups of 64/CW row tiles
-  int32_t ksplit;         // waves per workgroup
-  int32_t chunk_shift;    // log2 of the run of consecutive workgroups one XCD takes
-  uint32_t nblocks;
-  EpiParams ep;
-};
-
-template <int S>
-__device__ __forceinline__ void zero_acc(uint32_t (&acc)[16][S]) {
-#pragma unroll
-  for (int j = 0; j < 16; ++j)
-#pragma unroll
-    for (int i = 0; i < S; ++i) acc[j][i] = 0u;
-}
-
-// S planes of one word row of X for this lane's column.
-// UNI: the word row is wave-uniform (scalar offset); otherwise per lane.
-template <int S, bool UNI, bool MULTI>
-__device__ __forceinline__ void load_x(uint32_t (&x)[S], __amdgpu_buffer_rsrc_t rx, uint32_t kw,
-                                       uint32_t col4, const AggParams& p, int plane0) {
-  if constexpr (UNI) {
-    const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)kw) * p.ldx4;
-#pragma unroll
-    for (int i = 0; i < S; ++i) {
-      if (MULTI && plane0 + i >= p.s) {
-        x[i] = 0u;
-      } else {
-        x[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, col4, base + (uint32_t)(plane0 + i) * p.psx4, 0);
-      }
-    }
-  } else {
-    const uint32_t voff = kw * p.ldx4 + col4;
-#pragma unroll
-    for (int i = 0; i < S; ++i) {
-      if (MULTI && plane0 + i >= p.s) {
-        x[i] = 0u;
-      } else {
-        x[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff, (uint32_t)(plane0 + i) * p.psx4, 0);
-      }
-    }
-  }
-}
-
-// The four adjacency words (one per word step) of loop iteration `it` for this
-// lane's row, and the word rows of X they meet.  An iteration covers 4 word
-// steps: one 128-bit tile, two 64-bit tiles or four 32-bit tiles.
-struct Step4 {
-  uint32_t a[4];
-  uint32_t kw[4];
-};
-
-template <bool UNI>
-__device__ __forceinline__ Step4 load_steps(const AggParams& p, const uint32_t* arow, bool row_ok,
-                                            const int32_t* ci, int n, int it, uint32_t kw_base,
-                                            uint32_t kw_max) {
-  Step4 r;
-  const int tw = p.tile_words;
-  const int per_it = 4 / tw;            // tiles per iteration
-#pragma unroll
-  for (int q = 0; q < 4; ++q) { r.a[q] = 0u; r.kw[q] = 0u; }
-  if (tw == 4) {
-    const int t = it;
-    const bool ok = t < n;
-    int tc = ok ? (ci ? ci[t] : t) : 0;
-    if (UNI) tc = __builtin_amdgcn_readfirstlane(tc);
-    const uint4 v = (ok && row_ok) ? *reinterpret_cast<const uint4*>(arow + (int64_t)tc * 4)
-                                   : make_uint4(0u, 0u, 0u, 0u);
-    r.a[0] = v.x; r.a[1] = v.y; r.a[2] = v.z; r.a[3] = v.w;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) r.kw[q] = min(kw_base + (uint32_t)tc * 4u + q, kw_max);
-  } else if (tw == 2) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int t = it * per_it + h;
-      const bool ok = t < n;
-      int tc = ok ? (ci ? ci[t] : t) : 0;
-      if (UNI) tc = __builtin_amdgcn_readfirstlane(tc);
-      const uint2 v = (ok && row_ok) ? *reinterpret_cast<const uint2*>(arow + (int64_t)tc * 2)
-                                     : make_uint2(0u, 0u);
-      r.a[2 * h] = v.x; r.a[2 * h + 1] = v.y;
-      r.kw[2 * h] = min(kw_base + (uint32_t)tc * 2u, kw_max);
-      r.kw[2 * h + 1] = min(kw_base + (uint32_t)tc * 2u + 1u, kw_max);
-    }
-  } else {
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const int t = it * per_it + h;
-      const bool ok = t < n;
-      int tc = ok ? (ci ? ci[t] : t) : 0;
-      if (UNI) tc = __builtin_amdgcn_readfirstlane(tc);
-      r.a[h] = (ok && row_ok) ? arow[tc] : 0u;
-      r.kw[h] = min(kw_base + (uint32_t)tc, kw_max);
-    }
-  }
-  return r;
-}
+#include "agg_core.inc"
 
 // The words that the ballots of bit (p0 + i) of q, i < S, give for one output
 // row of the wave.  CWS >= 5: the two halves of the 64-bit ballot (CW = 64: two
@@ -186,7 +72,9 @@ __device__ __forceinline__ void pack_rows_fast(const uint32_t (&q)[16], uint32_t
   if constexpr (J + 1 < 16) pack_rows_fast<J + 1, S, CWS>(q, ow);
 }
 
-template <int S, int CWS, bool MULTI>
+// TW: words per tile (1, 2, 4) for CWS == 6, where the tile loop is specialized;
+// 0 otherwise (tile width read at run time).
+template <int S, int CWS, bool MULTI, int TW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void aggregate_kernel(const AggParams p) {
   constexpr bool UNI = CWS == 6;
   extern __shared__ uint32_t lds[];   // [ksplit][16][64] partial sums when ksplit > 1
@@ -233,27 +121,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
     uint32_t acc[16][S];
     zero_acc<S>(acc);
 
-    int it = wave;
-    if (__builtin_amdgcn_ballot_w64(it < n_it) != 0ull) {
-      Step4 cur = load_steps<UNI>(p, arow, row_ok, ci, n, it, kw_base, kw_max);
-      uint32_t x0[S], x1[S];
-      load_x<S, UNI, MULTI>(x0, rx, cur.kw[0], col4, p, plane0);
-      while (true) {
-        const int it_next = it + p.ksplit;
-        const bool more = __builtin_amdgcn_ballot_w64(it_next < n_it) != 0ull;
-        Step4 nxt = cur;
-        if (more) nxt = load_steps<UNI>(p, arow, row_ok, ci, n, it_next, kw_base, kw_max);
-        load_x<S, UNI, MULTI>(x1, rx, cur.kw[1], col4, p, plane0);
-        popc_rows<S>::run(cur.a[0], x0, acc);
-        load_x<S, UNI, MULTI>(x0, rx, cur.kw[2], col4, p, plane0);
-        popc_rows<S>::run(cur.a[1], x1, acc);
-        load_x<S, UNI, MULTI>(x1, rx, cur.kw[3], col4, p, plane0);
-        popc_rows<S>::run(cur.a[2], x0, acc);
-        load_x<S, UNI, MULTI>(x0, rx, nxt.kw[0], col4, p, plane0);
-        popc_rows<S>::run(cur.a[3], x1, acc);
-        if (!more) break;
-        cur = nxt;
-        it = it_next;
+    if constexpr (UNI) {
+      const __amdgpu_buffer_rsrc_t ra = agg_row_tile_rsrc(p, rt);
+      const uint32_t va_off = (uint32_t)(lane & 15) * (uint32_t)(p.lda * 4);
+      agg_loop_uniform<S, (TW > 0 ? TW : 4), MULTI>(acc, p, ra, va_off, rx, col4, ci, n, wave, p.ksplit, kw_base,
+                                                    kw_max, plane0);
+    } else {
+      int it = wave;
+      if (__builtin_amdgcn_ballot_w64(it < n_it) != 0ull) {
+        Step4 cur = load_steps<UNI>(p, arow, row_ok, load_tiles<UNI>(p, ci, n, it), n, kw_base, kw_max);
+        Tiles4 t_nxt = load_tiles<UNI>(p, ci, n, it + p.ksplit);
+        uint32_t x0[S], x1[S];
+        load_x<S, UNI, MULTI>(x0, rx, cur.kw[0], col4, p, plane0);
+        while (true) {
+          const int it_next = it + p.ksplit;
+          const bool more = __builtin_amdgcn_ballot_w64(it_next < n_it) != 0ull;
+          const Tiles4 t_nn = load_tiles<UNI>(p, ci, n, it_next + p.ksplit);   // two iterations ahead
+          Step4 nxt = cur;
+          if (more) nxt = load_steps<UNI>(p, arow, row_ok, t_nxt, n, kw_base, kw_max);
+          load_x<S, UNI, MULTI>(x1, rx, cur.kw[1], col4, p, plane0);
+          popc_rows<S>::run(cur.a[0], x0, acc);
+          load_x<S, UNI, MULTI>(x0, rx, cur.kw[2], col4, p, plane0);
+          popc_rows<S>::run(cur.a[1], x1, acc);
+          load_x<S, UNI, MULTI>(x1, rx, cur.kw[3], col4, p, plane0);
+          popc_rows<S>::run(cur.a[2], x0, acc);
+          load_x<S, UNI, MULTI>(x0, rx, nxt.kw[0], col4, p, plane0);
+          popc_rows<S>::run(cur.a[3], x1, acc);
+          if (!more) break;
+          cur = nxt;
+          t_nxt = t_nn;
+          it = it_next;
+        }
       }
     }
     // shift-and-add of the per-plane popcounts (Algorithm 1, elementwise reduction)
@@ -395,7 +293,16 @@ template <int S, int CWS, bool MULTI>
 qgtc_status launch(const AggParams& p, hipStream_t stream) {
   const unsigned grid = xcd_deal_grid(p.nblocks, p.chunk_shift);
   const size_t lds = p.ksplit > 1 ? (size_t)p.ksplit * 16 * 64 * sizeof(uint32_t) : 0;
-  hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
+  if constexpr (CWS == 6) {
+    if (p.tile_words == 4)
+      hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI, 4>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
+    else if (p.tile_words == 2)
+      hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI, 2>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
+    else
+      hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI, 1>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
+  } else {
+    hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI, 0>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
+  }
   return launch_status();
 }
 
@@ -422,49 +329,9 @@ using namespace qgtc;
 extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc_bits* X,
                                       const qgtc_epilogue* ep, void* out, int64_t ld_out, void* stream) {
   if (!A || !X || !ep || !out) return QGTC_ERR_NULL;
-  qgtc_status st = check_adjacency(A);
-  if (st != QGTC_OK) return st;
-  st = check_bits(X, QGTC_RIGHT);
-  if (st != QGTC_OK) return st;
-  if (A->block_rows > 0) {
-    if (A->rows != X->rows) return QGTC_ERR_SHAPE;
-  } else if (A->cols != X->rows) {
-    return QGTC_ERR_SHAPE;
-  }
-  const int64_t x_words = span_words(X);
-  if (x_words * 4 >= (int64_t)1 << 32 || X->ld_words * 4 >= (int64_t)1 << 31 ||
-      X->plane_stride_words * 4 >= (int64_t)1 << 31)
-    return QGTC_ERR_UNSUPPORTED;
-
   AggParams p{};
-  p.A = A->data;
-  p.lda = A->ld_words;
-  p.rows = A->rows;
-  p.block_rows = A->block_rows;
-  p.X = X->data;
-  p.ldx4 = (uint32_t)(X->ld_words * 4);
-  p.psx4 = (uint32_t)(X->plane_stride_words * 4);
-  p.x_bytes = (uint32_t)(x_words * 4);
-  p.x_kwords = cdiv(X->rows, 32);
-  p.s = X->nbits;
-  p.cols = X->cols;
-  if (map) {
-    if (!map->row_cnt || !map->col_idx) return QGTC_ERR_NULL;
-    if (map->tile_rows != 16 ||
-        (map->tile_kbits != 32 && map->tile_kbits != 64 && map->tile_kbits != 128))
-      return QGTC_ERR_UNSUPPORTED;
-    if (map->n_tile_rows != cdiv(A->rows, 16) || map->n_tile_cols != cdiv(A->cols, map->tile_kbits))
-      return QGTC_ERR_SHAPE;
-    p.row_cnt = map->row_cnt;
-    p.col_idx = map->col_idx;
-    p.n_tile_rows = map->n_tile_rows;
-    p.n_tile_cols = map->n_tile_cols;
-    p.tile_words = map->tile_kbits / 32;
-  } else {
-    p.n_tile_rows = cdiv(A->rows, 16);
-    p.n_tile_cols = cdiv(A->cols, 128);
-    p.tile_words = 4;
-  }
+  qgtc_status st = agg_fill_params(A, map, X, &p);
+  if (st != QGTC_OK) return st;
   const bool square = A->block_rows > 0 || A->rows == A->cols;
   st = make_epilogue(ep, out, ld_out, A->rows, X->cols, QGTC_LEFT, square, &p.ep);
   if (st != QGTC_OK) return st;
@@ -484,14 +351,7 @@ extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* m
   // are the diagonal tiles); dealing short runs round-robin spreads the rows of
   // one subgraph over all XCDs, so a subgraph that holds far more tiles than the
   // others (the hubs of a power-law graph) does not leave seven XCDs idle.
-  {
-    const int opt = agg_chunk_option();
-    int64_t chunk = (int64_t)(opt > 0 ? opt : 8) * p.n_cg;
-    if (opt < 0) chunk = (p.nblocks + 7u) / 8u;          // one run per XCD
-    int sh = 0;
-    while (((int64_t)1 << sh) < chunk && sh < 30) ++sh;
-    p.chunk_shift = sh;
-  }
+  p.chunk_shift = agg_chunk_shift(p.n_cg, p.nblocks);
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_AGGREGATE, s);

@@ -92,9 +92,13 @@ qgtc_status make_epilogue(const qgtc_epilogue* ep, void* out, int64_t ld_out, in
 namespace {
 int g_update_path = 0;
 int g_agg_chunk = 0;
+int g_layer_path = 0;
+int g_layer_ksplit = 0;
 }
 int update_path_option() { return g_update_path; }
 int agg_chunk_option() { return g_agg_chunk; }
+int layer_path_option() { return g_layer_path; }
+int layer_ksplit_option() { return g_layer_ksplit; }
 
 // ---- event-based kernel timing ------------------------------------------------
 namespace {
@@ -162,6 +166,16 @@ extern "C" qgtc_status qgtc_set_option(int32_t option, int32_t value) {
     g_update_path = value;
     return QGTC_OK;
   }
+  if (option == QGTC_OPT_LAYER_PATH) {
+    if (value < 0 || value > 1) return QGTC_ERR_UNSUPPORTED;
+    g_layer_path = value;
+    return QGTC_OK;
+  }
+  if (option == QGTC_OPT_LAYER_KSPLIT) {
+    if (value != 0 && value != 1 && value != 2 && value != 4) return QGTC_ERR_UNSUPPORTED;
+    g_layer_ksplit = value;
+    return QGTC_OK;
+  }
   if (option == QGTC_OPT_AGG_XCD_RUN) {
     if (value > 4096) return QGTC_ERR_UNSUPPORTED;
     g_agg_chunk = value;
@@ -191,9 +205,21 @@ extern "C" size_t qgtc_describe(qgtc_bits* d, int32_t rows, int32_t cols, int32_
   return (size_t)(d->plane_stride_words * nbits);
 }
 
-extern "C" size_t qgtc_layer_workspace_bytes(int32_t rows, int32_t cols, int32_t nbits) {
-  if (rows < 0 || cols < 0 || nbits < 1 || nbits > 32) return 0;
-  return (size_t)rows * (size_t)cdiv(cols, 32) * (size_t)nbits * 4 + 16;
+namespace {
+// Two-kernel path: bytes of the packed planes of Y (rounded up to 16) ...
+size_t layer_y_bytes(int32_t rows, int32_t cols, int32_t nbits) {
+  return ((size_t)rows * (size_t)cdiv(cols, 32) * (size_t)nbits * 4 + 15) / 16 * 16;
+}
+}  // namespace
+
+extern "C" size_t qgtc_layer_workspace_bytes(int32_t rows, int32_t in_cols, int32_t out_cols,
+                                             int32_t nbits) {
+  if (rows < 0 || in_cols < 0 || out_cols < 0 || nbits < 1 || nbits > 32) return 0;
+  // ... plus one int32 per row for the row sums of Y; the fused kernel keeps only
+  // the weights in operand order there
+  const size_t two = layer_y_bytes(rows, in_cols, nbits) + (size_t)rows * 4 + 16;
+  const size_t fused = layer_fused_workspace_bytes(in_cols, out_cols);
+  return two > fused ? two : fused;
 }
 
 extern "C" qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc_bits* X,
@@ -204,7 +230,7 @@ extern "C" qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map, 
   if (agg_ep->mode != QGTC_OUT_BITS) return QGTC_ERR_UNSUPPORTED;
   if (((uintptr_t)workspace & 15u) != 0) return QGTC_ERR_ALIGN;
   if (agg_ep->rq_nbits < 1 || agg_ep->rq_nbits > 32) return QGTC_ERR_BITWIDTH;
-  if (workspace_bytes < qgtc_layer_workspace_bytes(A->rows, X->cols, agg_ep->rq_nbits))
+  if (workspace_bytes < qgtc_layer_workspace_bytes(A->rows, X->cols, W->cols, agg_ep->rq_nbits))
     return QGTC_ERR_WORKSPACE;
   // the requantized aggregation result, packed as the left operand of the update
   qgtc_bits Y{};
@@ -216,16 +242,35 @@ extern "C" qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map, 
   Y.block_rows = 0;
   Y.ld_words = cdiv(X->cols, 32);
   Y.plane_stride_words = (int64_t)A->rows * Y.ld_words;
-  // validate the update before anything is launched
-  qgtc_status st = check_bits(W, QGTC_RIGHT);
+  // validate everything before anything is launched
+  qgtc_status st = check_adjacency(A);
+  if (st != QGTC_OK) return st;
+  st = check_bits(X, QGTC_RIGHT);
+  if (st != QGTC_OK) return st;
+  st = check_bits(W, QGTC_RIGHT);
   if (st != QGTC_OK) return st;
   if (W->rows != X->cols) return QGTC_ERR_SHAPE;
   EpiParams probe;
   st = make_epilogue(upd_ep, out, ld_out, A->rows, W->cols, QGTC_RIGHT, false, &probe);
   if (st != QGTC_OK) return st;
+
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  bool done = false;
+  st = layer_fused(A, map, X, W, agg_ep, upd_ep, workspace, workspace_bytes, out, ld_out, s, &done);
+  if (st != QGTC_OK || done) return st;
+
   st = qgtc_aggregate(A, map, X, agg_ep, &Y, 0, stream);
   if (st != QGTC_OK) return st;
-  return qgtc_update(&Y, W, upd_ep, out, ld_out, stream);
+  qgtc_epilogue upd = *upd_ep;
+  if (upd.mode == QGTC_OUT_F32 && upd.row_i == nullptr && upd.rs != 0.0) {
+    // the row sums of Y only exist now
+    int32_t* sums = reinterpret_cast<int32_t*>(reinterpret_cast<uint8_t*>(workspace) +
+                                               layer_y_bytes(A->rows, X->cols, agg_ep->rq_nbits));
+    st = qgtc_row_sums(&Y, sums, stream);
+    if (st != QGTC_OK) return st;
+    upd.row_i = sums;
+  }
+  return qgtc_update(&Y, W, &upd, out, ld_out, stream);
 }
 
 extern "C" qgtc_status qgtc_prof_enable(int32_t on) {

@@ -1,0 +1,415 @@
+// One quantized GNN layer in a single kernel (Algorithm 1 of the paper with the
+// inter-layer fusion of Section 4.5 taken one step further): neighbour
+// aggregation on the vector ALUs, requantization, node update on the int8 matrix
+// cores and the output epilogue, with the aggregated tile never leaving the CU.
+//
+// A workgroup owns one 16-row tile of A.
+//   1. Aggregation: as in aggregate.hip (lane <-> feature column, AND + popcount
+//      with the adjacency word broadcast by DPP, zero tiles jumped through the
+//      tile list).  The workgroup's waves stand side by side over the 64-column
+//      groups of X (a wave walks several groups when there are more groups than
+//      waves) and, for short grids, split the tile list between them.
+//   2. Each wave requantizes its 16 x 64 results to codes of at most 8 bits and
+//      writes them as bytes into the Y tile in LDS, row-major: this is already
+//      the operand order of the matrix instruction (16 consecutive K positions
+//      per lane), so the popcount side hands over to the matrix cores without
+//      a transposition.
+//   3. Update: v_mfma_i32_16x16x64_i8 over the Y tile and the weights, which a
+//      small kernel has put into operand order as bytes beforehand.  8-bit codes
+//      are split into 7 bits + top bit because the instruction is signed.  The
+//      16-column output tiles (and chunks of K) are dealt to the waves; results
+//      are added into the Z tile in LDS.
+//   4. Epilogue: lane <-> output column, 16 rows per lane: int32, dequantized
+//      fp32, or requantized codes whose 8 x 16 bit matrix is transposed in
+//      registers into the 16-bit halves of the packed words of the next layer's X
+//      (32 nodes per word, so a 16-row tile owns half a word).
+#include "qgtc_internal.h"
+
+namespace qgtc {
+namespace {
+
+#include "agg_core.inc"
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+struct LayerParams {
+  AggParams a;            // aggregation operands; a.ep: requantization of its result
+  EpiParams up;           // epilogue of the update
+  const uint8_t* wb;      // weights as bytes in operand order: [part][tile][k step][lane][16]
+  int64_t wb_part;        // bytes between the two parts (7 low bits / top bit)
+  int32_t h;              // output columns
+  int32_t n_nt_w;         // 16-column output tiles that come from W
+  int32_t n_nt;           // ... plus the all-ones tile that yields the row sums of Y
+  int32_t n_ks;           // 64-wide steps along the contraction dimension
+  int32_t n_kc, ks_per;   // chunks of steps dealt to different waves, steps per chunk
+  int32_t ys;             // bytes per row of the Y tile
+  int32_t zs;             // words per row of the Z tile
+  int32_t cgw;            // waves side by side over the column groups
+  int32_t n_pass;         // column groups per wave
+  int32_t split_y, split_w;
+  int32_t want_rowsum;
+  int32_t yb_off, z_off;  // LDS offsets in words
+};
+
+// Weights: packed planes -> bytes in the operand order of the matrix instruction.
+// Thread (tile nt, step ks, lane l) writes the 16 bytes of column 16 nt + l % 16,
+// K positions 64 ks + 16 (l / 16) .. + 15.
+__global__ __launch_bounds__(256) void weight_bytes_kernel(const uint32_t* W, int64_t ldw, int64_t psw,
+                                                           int t, int kwords, int cols, int n_nt_w,
+                                                           int n_ks, int split_w, uint8_t* wb,
+                                                           int64_t wb_part) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int lane = idx & 63;
+  const int ks = (idx >> 6) % n_ks;
+  const int nt = (idx >> 6) / n_ks;
+  if (nt >= n_nt_w) return;
+  const int col = nt * 16 + (lane & 15);
+  const int k0 = ks * 64 + (lane >> 4) * 16;
+  const int kw = k0 >> 5;
+  const int sh = k0 & 31;
+  uint32_t f[8];
+#pragma unroll
+  for (int pl = 0; pl < 8; ++pl) {
+    f[pl] = 0u;
+    if (pl < t && col < cols && kw < kwords)
+      f[pl] = (W[(int64_t)pl * psw + (int64_t)kw * ldw + col] >> sh) & 0xffffu;
+  }
+  uint32_t d[4];
+  planes_to_bytes(f, t, d);
+  v4u lo = {d[0], d[1], d[2], d[3]};
+  uint8_t* dst = wb + (int64_t)idx * 16;
+  if (split_w) {
+    v4u hi = (lo >> 7) & 0x01010101u;
+    lo = lo & 0x7f7f7f7fu;
+    *reinterpret_cast<v4u*>(dst + wb_part) = hi;
+  }
+  *reinterpret_cast<v4u*>(dst) = lo;
+}
+
+template <int S, int TW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void layer_kernel(const LayerParams p) {
+  extern __shared__ uint32_t lds[];
+  const AggParams& a = p.a;
+  const unsigned bid = xcd_deal(blockIdx.x, a.chunk_shift);
+  if (bid >= a.nblocks) return;                      // whole workgroup leaves together
+  const int tr = (int)bid;                           // tile row of this workgroup
+
+  const int nw = (int)(blockDim.x >> 6);
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int lane = threadIdx.x & 63;
+  const int wcg = wave % p.cgw;                      // position over the column groups
+  const int kpart = wave / p.cgw;                    // share of the tile list
+  uint32_t* part = lds;                              // [wave][16][64] partial sums (K split)
+  uint8_t* yb = reinterpret_cast<uint8_t*>(lds + p.yb_off);
+  uint32_t* z = lds + p.z_off;
+
+  for (int i = threadIdx.x; i < 16 * p.zs; i += (int)blockDim.x) z[i] = 0u;
+
+  const int out_row0 = tr * 16;
+  const __amdgpu_buffer_rsrc_t ra = agg_row_tile_rsrc(a, tr);
+  const uint32_t va_off = (uint32_t)(lane & 15) * (uint32_t)(a.lda * 4);   // this lane's adjacency row
+  int n = a.row_cnt ? a.row_cnt[tr] : a.n_tile_cols;
+  n = __builtin_amdgcn_readfirstlane(n);
+  const int32_t* ci = a.col_idx ? a.col_idx + (int64_t)tr * a.n_tile_cols : nullptr;
+  uint32_t kw_base = 0u;
+  if (a.block_rows > 0) kw_base = (uint32_t)(out_row0 / a.block_rows) * (uint32_t)(a.block_rows >> 5);
+  const uint32_t kw_max = (uint32_t)(a.x_kwords - 1);
+  __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.X, 0, (int)a.x_bytes, 0x00020000);
+  const int km = a.ksplit - 1;                       // ksplit is 1, 2 or 4
+
+  const EpiParams& ea = a.ep;
+  const uint32_t qmax_a = (1u << ea.rq_nbits) - 1u;  // at most 8 bits here
+  const float qmaxf_a = (float)qmax_a;
+
+  // ---- 1 + 2: aggregate, requantize, bytes into the Y tile ---------------------
+  for (int pass = 0; pass < p.n_pass; ++pass) {
+    const int cg = pass * p.cgw + wcg;               // wave-uniform
+    const bool cg_ok = cg < a.n_cg;
+    const int c = cg * 64 + lane;
+    const bool c_ok = cg_ok && c < a.cols;
+    const uint32_t col4 = (uint32_t)(c_ok ? c : a.cols - 1) * 4u;
+
+    uint32_t acc[16][S];
+    zero_acc<S>(acc);
+    if (cg_ok)
+      agg_loop_uniform<S, TW, false>(acc, a, ra, va_off, rx, col4, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
+    // shift-and-add of the per-plane popcounts (Algorithm 1, elementwise reduction)
+    uint32_t y[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      uint32_t v = 0u;
+#pragma unroll
+      for (int i = 0; i < S; ++i) v += acc[j][i] << i;
+      y[j] = v;
+    }
+
+    // K split: wave (wcg, kpart) finishes the rows j with j % ksplit == kpart
+    if (a.ksplit > 1) {
+      if (pass > 0) __syncthreads();                 // the sums of the previous pass have been read
+#pragma unroll
+      for (int j = 0; j < 16; ++j) part[(wave * 16 + j) * 64 + lane] = y[j];
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        if ((j & km) != kpart) continue;             // wave-uniform
+        uint32_t v = 0u;
+        for (int kp = 0; kp < a.ksplit; ++kp) v += part[((kp * p.cgw + wcg) * 16 + j) * 64 + lane];
+        y[j] = v;
+      }
+    }
+
+    // GIN self term: the 16 bits (row0 % 32 ..) of word row (row0 / 32) of every
+    // plane of X are this lane's codes of the 16 rows, bit-transposed
+    if (ea.self_term != 0) {
+      const uint32_t srow = min((uint32_t)(out_row0 >> 5), kw_max);
+      const uint32_t voff = srow * a.ldx4 + col4;
+      const int bit0 = out_row0 & 31;
+      uint32_t f[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        f[i] = 0u;
+        if (i < S) f[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff, (uint32_t)i * a.psx4, 0) >> bit0;
+      }
+      uint32_t lo0 = (f[0] & 0xffu) | ((f[1] & 0xffu) << 8) | ((f[2] & 0xffu) << 16) | (f[3] << 24);
+      uint32_t hi0 = (f[4] & 0xffu) | ((f[5] & 0xffu) << 8) | ((f[6] & 0xffu) << 16) | (f[7] << 24);
+      uint32_t lo1 = ((f[0] >> 8) & 0xffu) | (f[1] & 0xff00u) | ((f[2] & 0xff00u) << 8) | ((f[3] & 0xff00u) << 16);
+      uint32_t hi1 = ((f[4] >> 8) & 0xffu) | (f[5] & 0xff00u) | ((f[6] & 0xff00u) << 8) | ((f[7] & 0xff00u) << 16);
+      transpose_bits_8x8(lo0, hi0);                  // byte j: code of row j (rows 0..7)
+      transpose_bits_8x8(lo1, hi1);                  // rows 8..15
+      const uint32_t sw[4] = {lo0, hi0, lo1, hi1};
+#pragma unroll
+      for (int j = 0; j < 16; ++j) y[j] += (sw[j >> 2] >> (8 * (j & 3))) & 0xffu;
+    }
+
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if ((j & km) != kpart) continue;
+      const bool ok = c_ok && (out_row0 + j) < a.rows;
+      const uint32_t q = ok ? requantize_i32(y[j], ea, qmax_a, qmaxf_a) : 0u;
+      if (cg_ok) yb[j * p.ys + c] = (uint8_t)q;
+    }
+  }
+  __syncthreads();
+
+  // ---- 3: Z += Y tile x W on the matrix cores -----------------------------------
+  {
+    const int ln = lane & 15;                        // row of Y / column of W inside a tile
+    const int g = lane >> 4;                         // K sub-block, and row group of the result
+    const int n_units = p.n_nt * p.n_kc;
+    for (int u = wave; u < n_units; u += nw) {
+      const int nt = u % p.n_nt;
+      const int kc = u / p.n_nt;
+      const int ks1 = min((kc + 1) * p.ks_per, p.n_ks);
+      const bool ones = nt >= p.n_nt_w;              // the tile whose column 0 sums the rows of Y
+      v4i acc1 = {0, 0, 0, 0}, acc7 = {0, 0, 0, 0}, acc14 = {0, 0, 0, 0};
+      for (int ks = kc * p.ks_per; ks < ks1; ++ks) {
+        const v4u av = *reinterpret_cast<const v4u*>(yb + ln * p.ys + ks * 64 + g * 16);
+        v4u a7 = av, ab = {0u, 0u, 0u, 0u};
+        if (p.split_y) {
+          a7 = av & 0x7f7f7f7fu;
+          ab = (av >> 7) & 0x01010101u;
+        }
+        v4u b7 = {0u, 0u, 0u, 0u}, bb = {0u, 0u, 0u, 0u};
+        if (ones) {
+          if (ln == 0) b7 = (v4u){0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
+        } else {
+          const uint8_t* src = p.wb + ((int64_t)(nt * p.n_ks + ks) * 64 + lane) * 16;
+          b7 = *reinterpret_cast<const v4u*>(src);
+          if (p.split_w) bb = *reinterpret_cast<const v4u*>(src + p.wb_part);
+        }
+        acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)b7, acc1, 0, 0, 0);
+        if (p.split_y) acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)b7, acc7, 0, 0, 0);
+        if (p.split_w && !ones) {
+          acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)bb, acc7, 0, 0, 0);
+          if (p.split_y) acc14 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)bb, acc14, 0, 0, 0);
+        }
+      }
+      // element r of the result: row 4 g + r, column ln of the tile
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t v = (uint32_t)acc1[r] + ((uint32_t)acc7[r] << 7) + ((uint32_t)acc14[r] << 14);
+        atomicAdd(&z[(4 * g + r) * p.zs + nt * 16 + ln], v);
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- 4: epilogue, lane <-> output column ---------------------------------------
+  const EpiParams& e = p.up;
+  for (int hb = wave * 64; hb < p.h; hb += nw * 64) {
+    const int h = hb + lane;
+    const bool h_ok = h < p.h;
+    const int hc = h_ok ? h : p.h - 1;
+    uint32_t zz[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) zz[j] = z[j * p.zs + hc];
+
+    if (e.mode == QGTC_OUT_I32) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int row = out_row0 + j;
+        int32_t o = (int32_t)zz[j];
+        if (e.relu && o < 0) o = 0;
+        if (h_ok && row < a.rows) reinterpret_cast<int32_t*>(e.out)[(int64_t)row * e.ld_out + h] = o;
+      }
+    } else if (e.mode == QGTC_OUT_F32) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int row = out_row0 + j;
+        if (h_ok && row < a.rows) {
+          double ri = 0.0;
+          if (p.want_rowsum) ri = (double)z[j * p.zs + p.n_nt_w * 16];
+          else if (e.row_i) ri = (double)e.row_i[row];
+          reinterpret_cast<float*>(e.out)[(int64_t)row * e.ld_out + h] = dequantize_f64_ri(zz[j], ri, row, h, e);
+        }
+      }
+    } else {
+      const int qbits = e.rq_nbits;                  // at most 8 here
+      const uint32_t qmax = (1u << qbits) - 1u;
+      const float qmaxf = (float)qmax;
+      uint32_t b[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const bool ok = h_ok && (out_row0 + j) < a.rows;
+        const uint32_t q = ok ? requantize_i32(zz[j], e, qmax, qmaxf) : 0u;
+        b[j >> 2] |= q << (8 * (j & 3));
+      }
+      transpose_bits_8x8(b[0], b[1]);                // byte i: bit i of the codes of rows 0..7
+      transpose_bits_8x8(b[2], b[3]);                // rows 8..15
+      // RIGHT layout of the next layer's X: 32 consecutive rows per word; this tile
+      // owns the lower or the upper 16 bits.  The last tile of a matrix whose row
+      // count leaves the upper half without a tile writes the whole word.
+      const bool upper = (out_row0 & 16) != 0;
+      const bool whole = !upper && out_row0 + 16 >= a.rows;
+      uint8_t* dst = reinterpret_cast<uint8_t*>(e.out) +
+                     (((int64_t)(out_row0 >> 5) * e.ld_out + hc) << 2) + (upper ? 2 : 0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t w0 = (b[i >> 2] >> (8 * (i & 3))) & 0xffu;
+        const uint32_t w1 = (b[2 + (i >> 2)] >> (8 * (i & 3))) & 0xffu;
+        const uint32_t word = w0 | (w1 << 8);
+        if (i < qbits && h_ok) {
+          uint8_t* d = dst + (int64_t)i * e.ps_out * 4;
+          if (whole) *reinterpret_cast<uint32_t*>(d) = word;
+          else *reinterpret_cast<uint16_t*>(d) = (uint16_t)word;
+        }
+      }
+    }
+  }
+}
+
+template <int S>
+qgtc_status launch(const LayerParams& p, unsigned nw, size_t lds_bytes, hipStream_t stream) {
+  const unsigned grid = xcd_deal_grid(p.a.nblocks, p.a.chunk_shift);
+  if (p.a.tile_words == 4)
+    hipLaunchKernelGGL((layer_kernel<S, 4>), dim3(grid), dim3(64 * nw), lds_bytes, stream, p);
+  else if (p.a.tile_words == 2)
+    hipLaunchKernelGGL((layer_kernel<S, 2>), dim3(grid), dim3(64 * nw), lds_bytes, stream, p);
+  else
+    hipLaunchKernelGGL((layer_kernel<S, 1>), dim3(grid), dim3(64 * nw), lds_bytes, stream, p);
+  return launch_status();
+}
+
+}  // namespace
+
+size_t layer_fused_workspace_bytes(int32_t in_cols, int32_t out_cols) {
+  // two parts of ceil(out/16) x ceil(in/64) operand blocks of 1 KiB
+  return (size_t)2 * (size_t)cdiv(out_cols, 16) * (size_t)cdiv(in_cols, 64) * 1024;
+}
+
+qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc_bits* X,
+                        const qgtc_bits* W, const qgtc_epilogue* agg_ep, const qgtc_epilogue* upd_ep,
+                        void* workspace, size_t workspace_bytes, void* out, int64_t ld_out,
+                        hipStream_t stream, bool* done) {
+  *done = false;
+  if (layer_path_option() == 1) return QGTC_OK;
+  if (!A || !X || !W || !agg_ep || !upd_ep || !workspace || !out) return QGTC_OK;
+  // what the kernel covers; everything else takes the two-kernel path
+  if (X->nbits > 8 || W->nbits > 8 || agg_ep->rq_nbits < 1 || agg_ep->rq_nbits > 8) return QGTC_OK;
+  if (upd_ep->mode == QGTC_OUT_BITS && upd_ep->rq_nbits > 8) return QGTC_OK;
+  if (X->cols <= 32 || X->cols > 1024 || W->cols < 1 || W->cols > 256) return QGTC_OK;
+  if (A->rows < 1) return QGTC_OK;
+  if (workspace_bytes < layer_fused_workspace_bytes(X->cols, W->cols)) return QGTC_OK;
+  if (!(agg_ep->rq_inv_scale > 0.0f)) return QGTC_OK;
+
+  LayerParams p{};
+  if (agg_fill_params(A, map, X, &p.a) != QGTC_OK) return QGTC_OK;
+  if (check_bits(W, QGTC_RIGHT) != QGTC_OK || W->rows != X->cols) return QGTC_OK;
+  const bool square = A->block_rows > 0 || A->rows == A->cols;
+  if (agg_ep->self_term && !square) return QGTC_OK;
+  if (make_epilogue(upd_ep, out, ld_out, A->rows, W->cols, QGTC_RIGHT, false, &p.up) != QGTC_OK)
+    return QGTC_OK;
+
+  EpiParams& ea = p.a.ep;
+  ea = EpiParams{};
+  ea.mode = QGTC_OUT_BITS;
+  ea.relu = agg_ep->relu ? 1 : 0;
+  ea.self_term = agg_ep->self_term ? 1 : 0;
+  ea.rq_nbits = agg_ep->rq_nbits;
+  ea.rq_lo = agg_ep->rq_lo;
+  ea.rq_inv_scale = agg_ep->rq_inv_scale;
+
+  AggParams& a = p.a;
+  a.cw_shift = 6;
+  a.n_cg = cdiv(X->cols, 64);
+  a.n_rt = a.n_tile_rows;
+  a.nblocks = (uint32_t)a.n_tile_rows;
+  p.cgw = a.n_cg <= 4 ? a.n_cg : (a.n_cg % 3 == 0 ? 3 : 4);
+  p.n_pass = cdiv(a.n_cg, p.cgw);
+  // few waves: let two or four waves split each tile list
+  a.ksplit = 1;
+  const int opt_k = layer_ksplit_option();
+  if (opt_k > 0) {
+    a.ksplit = opt_k;
+    while (p.cgw * a.ksplit > 4 && a.ksplit > 1) a.ksplit >>= 1;
+  } else {
+    while ((int64_t)a.n_tile_rows * p.cgw * a.ksplit < 6144 && p.cgw * a.ksplit * 2 <= 4) a.ksplit *= 2;
+  }
+  const unsigned nw = (unsigned)(p.cgw * a.ksplit);
+  a.chunk_shift = agg_chunk_shift(1, a.nblocks);
+
+  p.h = W->cols;
+  p.n_nt_w = cdiv(W->cols, 16);
+  p.want_rowsum = upd_ep->mode == QGTC_OUT_F32 && upd_ep->row_i == nullptr && upd_ep->rs != 0.0;
+  p.n_nt = p.n_nt_w + (p.want_rowsum ? 1 : 0);
+  p.n_ks = a.n_cg;
+  p.n_kc = (int)nw / p.n_nt;
+  if (p.n_kc < 1) p.n_kc = 1;
+  if (p.n_kc > p.n_ks) p.n_kc = p.n_ks;
+  p.ks_per = cdiv(p.n_ks, p.n_kc);
+  p.n_kc = cdiv(p.n_ks, p.ks_per);
+  p.ys = p.n_ks * 64 + 16;
+  p.zs = p.n_nt * 16;
+  p.split_y = agg_ep->rq_nbits == 8;
+  p.split_w = W->nbits == 8;
+  p.yb_off = a.ksplit > 1 ? (int)nw * 16 * 64 : 0;
+  p.z_off = p.yb_off + 4 * p.ys;
+  const size_t lds_bytes = (size_t)(p.z_off + 16 * p.zs) * 4;
+  if (lds_bytes > 64 * 1024) return QGTC_OK;
+
+  uint8_t* wb = reinterpret_cast<uint8_t*>(workspace);
+  p.wb = wb;
+  p.wb_part = (int64_t)p.n_nt_w * p.n_ks * 1024;
+
+  ProfScope prof(QGTC_KERNEL_LAYER, stream);
+  const int prep_threads = p.n_nt_w * p.n_ks * 64;
+  hipLaunchKernelGGL(weight_bytes_kernel, dim3((unsigned)cdiv(prep_threads, 256)), dim3(256), 0, stream,
+                     W->data, W->ld_words, W->plane_stride_words, W->nbits, cdiv(W->rows, 32), W->cols,
+                     p.n_nt_w, p.n_ks, p.split_w, wb, p.wb_part);
+  qgtc_status st = launch_status();
+  if (st != QGTC_OK) return st;
+  *done = true;
+  switch (X->nbits) {
+    case 1: return launch<1>(p, nw, lds_bytes, stream);
+    case 2: return launch<2>(p, nw, lds_bytes, stream);
+    case 3: return launch<3>(p, nw, lds_bytes, stream);
+    case 4: return launch<4>(p, nw, lds_bytes, stream);
+    case 5: return launch<5>(p, nw, lds_bytes, stream);
+    case 6: return launch<6>(p, nw, lds_bytes, stream);
+    case 7: return launch<7>(p, nw, lds_bytes, stream);
+    default: return launch<8>(p, nw, lds_bytes, stream);
+  }
+}
+
+}  // namespace qgtc

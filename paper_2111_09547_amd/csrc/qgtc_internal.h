@@ -78,6 +78,19 @@ struct UpdParams {
 };
 
 
+// Fused layer (layer.hip): aggregation, requantization and update in one kernel,
+// the intermediate staying in LDS.  *done is false when the shapes or bit widths
+// do not fit; nothing has been launched then.
+qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc_bits* X,
+                        const qgtc_bits* W, const qgtc_epilogue* agg_ep, const qgtc_epilogue* upd_ep,
+                        void* workspace, size_t workspace_bytes, void* out, int64_t ld_out,
+                        hipStream_t stream, bool* done);
+size_t layer_fused_workspace_bytes(int32_t in_cols, int32_t out_cols);
+// 0 = fused kernel whenever it applies, 1 = always aggregate and update separately
+int layer_path_option();
+// 0 = automatic, 1 / 2 / 4 = waves that split a tile list in the fused layer kernel
+int layer_ksplit_option();
+
 // int8 matrix-core variant of the update for s, t <= 8 (update_mfma.hip).
 bool update_mfma_eligible(const UpdParams& p);
 qgtc_status update_mfma_launch(const UpdParams& p, hipStream_t stream);
@@ -124,10 +137,10 @@ __device__ __forceinline__ uint32_t requantize_i32(uint32_t c_u32, const EpiPara
 }
 
 // fp32 output of the dequantizing epilogue; see QGTC_OUT_F32 in qgtc.h.
-__device__ __forceinline__ float dequantize_f64(uint32_t c_u32, int row, int col,
-                                                const EpiParams& e) {
+// ri: the entry of row_i for this row (0 when there is none).
+__device__ __forceinline__ float dequantize_f64_ri(uint32_t c_u32, double ri, int row, int col,
+                                                   const EpiParams& e) {
   const double c = (double)(int32_t)c_u32;
-  const double ri = e.row_i ? (double)e.row_i[row] : 0.0;
   const double rl = e.row_l ? (double)e.row_l[row] : 0.0;
   const double ci = e.col_i ? (double)e.col_i[col] : 0.0;
   const double t1 = e.cc * c + e.rs * ri;
@@ -136,6 +149,43 @@ __device__ __forceinline__ float dequantize_f64(uint32_t c_u32, int row, int col
   double v = t1 + t2;
   if (e.relu && v < 0.0) v = 0.0;
   return (float)v;
+}
+
+__device__ __forceinline__ float dequantize_f64(uint32_t c_u32, int row, int col,
+                                                const EpiParams& e) {
+  return dequantize_f64_ri(c_u32, e.row_i ? (double)e.row_i[row] : 0.0, row, col, e);
+}
+
+// 4 bits -> bit 0 of each of 4 bytes: the four shifted copies of x do not overlap.
+__device__ __forceinline__ uint32_t spread4(uint32_t x4) {
+  return __umul24(x4, 0x204081u) & 0x01010101u;
+}
+
+// 16-bit fields of up to 8 planes -> 16 bytes (as 4 dwords), byte j = sum_p bit_j(plane p) << p.
+// Planes past the operand's bit width are passed as zeros.
+__device__ __forceinline__ void planes_to_bytes(const uint32_t (&f)[8], int nplanes, uint32_t (&d)[4]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    uint32_t v = 0u;
+#pragma unroll
+    for (int pl = 0; pl < 8; ++pl)
+      if (pl < nplanes) v |= spread4((f[pl] >> (4 * q)) & 0xfu) << pl;   // wave-uniform test
+    d[q] = v;
+  }
+}
+
+// Transpose of an 8 x 8 bit matrix held as 8 bytes (byte r of hi:lo = row r, bit c
+// of it = column c): afterwards byte c holds column c, bit r of it = row r.
+// Three rounds of swapping ever larger off-diagonal blocks.
+__device__ __forceinline__ void transpose_bits_8x8(uint32_t& lo, uint32_t& hi) {
+  uint32_t t;
+  t = (lo ^ (lo >> 7)) & 0x00AA00AAu;  lo = lo ^ t ^ (t << 7);
+  t = (hi ^ (hi >> 7)) & 0x00AA00AAu;  hi = hi ^ t ^ (t << 7);
+  t = (lo ^ (lo >> 14)) & 0x0000CCCCu; lo = lo ^ t ^ (t << 14);
+  t = (hi ^ (hi >> 14)) & 0x0000CCCCu; hi = hi ^ t ^ (t << 14);
+  t = (lo ^ ((lo >> 28) | (hi << 4))) & 0xF0F0F0F0u;
+  lo = lo ^ t ^ (t << 28);
+  hi = hi ^ (t >> 4);
 }
 
 #endif  // __HIPCC__

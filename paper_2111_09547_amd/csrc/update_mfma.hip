@@ -30,24 +30,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kRowsPerWave = 32;
 constexpr int kPad = 16;   // bytes of padding per LDS row of W
 
-// 4 bits -> bit 0 of each of 4 bytes: the four shifted copies of x do not overlap.
-__device__ __forceinline__ uint32_t spread4(uint32_t x4) {
-  return __umul24(x4, 0x204081u) & 0x01010101u;
-}
-
-// 16-bit fields of up to 8 planes -> 16 bytes (as 4 dwords), byte j = sum_p bit_j(plane p) << p.
-// Planes past the operand's bit width are passed as zeros.
-__device__ __forceinline__ void planes_to_bytes(const uint32_t (&f)[8], int nplanes, uint32_t (&d)[4]) {
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    uint32_t v = 0u;
-#pragma unroll
-    for (int pl = 0; pl < 8; ++pl)
-      if (pl < nplanes) v |= spread4((f[pl] >> (4 * q)) & 0xfu) << pl;   // wave-uniform test
-    d[q] = v;
-  }
-}
-
 __device__ __forceinline__ v4i as_v4i(const uint32_t (&d)[4]) {
   v4i v = {(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
   return v;

@@ -51,7 +51,7 @@ class QuantGNN:
         self.W = [B.alloc_bits(d, h, t, B.RIGHT) for d, h in self.dims]
         n = self.A.rows
         dmax = max(d for d, _ in self.dims)
-        ws_bytes = B.lib().qgtc_layer_workspace_bytes(n, dmax, s)
+        ws_bytes = max(B.lib().qgtc_layer_workspace_bytes(n, d, h, s) for d, h in self.dims)
         self.workspace = torch.empty(ws_bytes // 4 + 1, dtype=torch.int32, device=self.A.words.device)
         # ping-pong buffers for the low-bit activations between layers
         hmax = max(h for _, h in self.dims)
@@ -151,15 +151,6 @@ class QuantGNN:
                 return B.qgtc_layer(self.A, self.map, xb, W, agg_ep, B.Epilogue(mode=B.OUT_I32),
                                     self.workspace, out=out)
             else:
-                yb = B.qgtc_aggregate(self.A, self.map, xb, agg_ep,
-                                      out=self._y_bits(self.dims[l][0]))
-                rs = B.qgtc_row_sums(yb)
-                ep = self.last_layer_dequant(l, x_lo, x_scale, r.agg_hi, rs)
-                return B.qgtc_update(yb, W, ep, out=out)
-
-    def _y_bits(self, cols: int) -> B.Bits:
-        d, _ = B.describe(self.A.rows, cols, self.s, B.LEFT)
-        d.ld_words = -(-cols // 32)
-        d.plane_stride_words = self.A.rows * d.ld_words
-        d.data = self.workspace.data_ptr()
-        return B.Bits(self.workspace, d)
+                # row_i = None: the layer takes the row sums of its own requantized Y
+                ep = self.last_layer_dequant(l, x_lo, x_scale, r.agg_hi, None)
+                return B.qgtc_layer(self.A, self.map, xb, W, agg_ep, ep, self.workspace, out=out)

@@ -43,7 +43,7 @@ def test_describe_and_sizes():
     nb = b.lib().qgtc_tile_map_bytes(256, 256, 16, 128)
     assert nb >= (16 + 16 * 2 + 1 + 256) * 4
     assert b.lib().qgtc_tile_map_bytes(256, 256, 7, 128) == 0
-    assert b.lib().qgtc_layer_workspace_bytes(100, 70, 4) >= 100 * 3 * 4 * 4
+    assert b.lib().qgtc_layer_workspace_bytes(100, 70, 16, 4) >= 100 * 3 * 4 * 4 + 100 * 4
 
 
 def test_status_strings():

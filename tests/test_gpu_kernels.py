@@ -264,6 +264,91 @@ def test_layer_matches_oracle(cfg, bits, nb):
 
 
 # ------------------------------------------------- update on the matrix cores
+# ------------------------------------------------------------------- fused layer
+def _layer_case(rng, n, d, h, s, t, block, self_term, p_edge=0.06):
+    A = np.zeros((n, n), dtype=np.uint8)
+    if block:
+        for b0 in range(0, n, block):
+            b1 = min(n, b0 + block)
+            A[b0:b1, b0:b1] = rand_graph(rng, b1 - b0, b1 - b0, p_edge)
+    else:
+        A = rand_graph(rng, n, n, p_edge)
+    if self_term:
+        A[np.arange(n), np.arange(n)] = 0
+    Xq = rng.integers(0, 2 ** s, size=(n, d)).astype(np.uint32)
+    Wq = rng.integers(0, 2 ** t, size=(d, h)).astype(np.uint32)
+    return A, Xq, Wq
+
+
+@pytest.mark.parametrize("shape", [(40, 33, 5), (100, 64, 64), (330, 70, 16), (257, 128, 100),
+                                   (530, 200, 256), (96, 512, 16), (200, 600, 40), (64, 1024, 24)])
+@pytest.mark.parametrize("st", [(8, 8), (8, 3), (4, 8), (7, 7), (1, 1), (2, 5)])
+def test_fused_layer_all_outputs(shape, st):
+    """qgtc_layer as one kernel: int32, packed low-bit and fp32 outputs against the
+    oracle, and against the same call run as two kernels, for every way of
+    splitting the tile lists between waves."""
+    n, d, h = shape
+    s, t = st
+    rng = np.random.default_rng([11, n, d, h, s, t])
+    block = 96 if n % 2 == 0 else 0
+    self_term = (n + s) % 2 == 0
+    A, Xq, Wq = _layer_case(rng, n, d, h, s, t, block, self_term)
+    Y = qgnn.aggregate(A, Xq, self_term)
+    rq_inv = qgnn.inv_scale(0.0, float(max(1, qgnn.as_signed(Y).max())), s)
+    Yq = qgnn.requantize(Y, 0, rq_inv, s)
+    Z = qgnn.update(Yq, Wq)
+
+    Xb = q.qgtc_pack_bits(dev(Xq.view(np.int32)), s, q.RIGHT)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=s, rq_lo=0, rq_inv_scale=float(rq_inv),
+                        self_term=self_term)
+    out_bits = min(s, 6)
+    z_inv = qgnn.inv_scale(0.0, float(max(1, qgnn.as_signed(Z).max())), out_bits)
+    want_bits = bp.pack(qgnn.requantize(Z, 3, z_inv, out_bits, relu=True), out_bits, bp.RIGHT)
+    rl = rng.integers(1, 30, size=n).astype(np.int32)
+    cs = Wq.sum(axis=0).astype(np.int32)
+    kw = dict(cc=1.7e-3, rs=-0.031, l0a=0.4, l0b=-0.9, ck=-6.4, cs=0.0125)
+    want_f32 = qgnn.dequantize(Z, row_i=Yq.sum(axis=1, dtype=np.int64), row_l=rl, col_i=cs, **kw)
+
+    storages = [(pack_adjacency(A), 128), (pack_adjacency(A), None)]
+    if block:
+        compact = np.zeros((n, block), dtype=np.uint8)
+        for r in range(n):
+            b0 = (r // block) * block
+            seg = A[r, b0:b0 + block]
+            compact[r, :seg.size] = seg
+        storages.append((q.qgtc_pack_bits(dev(compact), 1, q.LEFT, block_rows=block), 32))
+    try:
+        for Ab, kb in storages:
+            m = q.qgtc_build_tile_map(Ab, 16, kb) if kb else None
+            for path, ksplit in ((q.LAYER_FUSED, 0), (q.LAYER_FUSED, 1), (q.LAYER_FUSED, 2),
+                                 (q.LAYER_FUSED, 4), (q.LAYER_TWO_KERNELS, 0)):
+                q.qgtc_set_option(q.OPT_LAYER_PATH, path)
+                q.qgtc_set_option(q.OPT_LAYER_KSPLIT, ksplit)
+                tag = (kb, path, ksplit)
+                q.qgtc_prof_enable(True)
+                q.qgtc_prof_reset()
+                got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32))
+                fused_launches = q.qgtc_prof_read(q.KERNEL_LAYER)[1]
+                q.qgtc_prof_enable(False)
+                q.qgtc_prof_reset()
+                assert fused_launches == (1 if path == q.LAYER_FUSED else 0), tag
+                assert (as_u32(got) == Z).all(), tag
+                ep = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=out_bits, rq_lo=3,
+                                rq_inv_scale=float(z_inv))
+                # poison the destination: every word, padding included, must be written
+                dst = q.alloc_bits(n, h, out_bits, q.RIGHT)
+                dst.words.fill_(-1)
+                got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep, out=dst)
+                assert (words_np(got) == want_bits).all(), tag
+                ep = q.Epilogue(mode=q.OUT_F32, row_i=None, row_l=dev(rl), col_i=dev(cs), **kw)
+                got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep).cpu().numpy()
+                assert np.allclose(got, want_f32, rtol=1e-6, atol=1e-6 * np.abs(want_f32).max()), tag
+    finally:
+        q.qgtc_set_option(q.OPT_LAYER_PATH, q.LAYER_FUSED)
+        q.qgtc_set_option(q.OPT_LAYER_KSPLIT, 0)
+
+
 @pytest.mark.parametrize("st", [(1, 1), (2, 3), (4, 4), (7, 7), (8, 8), (8, 2), (3, 8), (8, 7)])
 @pytest.mark.parametrize("shape", [(100, 64, 64), (257, 128, 16), (70, 40, 5), (1000, 512, 16), (64, 300, 70),
                                    (4096, 64, 64), (33, 16, 130)])
