@@ -29,6 +29,11 @@ sys.path.insert(0, ROOT)
 VALU_LANE_OPS = 256 * 64 * 2.4e9
 PEAK_BITOPS = VALU_LANE_OPS / 2 * 64          # 1.258e15 bit-op/s
 
+# HBM bytes per launch of the dominant kernel (read + write), from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarized under profiles/ (counters cannot be read
+# from inside this process); keyed by (config, bits).  None: not profiled.
+TRAFFIC = {}
+
 
 def workload_bitops(net, n_nodes, tile_kbits):
     """Executed bit-operations of one forward pass, per kernel family."""
@@ -91,7 +96,7 @@ def main():
 
     import torch
     import paper_2111_09547_amd as q
-    from paper_2111_09547_amd.model import QuantGNN
+    from paper_2111_09547_amd.model import QuantGNN, fused_layer_applies
     from workloads import make_workload
 
     torch.cuda.set_device(0)
@@ -148,32 +153,35 @@ def main():
         step()
     torch.cuda.synchronize()
     kinds = {"pack": q.KERNEL_PACK, "tile_map": q.KERNEL_TILE_MAP, "aggregate": q.KERNEL_AGGREGATE,
-             "update": q.KERNEL_UPDATE, "sums": q.KERNEL_SUMS}
+             "update": q.KERNEL_UPDATE, "sums": q.KERNEL_SUMS, "layer": q.KERNEL_LAYER}
     prof = {k: q.qgtc_prof_read(v) for k, v in kinds.items()}
     q.qgtc_prof_enable(False)
     q.qgtc_prof_reset()
 
-    # the update alone on both of its kernels (popcount on the vector ALUs vs int8 matrix cores)
-    upd_paths = {}
-    for name, path in (("popcount", q.UPDATE_POPCOUNT), ("matrix_cores", q.UPDATE_MATRIX_CORES)):
-        q.qgtc_set_option(q.OPT_UPDATE_PATH, path)
-        layers_only()
-        q.qgtc_prof_enable(True)
-        q.qgtc_prof_reset()
-        for _ in range(20):
-            layers_only()
-        torch.cuda.synchronize()
-        upd_paths[name + "_ms_per_step"] = q.qgtc_prof_read(q.KERNEL_UPDATE)[0] / 20
-        q.qgtc_prof_enable(False)
-        q.qgtc_prof_reset()
-    q.qgtc_set_option(q.OPT_UPDATE_PATH, q.UPDATE_AUTO)
+    # the same forward pass as separate aggregation and update kernels (what the fused
+    # layer kernel replaces)
+    q.qgtc_set_option(q.OPT_LAYER_PATH, q.LAYER_TWO_KERNELS)
+    planes = QuantGNN(A_src, Ws, w.s, w.t, self_term, tile_kbits=args.tile_kbits,
+                      block_rows=block_rows, weights_as_bytes=False)
+    for _ in range(3):
+        planes.forward(X, xr, ranges, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        planes.forward(X, xr, ranges, out=out)
+    torch.cuda.synchronize()
+    ms_two_kernels = (time.perf_counter() - t0) * 1e3 / 20
+    q.qgtc_set_option(q.OPT_LAYER_PATH, q.LAYER_FUSED)
+    del planes
 
     agg_ops, upd_ops, nnz = workload_bitops(net, g.n_nodes, args.tile_kbits)
     total_ops = sum(agg_ops) + sum(upd_ops)
-    agg_ms, agg_n = prof["aggregate"]
-    upd_ms, upd_n = prof["update"]
-    agg_rate = sum(agg_ops) * args.steps / (agg_ms * 1e-3)          # bit-op/s over all launches
-    upd_rate = sum(upd_ops) * args.steps / (upd_ms * 1e-3)
+    # the dominant kernel: the fused layer kernel where it applies, else the aggregation
+    fused = prof["layer"][1] > 0
+    dom_ms, dom_n = prof["layer"] if fused else prof["aggregate"]
+    fused_layers = [fused_layer_applies(d, h, w.s, w.t) for d, h in net.dims]
+    dom_ops = sum(o for o, f in zip(agg_ops, fused_layers) if f == fused)
+    agg_rate = dom_ops * args.steps / (dom_ms * 1e-3)               # bit-op/s over all launches
     n_layers = len(net.dims)
     dense_macs = sum(2.0 * g.n_nodes * g.block * d + 2.0 * g.n_nodes * d * h for d, h in net.dims)
 
@@ -194,16 +202,16 @@ def main():
         "ms_per_layer": ms_layers / n_layers,
         "ms_layers_only": ms_layers,
         "tops_equiv_dense": dense_macs / (ms_layers * 1e-3) / 1e12,
-        "roofline": {"bound": "alu", "kernel": "aggregate_kernel",
+        "ms_layers_two_kernels": ms_two_kernels,
+        "roofline": {"bound": "alu", "kernel": "layer_kernel" if fused else "aggregate_kernel",
                      "achieved": agg_rate / 1e12, "peak": PEAK_BITOPS / 1e12,
                      "unit": "Tbit-op/s", "frac": agg_rate / PEAK_BITOPS,
-                     "avg_launch_ms": agg_ms / max(agg_n, 1), "launches": agg_n,
-                     "traffic": None},
+                     "avg_launch_ms": dom_ms / max(dom_n, 1), "launches": dom_n,
+                     "counted": "executed AND+popcount bit-ops of the aggregation only; the update "
+                                "inside the same kernel runs on the matrix cores and is not counted",
+                     "traffic": TRAFFIC.get((w.cfg, w.s))},
         "kernels": {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps}
                     for k, v in prof.items()},
-        "update": {"path": "int8 matrix cores (automatic choice for s*t >= 4, s,t <= 8)"
-                           if w.s * w.t >= 4 and w.s <= 8 and w.t <= 8 else "popcount",
-                   "bit_ops_equiv_rate": upd_rate / 1e12, "unit": "Tbit-op/s", **upd_paths},
     }
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w, ranges, total_ops)

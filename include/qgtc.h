@@ -67,8 +67,22 @@ const char* qgtc_status_string(qgtc_status s);
  * only the cols == block_rows entries of its own diagonal block, entry j
  * standing for column (r / block_rows) * block_rows + j.  block_rows must be a
  * multiple of 32.
+ *
+ * QGTC_RIGHT_BYTES (weights W of qgtc_layer only; K x cols, nbits <= 8): the codes
+ * themselves, one byte each, in the operand order of the int8 matrix instruction
+ * that the fused layer kernel feeds (the paper caches the decomposed W across
+ * subgraphs, end of Section 3.2; this is the form to cache here).  Columns are
+ * taken in tiles of 16 and K in steps of 64; the 1 KiB block of (tile nt, step ks)
+ * holds, for lane l = c % 16 + 16 * ((k % 64) / 16), the 16 consecutive bytes
+ * k % 16 = 0..15 of column c, row k:
+ *   byte(k, c) = bytes[part * 4 * plane_stride_words + (c / 16) * 4 * ld_words +
+ *                      (k / 64) * 1024 + l * 16 + k % 16]
+ * with ld_words = 256 * ceil(rows / 64) and plane_stride_words = ceil(cols / 16) *
+ * ld_words.  8-bit codes are stored as two parts, their low 7 bits (part 0) and
+ * their top bit (part 1), because the instruction multiplies signed bytes;
+ * narrower codes have part 0 only.  Zero fill.  data must be 16-byte aligned.
  * ------------------------------------------------------------------------- */
-enum { QGTC_LEFT = 0, QGTC_RIGHT = 1 };
+enum { QGTC_LEFT = 0, QGTC_RIGHT = 1, QGTC_RIGHT_BYTES = 2 };
 
 typedef struct qgtc_bits {
   uint32_t* data;
@@ -86,6 +100,7 @@ typedef struct qgtc_bits {
  * strides and returns the number of 32-bit words the buffer needs:
  *   LEFT : ld = 4*ceil(cols/128), plane stride = rows*ld
  *   RIGHT: ld = cols,             plane stride = ceil(rows/32)*ld
+ *   RIGHT_BYTES: as stated above; the return value covers both parts for 8 bits
  * d->data is left untouched.  Returns 0 on invalid arguments. */
 size_t qgtc_describe(qgtc_bits* d, int32_t rows, int32_t cols, int32_t nbits,
                      int32_t layout, int32_t block_rows);
@@ -109,19 +124,21 @@ enum { QGTC_SRC_F32 = 0, QGTC_SRC_U8 = 1, QGTC_SRC_I32 = 2 };
  * planes and pack into dst ("Tensor.to_bit", Sections 4.2 and 5).
  * src: device, row-major rows x cols with leading dimension ld_src (elements).
  * dst: descriptor filled by the caller (qgtc_describe) with rows/cols equal to
- * the arguments; every word of the packed matrix, padding included, is written. */
+ * the arguments; every word of the packed matrix, padding included, is written.
+ * Any of the three layouts. */
 qgtc_status qgtc_pack_bits(const void* src, int32_t src_dtype, int32_t rows,
                            int32_t cols, int64_t ld_src, const qgtc_quant* q,
                            const qgtc_bits* dst, void* stream);
 
-/* Decode packed planes back to one uint32 per entry ("Tensor.to_val",
- * Section 5).  dst: device, row-major rows x cols, leading dimension ld_dst. */
+/* Decode a packed matrix (any layout) back to one uint32 per entry
+ * ("Tensor.to_val", Section 5).  dst: device, row-major rows x cols, leading
+ * dimension ld_dst. */
 qgtc_status qgtc_unpack_bits(const qgtc_bits* src, uint32_t* dst, int64_t ld_dst,
                              void* stream);
 
 /* Value sums of a packed matrix, sum_p 2^p * popcnt, modulo 2^32:
- * per row of a LEFT operand (out: rows entries) or per column of a RIGHT
- * operand (out: cols entries).  They feed the dequantizing epilogue below. */
+ * per row of a LEFT operand (out: rows entries) or per column of a RIGHT or
+ * RIGHT_BYTES operand (out: cols entries).  They feed the dequantizing epilogue below. */
 qgtc_status qgtc_row_sums(const qgtc_bits* m, int32_t* out, void* stream);
 qgtc_status qgtc_col_sums(const qgtc_bits* m, int32_t* out, void* stream);
 
@@ -228,6 +245,9 @@ qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W,
  * through LDS as bytes straight into the int8 matrix cores.  Otherwise the
  * call runs qgtc_aggregate into packed planes in `workspace`, then qgtc_update.
  * Both give the same integers.
+ * W: RIGHT (planes; the fused kernel is preceded by a small kernel that re-orders
+ * them) or RIGHT_BYTES (taken as it is; QGTC_ERR_UNSUPPORTED when the fused
+ * kernel does not apply).
  * upd_ep in QGTC_OUT_F32 mode: with row_i == NULL and rs != 0 the row sums of
  * the requantized aggregation result (the left operand of the update, which only
  * exists inside the call) are taken for row_i.

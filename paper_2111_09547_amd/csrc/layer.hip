@@ -87,6 +87,13 @@ __global__ __launch_bounds__(256) void weight_bytes_kernel(const uint32_t* W, in
   *reinterpret_cast<v4u*>(dst) = lo;
 }
 
+// Parameters that only the phases after the tile loop need are read from the
+// kernel-argument segment through a pointer the compiler cannot see through, at
+// the point of use: loaded at kernel entry (where the compiler puts every argument
+// load) they would sit in ~200 SGPRs across the tile loop and be spilled.
+typedef const __attribute__((address_space(4))) LayerParams* LateParams;
+#define QGTC_LATE(ptr) asm volatile("" : "+s"(ptr))
+
 template <int S, int TW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void layer_kernel(const LayerParams p) {
   extern __shared__ uint32_t lds[];
@@ -94,6 +101,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
   const unsigned bid = xcd_deal(blockIdx.x, a.chunk_shift);
   if (bid >= a.nblocks) return;                      // whole workgroup leaves together
   const int tr = (int)bid;                           // tile row of this workgroup
+  LateParams kp = (LateParams)__builtin_amdgcn_kernarg_segment_ptr();
 
   const int nw = (int)(blockDim.x >> 6);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -118,9 +126,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
   __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.X, 0, (int)a.x_bytes, 0x00020000);
   const int km = a.ksplit - 1;                       // ksplit is 1, 2 or 4
 
-  const EpiParams& ea = a.ep;
-  const uint32_t qmax_a = (1u << ea.rq_nbits) - 1u;  // at most 8 bits here
-  const float qmaxf_a = (float)qmax_a;
+  // B operands of the first matrix instruction of this wave, fetched while the Y tile
+  // is still being finished
+  const int ln = lane & 15;                          // row of Y / column of W inside a tile
+  const int g = lane >> 4;                           // K sub-block, and row group of the result
+  v4u b7_first, bb_first;                            // set in the last pass
 
   // ---- 1 + 2: aggregate, requantize, bytes into the Y tile ---------------------
   for (int pass = 0; pass < p.n_pass; ++pass) {
@@ -144,6 +154,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       y[j] = v;
     }
 
+    LateParams k2 = kp;
+    QGTC_LATE(k2);
+    if (pass == p.n_pass - 1) {
+      // unit `wave` is output tile `wave`, first chunk of K (see phase 3); a wave
+      // without such a unit fetches tile 0 and does not use it
+      const int nt0 = wave < k2->n_nt_w ? wave : 0;
+      const uint8_t* src = k2->wb + ((int64_t)(nt0 * k2->n_ks) * 64 + lane) * 16;
+      b7_first = *reinterpret_cast<const v4u*>(src);
+      bb_first = *reinterpret_cast<const v4u*>(src + (k2->split_w ? k2->wb_part : 0));
+    }
+
     // K split: wave (wcg, kpart) finishes the rows j with j % ksplit == kpart
     if (a.ksplit > 1) {
       if (pass > 0) __syncthreads();                 // the sums of the previous pass have been read
@@ -154,14 +175,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       for (int j = 0; j < 16; ++j) {
         if ((j & km) != kpart) continue;             // wave-uniform
         uint32_t v = 0u;
-        for (int kp = 0; kp < a.ksplit; ++kp) v += part[((kp * p.cgw + wcg) * 16 + j) * 64 + lane];
+        for (int kp2 = 0; kp2 < a.ksplit; ++kp2) v += part[((kp2 * p.cgw + wcg) * 16 + j) * 64 + lane];
         y[j] = v;
       }
     }
 
     // GIN self term: the 16 bits (row0 % 32 ..) of word row (row0 / 32) of every
     // plane of X are this lane's codes of the 16 rows, bit-transposed
-    if (ea.self_term != 0) {
+    if (k2->a.ep.self_term != 0) {
       const uint32_t srow = min((uint32_t)(out_row0 >> 5), kw_max);
       const uint32_t voff = srow * a.ldx4 + col4;
       const int bit0 = out_row0 & 31;
@@ -182,97 +203,136 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       for (int j = 0; j < 16; ++j) y[j] += (sw[j >> 2] >> (8 * (j & 3))) & 0xffu;
     }
 
+    {
+      const int relu = k2->a.ep.relu;
+      const int32_t rq_lo = k2->a.ep.rq_lo;
+      const float rq_inv = k2->a.ep.rq_inv_scale;
+      const uint32_t qmax = (1u << k2->a.ep.rq_nbits) - 1u;   // at most 8 bits here
+      const float qmaxf = (float)qmax;
+      const int ys = k2->ys;
+      const int valid_rows = a.rows - out_row0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      if ((j & km) != kpart) continue;
-      const bool ok = c_ok && (out_row0 + j) < a.rows;
-      const uint32_t q = ok ? requantize_i32(y[j], ea, qmax_a, qmaxf_a) : 0u;
-      if (cg_ok) yb[j * p.ys + c] = (uint8_t)q;
+      for (int j = 0; j < 16; ++j) {
+        if ((j & km) != kpart) continue;
+        uint32_t q = requantize_code(y[j], relu, rq_lo, rq_inv, qmax, qmaxf);
+        q = (c_ok && j < valid_rows) ? q : 0u;
+        if (cg_ok) yb[j * ys + c] = (uint8_t)q;
+      }
     }
   }
   __syncthreads();
 
   // ---- 3: Z += Y tile x W on the matrix cores -----------------------------------
+  // A unit is an output tile (16 columns) times a chunk of K steps; unit u goes to
+  // wave u % nw, units u < n_nt cover the first chunk.
   {
-    const int ln = lane & 15;                        // row of Y / column of W inside a tile
-    const int g = lane >> 4;                         // K sub-block, and row group of the result
-    const int n_units = p.n_nt * p.n_kc;
+    LateParams k3 = kp;
+    QGTC_LATE(k3);
+    const int n_nt = k3->n_nt, n_nt_w = k3->n_nt_w, n_ks = k3->n_ks, ks_per = k3->ks_per;
+    const int ys = k3->ys, zs = p.zs;
+    const bool split_y = k3->split_y != 0, split_w = k3->split_w != 0;
+    const uint8_t* wb = k3->wb;
+    const int64_t wb_part = k3->wb_part;
+    const int n_units = n_nt * k3->n_kc;
     for (int u = wave; u < n_units; u += nw) {
-      const int nt = u % p.n_nt;
-      const int kc = u / p.n_nt;
-      const int ks1 = min((kc + 1) * p.ks_per, p.n_ks);
-      const bool ones = nt >= p.n_nt_w;              // the tile whose column 0 sums the rows of Y
+      const int nt = u % n_nt;
+      const int kc = u / n_nt;
+      const int ks0 = kc * ks_per;
+      const int ks1 = min(ks0 + ks_per, n_ks);
+      const bool ones = nt >= n_nt_w;                // the tile whose column 0 sums the rows of Y
       v4i acc1 = {0, 0, 0, 0}, acc7 = {0, 0, 0, 0}, acc14 = {0, 0, 0, 0};
-      for (int ks = kc * p.ks_per; ks < ks1; ++ks) {
-        const v4u av = *reinterpret_cast<const v4u*>(yb + ln * p.ys + ks * 64 + g * 16);
+      for (int ks = ks0; ks < ks1; ++ks) {
+        const v4u av = *reinterpret_cast<const v4u*>(yb + ln * ys + ks * 64 + g * 16);
         v4u a7 = av, ab = {0u, 0u, 0u, 0u};
-        if (p.split_y) {
+        if (split_y) {
           a7 = av & 0x7f7f7f7fu;
           ab = (av >> 7) & 0x01010101u;
         }
         v4u b7 = {0u, 0u, 0u, 0u}, bb = {0u, 0u, 0u, 0u};
         if (ones) {
           if (ln == 0) b7 = (v4u){0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
+        } else if (u == wave && ks == 0) {
+          b7 = b7_first;                             // u == wave < n_nt: chunk 0, so ks0 == 0
+          bb = bb_first;
         } else {
-          const uint8_t* src = p.wb + ((int64_t)(nt * p.n_ks + ks) * 64 + lane) * 16;
+          const uint8_t* src = wb + ((int64_t)(nt * n_ks + ks) * 64 + lane) * 16;
           b7 = *reinterpret_cast<const v4u*>(src);
-          if (p.split_w) bb = *reinterpret_cast<const v4u*>(src + p.wb_part);
+          if (split_w) bb = *reinterpret_cast<const v4u*>(src + wb_part);
         }
         acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)b7, acc1, 0, 0, 0);
-        if (p.split_y) acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)b7, acc7, 0, 0, 0);
-        if (p.split_w && !ones) {
+        if (split_y) acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)b7, acc7, 0, 0, 0);
+        if (split_w && !ones) {
           acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)bb, acc7, 0, 0, 0);
-          if (p.split_y) acc14 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)bb, acc14, 0, 0, 0);
+          if (split_y) acc14 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)bb, acc14, 0, 0, 0);
         }
       }
       // element r of the result: row 4 g + r, column ln of the tile
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const uint32_t v = (uint32_t)acc1[r] + ((uint32_t)acc7[r] << 7) + ((uint32_t)acc14[r] << 14);
-        atomicAdd(&z[(4 * g + r) * p.zs + nt * 16 + ln], v);
+        atomicAdd(&z[(4 * g + r) * zs + nt * 16 + ln], v);
       }
     }
   }
   __syncthreads();
 
   // ---- 4: epilogue, lane <-> output column ---------------------------------------
-  const EpiParams& e = p.up;
-  for (int hb = wave * 64; hb < p.h; hb += nw * 64) {
+  LateParams k4 = kp;
+  QGTC_LATE(k4);
+  const int n_out = k4->h;
+  const int zs = p.zs;
+  const int mode = k4->up.mode;
+  const int valid_rows = a.rows - out_row0;
+  for (int hb = wave * 64; hb < n_out; hb += nw * 64) {
     const int h = hb + lane;
-    const bool h_ok = h < p.h;
-    const int hc = h_ok ? h : p.h - 1;
+    const bool h_ok = h < n_out;
+    const int hc = h_ok ? h : n_out - 1;
     uint32_t zz[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) zz[j] = z[j * p.zs + hc];
+    for (int j = 0; j < 16; ++j) zz[j] = z[j * zs + hc];
 
-    if (e.mode == QGTC_OUT_I32) {
+    if (mode == QGTC_OUT_I32) {
+      const int relu = k4->up.relu;
+      int32_t* out = reinterpret_cast<int32_t*>(k4->up.out) + (int64_t)out_row0 * k4->up.ld_out + h;
+      const int64_t ld_out = k4->up.ld_out;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const int row = out_row0 + j;
         int32_t o = (int32_t)zz[j];
-        if (e.relu && o < 0) o = 0;
-        if (h_ok && row < a.rows) reinterpret_cast<int32_t*>(e.out)[(int64_t)row * e.ld_out + h] = o;
+        if (relu && o < 0) o = 0;
+        if (h_ok && j < valid_rows) out[j * ld_out] = o;
       }
-    } else if (e.mode == QGTC_OUT_F32) {
+    } else if (mode == QGTC_OUT_F32) {
+      EpiParams e;
+      e.relu = k4->up.relu;
+      e.cc = k4->up.cc; e.rs = k4->up.rs; e.l0a = k4->up.l0a; e.l0b = k4->up.l0b;
+      e.ck = k4->up.ck; e.cs = k4->up.cs;
+      e.row_i = k4->up.row_i; e.row_l = k4->up.row_l; e.col_i = k4->up.col_i;
+      float* out = reinterpret_cast<float*>(k4->up.out);
+      const int64_t ld_out = k4->up.ld_out;
+      const int want_rowsum = k4->want_rowsum;
+      const int sum_col = k4->n_nt_w * 16;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         const int row = out_row0 + j;
-        if (h_ok && row < a.rows) {
+        if (h_ok && j < valid_rows) {
           double ri = 0.0;
-          if (p.want_rowsum) ri = (double)z[j * p.zs + p.n_nt_w * 16];
+          if (want_rowsum) ri = (double)z[j * zs + sum_col];
           else if (e.row_i) ri = (double)e.row_i[row];
-          reinterpret_cast<float*>(e.out)[(int64_t)row * e.ld_out + h] = dequantize_f64_ri(zz[j], ri, row, h, e);
+          out[(int64_t)row * ld_out + h] = dequantize_f64_ri(zz[j], ri, row, h, e);
         }
       }
     } else {
-      const int qbits = e.rq_nbits;                  // at most 8 here
+      const int relu = k4->up.relu;
+      const int32_t rq_lo = k4->up.rq_lo;
+      const float rq_inv = k4->up.rq_inv_scale;
+      const int qbits = k4->up.rq_nbits;             // at most 8 here
       const uint32_t qmax = (1u << qbits) - 1u;
       const float qmaxf = (float)qmax;
       uint32_t b[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const bool ok = h_ok && (out_row0 + j) < a.rows;
-        const uint32_t q = ok ? requantize_i32(zz[j], e, qmax, qmaxf) : 0u;
+        uint32_t q = requantize_code(zz[j], relu, rq_lo, rq_inv, qmax, qmaxf);
+        q = (h_ok && j < valid_rows) ? q : 0u;
         b[j >> 2] |= q << (8 * (j & 3));
       }
       transpose_bits_8x8(b[0], b[1]);                // byte i: bit i of the codes of rows 0..7
@@ -281,16 +341,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       // owns the lower or the upper 16 bits.  The last tile of a matrix whose row
       // count leaves the upper half without a tile writes the whole word.
       const bool upper = (out_row0 & 16) != 0;
-      const bool whole = !upper && out_row0 + 16 >= a.rows;
-      uint8_t* dst = reinterpret_cast<uint8_t*>(e.out) +
-                     (((int64_t)(out_row0 >> 5) * e.ld_out + hc) << 2) + (upper ? 2 : 0);
+      const bool whole = !upper && valid_rows <= 16;
+      const int64_t ps4 = k4->up.ps_out * 4;
+      uint8_t* dst = reinterpret_cast<uint8_t*>(k4->up.out) +
+                     (((int64_t)(out_row0 >> 5) * k4->up.ld_out + hc) << 2) + (upper ? 2 : 0);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const uint32_t w0 = (b[i >> 2] >> (8 * (i & 3))) & 0xffu;
         const uint32_t w1 = (b[2 + (i >> 2)] >> (8 * (i & 3))) & 0xffu;
         const uint32_t word = w0 | (w1 << 8);
         if (i < qbits && h_ok) {
-          uint8_t* d = dst + (int64_t)i * e.ps_out * 4;
+          uint8_t* d = dst + i * ps4;
           if (whole) *reinterpret_cast<uint32_t*>(d) = word;
           else *reinterpret_cast<uint16_t*>(d) = (uint16_t)word;
         }
@@ -323,19 +384,20 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
                         void* workspace, size_t workspace_bytes, void* out, int64_t ld_out,
                         hipStream_t stream, bool* done) {
   *done = false;
-  if (layer_path_option() == 1) return QGTC_OK;
+  if (layer_path_option() == 1 && W && W->layout != QGTC_RIGHT_BYTES) return QGTC_OK;
   if (!A || !X || !W || !agg_ep || !upd_ep || !workspace || !out) return QGTC_OK;
   // what the kernel covers; everything else takes the two-kernel path
   if (X->nbits > 8 || W->nbits > 8 || agg_ep->rq_nbits < 1 || agg_ep->rq_nbits > 8) return QGTC_OK;
   if (upd_ep->mode == QGTC_OUT_BITS && upd_ep->rq_nbits > 8) return QGTC_OK;
   if (X->cols <= 32 || X->cols > 1024 || W->cols < 1 || W->cols > 256) return QGTC_OK;
   if (A->rows < 1) return QGTC_OK;
-  if (workspace_bytes < layer_fused_workspace_bytes(X->cols, W->cols)) return QGTC_OK;
+  const bool w_bytes = W->layout == QGTC_RIGHT_BYTES;
+  if (!w_bytes && workspace_bytes < layer_fused_workspace_bytes(X->cols, W->cols)) return QGTC_OK;
   if (!(agg_ep->rq_inv_scale > 0.0f)) return QGTC_OK;
 
   LayerParams p{};
   if (agg_fill_params(A, map, X, &p.a) != QGTC_OK) return QGTC_OK;
-  if (check_bits(W, QGTC_RIGHT) != QGTC_OK || W->rows != X->cols) return QGTC_OK;
+  if (check_bits(W, w_bytes ? QGTC_RIGHT_BYTES : QGTC_RIGHT) != QGTC_OK || W->rows != X->cols) return QGTC_OK;
   const bool square = A->block_rows > 0 || A->rows == A->cols;
   if (agg_ep->self_term && !square) return QGTC_OK;
   if (make_epilogue(upd_ep, out, ld_out, A->rows, W->cols, QGTC_RIGHT, false, &p.up) != QGTC_OK)
@@ -357,14 +419,17 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   a.nblocks = (uint32_t)a.n_tile_rows;
   p.cgw = a.n_cg <= 4 ? a.n_cg : (a.n_cg % 3 == 0 ? 3 : 4);
   p.n_pass = cdiv(a.n_cg, p.cgw);
-  // few waves: let two or four waves split each tile list
+  // Waves that split each tile list: as many as it takes to put ~3000 waves on the
+  // chip when there are few tile rows; with two column groups, workgroups of four
+  // waves measured faster than pairs, so the lists are split in two there as well.
   a.ksplit = 1;
   const int opt_k = layer_ksplit_option();
   if (opt_k > 0) {
     a.ksplit = opt_k;
     while (p.cgw * a.ksplit > 4 && a.ksplit > 1) a.ksplit >>= 1;
   } else {
-    while ((int64_t)a.n_tile_rows * p.cgw * a.ksplit < 6144 && p.cgw * a.ksplit * 2 <= 4) a.ksplit *= 2;
+    while ((int64_t)a.n_tile_rows * p.cgw * a.ksplit < 3072 && p.cgw * a.ksplit * 2 <= 4) a.ksplit *= 2;
+    if (p.cgw == 2 && a.ksplit == 1) a.ksplit = 2;
   }
   const unsigned nw = (unsigned)(p.cgw * a.ksplit);
   a.chunk_shift = agg_chunk_shift(1, a.nblocks);
@@ -388,17 +453,21 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   const size_t lds_bytes = (size_t)(p.z_off + 16 * p.zs) * 4;
   if (lds_bytes > 64 * 1024) return QGTC_OK;
 
-  uint8_t* wb = reinterpret_cast<uint8_t*>(workspace);
-  p.wb = wb;
-  p.wb_part = (int64_t)p.n_nt_w * p.n_ks * 1024;
-
   ProfScope prof(QGTC_KERNEL_LAYER, stream);
-  const int prep_threads = p.n_nt_w * p.n_ks * 64;
-  hipLaunchKernelGGL(weight_bytes_kernel, dim3((unsigned)cdiv(prep_threads, 256)), dim3(256), 0, stream,
-                     W->data, W->ld_words, W->plane_stride_words, W->nbits, cdiv(W->rows, 32), W->cols,
-                     p.n_nt_w, p.n_ks, p.split_w, wb, p.wb_part);
-  qgtc_status st = launch_status();
-  if (st != QGTC_OK) return st;
+  if (w_bytes) {
+    p.wb = reinterpret_cast<const uint8_t*>(W->data);
+    p.wb_part = W->plane_stride_words * 4;
+  } else {
+    uint8_t* wb = reinterpret_cast<uint8_t*>(workspace);
+    p.wb = wb;
+    p.wb_part = (int64_t)p.n_nt_w * p.n_ks * 1024;
+    const int prep_threads = p.n_nt_w * p.n_ks * 64;
+    hipLaunchKernelGGL(weight_bytes_kernel, dim3((unsigned)cdiv(prep_threads, 256)), dim3(256), 0, stream,
+                       W->data, W->ld_words, W->plane_stride_words, W->nbits, cdiv(W->rows, 32), W->cols,
+                       p.n_nt_w, p.n_ks, p.split_w, wb, p.wb_part);
+    qgtc_status st = launch_status();
+    if (st != QGTC_OK) return st;
+  }
   *done = true;
   switch (X->nbits) {
     case 1: return launch<1>(p, nw, lds_bytes, stream);

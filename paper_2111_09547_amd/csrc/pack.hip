@@ -139,6 +139,40 @@ __global__ __launch_bounds__(256) void pack_left_u8_kernel(const PackParams p) {
   }
 }
 
+// RIGHT_BYTES: thread (tile nt, step ks, lane l) writes the 16 codes of column
+// 16 nt + l % 16, rows 64 ks + 16 (l / 16) .. + 15, as bytes (see qgtc.h).
+template <int SRC>
+__global__ __launch_bounds__(256) void pack_bytes_kernel(const PackParams p, int n_nt, int n_ks) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int lane = idx & 63;
+  const int ks = (idx >> 6) % n_ks;
+  const int nt = (idx >> 6) / n_ks;
+  if (nt >= n_nt) return;
+  const int col = nt * 16 + (lane & 15);
+  const int k0 = ks * 64 + (lane >> 4) * 16;
+  typename src_type<SRC>::type raw[16];
+#pragma unroll
+  for (int b = 0; b < 16; ++b) {
+    const bool ok = col < p.cols && k0 + b < p.rows;
+    raw[b] = fetch_raw<SRC>(p, ok ? (int64_t)(k0 + b) * p.ld_src + col : 0);
+  }
+  uint32_t d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int b = 0; b < 16; ++b) {
+    const bool ok = col < p.cols && k0 + b < p.rows;
+    const uint32_t code = ok ? to_code<SRC>(p, raw[b]) : 0u;
+    d[b >> 2] |= code << (8 * (b & 3));
+  }
+  uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(p.dst) + (int64_t)idx * 16);
+  if (p.nbits == 8) {
+    dst[p.ps / 4] = make_uint4((d[0] >> 7) & 0x01010101u, (d[1] >> 7) & 0x01010101u,
+                               (d[2] >> 7) & 0x01010101u, (d[3] >> 7) & 0x01010101u);
+    dst[0] = make_uint4(d[0] & 0x7f7f7f7fu, d[1] & 0x7f7f7f7fu, d[2] & 0x7f7f7f7fu, d[3] & 0x7f7f7f7fu);
+  } else {
+    dst[0] = make_uint4(d[0], d[1], d[2], d[3]);
+  }
+}
+
 struct UnpackParams {
   const uint32_t* src;
   int64_t ld, ps;
@@ -152,6 +186,15 @@ __global__ __launch_bounds__(256) void unpack_kernel(const UnpackParams p) {
   const int r = blockIdx.y * 4 + (threadIdx.x >> 6);
   if (c >= p.cols || r >= p.rows) return;
   uint32_t v = 0u;
+  if (p.layout == QGTC_RIGHT_BYTES) {
+    const uint8_t* bytes = reinterpret_cast<const uint8_t*>(p.src);
+    const int64_t off = (int64_t)(c >> 4) * p.ld * 4 + (int64_t)(r >> 6) * 1024 +
+                        ((c & 15) + 16 * ((r & 63) >> 4)) * 16 + (r & 15);
+    v = bytes[off];
+    if (p.nbits == 8) v |= (uint32_t)bytes[p.ps * 4 + off] << 7;
+    p.dst[(int64_t)r * p.ld_dst + c] = v;
+    return;
+  }
   for (int i = 0; i < p.nbits; ++i) {
     uint32_t word, bit;
     if (p.layout == QGTC_LEFT) {
@@ -203,6 +246,21 @@ __global__ __launch_bounds__(256) void row_sums_short_kernel(const UnpackParams 
 __global__ __launch_bounds__(256) void col_sums_kernel(const UnpackParams p, int32_t* out) {
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= p.cols) return;
+  if (p.layout == QGTC_RIGHT_BYTES) {
+    // bytes of column c: 16 at a time, both parts
+    const uint8_t* bytes = reinterpret_cast<const uint8_t*>(p.src);
+    uint32_t sum = 0u;
+    for (int r0 = 0; r0 < p.rows; r0 += 16) {
+      const int64_t off = (int64_t)(c >> 4) * p.ld * 4 + (int64_t)(r0 >> 6) * 1024 +
+                          ((c & 15) + 16 * ((r0 & 63) >> 4)) * 16;
+      for (int b = 0; b < 16; ++b) {               // zero fill past the last row
+        sum += bytes[off + b];
+        if (p.nbits == 8) sum += (uint32_t)bytes[p.ps * 4 + off + b] << 7;
+      }
+    }
+    out[c] = (int32_t)sum;
+    return;
+  }
   const int n_wr = (p.rows + 31) >> 5;
   uint32_t acc = 0u;
   for (int i = 0; i < p.nbits; ++i) {
@@ -215,7 +273,11 @@ __global__ __launch_bounds__(256) void col_sums_kernel(const UnpackParams p, int
 
 template <int SRC>
 qgtc_status launch_pack(const PackParams& p, int layout, hipStream_t s) {
-  if (layout == QGTC_RIGHT) {
+  if (layout == QGTC_RIGHT_BYTES) {
+    const int n_nt = cdiv(p.cols, 16), n_ks = cdiv(p.rows, 64);
+    hipLaunchKernelGGL((pack_bytes_kernel<SRC>), dim3((unsigned)cdiv((int64_t)n_nt * n_ks * 64, 256)), dim3(256),
+                       0, s, p, n_nt, n_ks);
+  } else if (layout == QGTC_RIGHT) {
     dim3 grid((unsigned)cdiv(p.cols, 64), (unsigned)cdiv(cdiv(p.rows, 32), 4));
     hipLaunchKernelGGL((pack_right_kernel<SRC>), grid, dim3(256), 0, s, p);
   } else if (SRC == QGTC_SRC_U8 && p.nbits == 1 && (p.cols & 15) == 0 && (p.ld_src & 15) == 0 &&
@@ -318,7 +380,7 @@ extern "C" qgtc_status qgtc_row_sums(const qgtc_bits* m, int32_t* out, void* str
 
 extern "C" qgtc_status qgtc_col_sums(const qgtc_bits* m, int32_t* out, void* stream) {
   if (!m || !out) return QGTC_ERR_NULL;
-  qgtc_status st = check_bits(m, QGTC_RIGHT);
+  qgtc_status st = check_bits(m, m->layout == QGTC_RIGHT_BYTES ? QGTC_RIGHT_BYTES : QGTC_RIGHT);
   if (st != QGTC_OK) return st;
   if (m->cols == 0) return QGTC_OK;
   UnpackParams p = unpack_params(m);

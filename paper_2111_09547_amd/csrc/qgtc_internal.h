@@ -123,17 +123,22 @@ __device__ __forceinline__ uint32_t quantize_f32(float x, float lo, float inv,
 }
 
 // Requantization of a 32-bit accumulator; see QGTC_OUT_BITS in qgtc.h.
-__device__ __forceinline__ uint32_t requantize_i32(uint32_t c_u32, const EpiParams& e,
-                                                   uint32_t qmax, float qmaxf) {
+__device__ __forceinline__ uint32_t requantize_code(uint32_t c_u32, int relu, int32_t rq_lo,
+                                                    float rq_inv_scale, uint32_t qmax, float qmaxf) {
   int32_t c = (int32_t)c_u32;
-  if (e.relu && c < 0) c = 0;
+  if (relu && c < 0) c = 0;
   // max(c - rq_lo, 0) as an exact 64-bit difference: it is below 2^32, and when
   // c > rq_lo the wrapped 32-bit subtraction is that difference
-  const uint32_t du = c > e.rq_lo ? (uint32_t)c - (uint32_t)e.rq_lo : 0u;
+  const uint32_t du = c > rq_lo ? (uint32_t)c - (uint32_t)rq_lo : 0u;
   const float f = (float)du;                      // round to nearest even
-  const float t = floorf(f * e.rq_inv_scale);
+  const float t = floorf(f * rq_inv_scale);
   if (t >= qmaxf) return qmax;
   return (uint32_t)t;
+}
+
+__device__ __forceinline__ uint32_t requantize_i32(uint32_t c_u32, const EpiParams& e,
+                                                   uint32_t qmax, float qmaxf) {
+  return requantize_code(c_u32, e.relu, e.rq_lo, e.rq_inv_scale, qmax, qmaxf);
 }
 
 // fp32 output of the dequantizing epilogue; see QGTC_OUT_F32 in qgtc.h.

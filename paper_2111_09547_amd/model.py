@@ -24,6 +24,11 @@ class LayerRanges:
     out_hi: int | None   # range [0, out_hi) of the update result (hidden layers)
 
 
+def fused_layer_applies(d: int, h: int, s: int, t: int) -> bool:
+    """The shapes and bit widths qgtc_layer runs as one kernel (see qgtc.h)."""
+    return 33 <= d <= 1024 and 1 <= h <= 256 and s <= 8 and t <= 8
+
+
 class QuantGNN:
     """A stack of quantized layers on one batch of subgraphs.
 
@@ -34,7 +39,8 @@ class QuantGNN:
     """
 
     def __init__(self, A_src, Ws, s: int, t: int, self_term: bool,
-                 tile_kbits: int = 128, use_map: bool = True, block_rows: int = 0):
+                 tile_kbits: int = 128, use_map: bool = True, block_rows: int = 0,
+                 weights_as_bytes: bool = True):
         self.s, self.t = s, t
         self.self_term = self_term
         self.tile_kbits = tile_kbits
@@ -48,7 +54,13 @@ class QuantGNN:
             self.A_src = A_src
             self.A = B.alloc_bits(A_src.shape[0], A_src.shape[1], 1, B.LEFT, block_rows)
         self.map = None
-        self.W = [B.alloc_bits(d, h, t, B.RIGHT) for d, h in self.dims]
+        # Weights are cached in the form their layer's kernel reads: bytes in
+        # matrix-core operand order where the fused layer kernel applies, bit planes
+        # for the two-kernel path.
+        self.w_layout = [B.RIGHT_BYTES if weights_as_bytes and fused_layer_applies(d, h, s, t) else B.RIGHT
+                         for d, h in self.dims]
+        self.W = [B.alloc_bits(d, h, t, lay) for (d, h), lay in zip(self.dims, self.w_layout)]
+        self._W_planes = None
         n = self.A.rows
         dmax = max(d for d, _ in self.dims)
         ws_bytes = max(B.lib().qgtc_layer_workspace_bytes(n, d, h, s) for d, h in self.dims)
@@ -69,8 +81,8 @@ class QuantGNN:
             self.deg = self.map.deg
         else:
             self.deg = B.qgtc_row_sums(self.A)
-        for W, r, dst in zip(self.Ws, self.w_ranges, self.W):
-            B.qgtc_pack_bits(W, self.t, B.RIGHT, quant=r, out=dst)
+        for W, r, dst, lay in zip(self.Ws, self.w_ranges, self.W, self.w_layout):
+            B.qgtc_pack_bits(W, self.t, lay, quant=r, out=dst)
         # only the last layer dequantizes, so only its column sums are needed
         self.w_colsum = [None] * (len(self.W) - 1) + [B.qgtc_col_sums(self.W[-1])]
 
@@ -97,7 +109,10 @@ class QuantGNN:
         layer (range = [0, max observed accumulator], at least 1)."""
         ranges = []
         xb = self.pack_input(X, x_range)
-        for l, W in enumerate(self.W):
+        if self._W_planes is None:          # qgtc_update reads bit planes
+            self._W_planes = [B.qgtc_pack_bits(W, self.t, B.RIGHT, quant=r)
+                              for W, r in zip(self.Ws, self.w_ranges)]
+        for l, W in enumerate(self._W_planes):
             y32 = B.qgtc_aggregate(self.A, self.map, xb,
                                    B.Epilogue(mode=B.OUT_I32, self_term=self.self_term))
             agg_hi = max(1, int(y32.max()))

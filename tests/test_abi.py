@@ -43,6 +43,10 @@ def test_describe_and_sizes():
     nb = b.lib().qgtc_tile_map_bytes(256, 256, 16, 128)
     assert nb >= (16 + 16 * 2 + 1 + 256) * 4
     assert b.lib().qgtc_tile_map_bytes(256, 256, 7, 128) == 0
+    words = b.lib().qgtc_describe(C.byref(d), 70, 20, 8, b.RIGHT_BYTES, 0)
+    assert (d.ld_words, d.plane_stride_words, words) == (512, 1024, 2048)
+    assert b.lib().qgtc_describe(C.byref(d), 70, 20, 7, b.RIGHT_BYTES, 0) == 1024
+    assert b.lib().qgtc_describe(C.byref(d), 70, 20, 9, b.RIGHT_BYTES, 0) == 0
     assert b.lib().qgtc_layer_workspace_bytes(100, 70, 16, 4) >= 100 * 3 * 4 * 4 + 100 * 4
 
 
@@ -107,6 +111,11 @@ def test_argument_validation_happens_before_any_launch():
     epb = b.Epilogue(mode=b.OUT_BITS, rq_nbits=2, rq_inv_scale=1.0).to_c()
     assert l.qgtc_layer(C.byref(A), None, C.byref(X), C.byref(W2), C.byref(epb), C.byref(ep),
                         C.c_void_p(0x30000), 16, out, 8, None) == 6
+    # weights as bytes are for the fused kernel only: a shape it does not cover is refused
+    Wby = _fake_bits(b, 16, 8, 2, b.RIGHT_BYTES)
+    assert l.qgtc_layer(C.byref(A), None, C.byref(X), C.byref(Wby), C.byref(epb), C.byref(ep),
+                        C.c_void_p(0x30000), 1 << 20, out, 8, None) == 7
+    assert l.qgtc_update(C.byref(Y), C.byref(Wby), C.byref(ep), out, 8, None) == 5
     # pack: fp32 source needs a quantizer with hi > lo
     D = _fake_bits(b, 64, 16, 2, b.RIGHT)
     assert l.qgtc_pack_bits(C.c_void_p(0x40000), 0, 64, 16, 16, None, C.byref(D), None) == 1

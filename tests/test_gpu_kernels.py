@@ -18,6 +18,36 @@ def rand_graph(rng, n, k, p):
 
 
 # ------------------------------------------------------------------ pack / unpack
+@pytest.mark.parametrize("bits", [1, 5, 8])
+@pytest.mark.parametrize("shape", [(1, 1), (45, 77), (130, 64), (64, 300), (512, 16)])
+def test_pack_bytes_layout(bits, shape):
+    """Codes as bytes in matrix-core operand order: position of every byte as the
+    header states it, 7 + 1 split for 8 bits, zero fill, from fp32 and from integers."""
+    rows, cols = shape
+    rng = np.random.default_rng([3, bits, rows, cols])
+    x = rng.standard_normal((rows, cols)).astype(np.float32)
+    lo, hi = float(x.min()), float(x.max()) + 1e-3
+    codes = qgnn.quantize(x, lo, hi, bits)
+    for src, kw in ((dev(x), dict(quant=(lo, hi))), (dev(codes.view(np.int32)), {})):
+        b = q.alloc_bits(rows, cols, bits, q.RIGHT_BYTES)
+        b.words.fill_(-1)
+        q.qgtc_pack_bits(src, bits, q.RIGHT_BYTES, out=b, **kw)
+        assert (as_u32(q.qgtc_unpack_bits(b)) == codes).all()
+        raw = b.words.cpu().numpy().view(np.uint8)
+        n_nt, n_ks = -(-cols // 16), -(-rows // 64)
+        parts = 2 if bits == 8 else 1
+        want = np.zeros((parts, n_nt, n_ks, 64, 16), dtype=np.uint8)
+        for k in range(rows):
+            for c in range(cols):
+                lane = c % 16 + 16 * ((k % 64) // 16)
+                v = int(codes[k, c])
+                want[0, c // 16, k // 64, lane, k % 16] = v & 0x7f if bits == 8 else v
+                if bits == 8:
+                    want[1, c // 16, k // 64, lane, k % 16] = v >> 7
+        assert b.c.ld_words == 256 * n_ks and b.c.plane_stride_words == n_nt * n_ks * 256
+        assert (raw[:want.size] == want.ravel()).all()
+
+
 @pytest.mark.parametrize("layout", [0, 1])
 @pytest.mark.parametrize("bits", [1, 2, 3, 8, 13, 32])
 @pytest.mark.parametrize("shape", [(1, 1), (45, 77), (130, 64), (64, 2100)])
@@ -300,6 +330,9 @@ def test_fused_layer_all_outputs(shape, st):
 
     Xb = q.qgtc_pack_bits(dev(Xq.view(np.int32)), s, q.RIGHT)
     Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    Wbytes = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT_BYTES)
+    assert (as_u32(q.qgtc_unpack_bits(Wbytes)) == Wq).all()
+    assert (as_u32(q.qgtc_col_sums(Wbytes)) == Wq.sum(axis=0, dtype=np.uint64).astype(np.uint32)).all()
     agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=s, rq_lo=0, rq_inv_scale=float(rq_inv),
                         self_term=self_term)
     out_bits = min(s, 6)
@@ -333,6 +366,9 @@ def test_fused_layer_all_outputs(shape, st):
                 q.qgtc_prof_enable(False)
                 q.qgtc_prof_reset()
                 assert fused_launches == (1 if path == q.LAYER_FUSED else 0), tag
+                assert (as_u32(got) == Z).all(), tag
+                # weights cached as bytes in operand order: always the fused kernel
+                got = q.qgtc_layer(Ab, m, Xb, Wbytes, agg_ep, q.Epilogue(mode=q.OUT_I32))
                 assert (as_u32(got) == Z).all(), tag
                 ep = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=out_bits, rq_lo=3,
                                 rq_inv_scale=float(z_inv))
