@@ -174,6 +174,20 @@ def main():
     q.qgtc_set_option(q.OPT_LAYER_PATH, q.LAYER_FUSED)
     del planes
 
+    # attainable AND + popcount rate, measured: the aggregation's inner block on registers
+    # only, three waves per SIMD as the kernels run (12 workgroups of 1 wave per CU)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    probe_iters, probe_wgs = 500, 256 * 12
+    q.qgtc_probe_popcount(probe_wgs, 1, probe_iters, sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        q.qgtc_probe_popcount(probe_wgs, 1, probe_iters, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    measured_peak = 3 * probe_wgs * probe_iters * 4 * 128 * 64 * 64.0 / (e0.elapsed_time(e1) * 1e-3)
+
     agg_ops, upd_ops, nnz = workload_bitops(net, g.n_nodes, args.tile_kbits)
     total_ops = sum(agg_ops) + sum(upd_ops)
     # the dominant kernel: the fused layer kernel where it applies, else the aggregation
@@ -209,6 +223,8 @@ def main():
                      "avg_launch_ms": dom_ms / max(dom_n, 1), "launches": dom_n,
                      "counted": "executed AND+popcount bit-ops of the aggregation only; the update "
                                 "inside the same kernel runs on the matrix cores and is not counted",
+                     "measured_peak": measured_peak / 1e12,
+                     "frac_of_measured_peak": agg_rate / measured_peak,
                      "traffic": TRAFFIC.get((w.cfg, w.s))},
         "kernels": {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps}
                     for k, v in prof.items()},

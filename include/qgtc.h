@@ -312,6 +312,15 @@ enum {
 };
 qgtc_status qgtc_set_option(int32_t option, int32_t value);
 
+/* Measurement aid: runs the AND + popcount inner block of the aggregation
+ * (16 rows x 8 planes = 256 vector instructions = 64 lanes x 32 x 128 one-bit
+ * multiply-accumulates per wave and call) 4 * iters times per wave on registers
+ * only, in `workgroups` workgroups of `waves_per_workgroup` (1..4) waves.  Timing
+ * the launch gives the attainable AND + popcount rate of the device as it is
+ * clocked at that moment.  sink: one device word, practically never written. */
+qgtc_status qgtc_probe_popcount(int32_t workgroups, int32_t waves_per_workgroup,
+                                int32_t iters, uint32_t* sink, void* stream);
+
 /* Library version, major*10000 + minor*100 + patch. */
 int32_t qgtc_version(void);
 

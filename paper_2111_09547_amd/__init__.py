@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     qgtc_update, qgtc_layer, qgtc_row_sums, qgtc_col_sums,
     qgtc_set_option, OPT_UPDATE_PATH, OPT_AGG_XCD_RUN, OPT_LAYER_PATH, OPT_LAYER_KSPLIT,
     LAYER_FUSED, LAYER_TWO_KERNELS, UPDATE_AUTO, UPDATE_POPCOUNT, UPDATE_MATRIX_CORES,
-    qgtc_prof_enable, qgtc_prof_reset, qgtc_prof_read, qgtc_version,
+    qgtc_probe_popcount, qgtc_prof_enable, qgtc_prof_reset, qgtc_prof_read, qgtc_version,
 )

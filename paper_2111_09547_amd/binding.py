@@ -91,6 +91,7 @@ def lib():
         "qgtc_layer": (C.c_int, [P(_BitsC), P(_TileMapC), P(_BitsC), P(_BitsC), P(_EpilogueC),
                                  P(_EpilogueC), vp, sz, vp, i64, vp]),
         "qgtc_set_option": (C.c_int, [i32, i32]),
+        "qgtc_probe_popcount": (C.c_int, [i32, i32, i32, C.c_void_p, C.c_void_p]),
         "qgtc_prof_enable": (C.c_int, [i32]),
         "qgtc_prof_reset": (C.c_int, []),
         "qgtc_prof_read": (C.c_int, [i32, P(C.c_double), P(i64)]),
@@ -317,6 +318,11 @@ UPDATE_AUTO, UPDATE_POPCOUNT, UPDATE_MATRIX_CORES = 0, 1, 2
 
 def qgtc_set_option(option: int, value: int):
     _check(lib().qgtc_set_option(option, value), "qgtc_set_option")
+
+
+def qgtc_probe_popcount(workgroups: int, waves_per_workgroup: int, iters: int, sink: torch.Tensor):
+    _check(lib().qgtc_probe_popcount(workgroups, waves_per_workgroup, iters,
+                                     C.c_void_p(sink.data_ptr()), _stream()), "qgtc_probe_popcount")
 
 
 def qgtc_prof_enable(on: bool):

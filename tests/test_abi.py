@@ -125,6 +125,14 @@ def test_argument_validation_happens_before_any_launch():
     assert l.qgtc_aggregate(C.byref(A), C.byref(m), C.byref(X), C.byref(ep), out, 16, None) == 7
 
 
+def test_probe_arguments_are_checked():
+    import paper_2111_09547_amd.binding as b
+    l = b.lib()
+    assert l.qgtc_probe_popcount(1, 1, 1, None, None) == 1
+    assert l.qgtc_probe_popcount(0, 1, 1, C.c_void_p(0x1000), None) == 2
+    assert l.qgtc_probe_popcount(1, 5, 1, C.c_void_p(0x1000), None) == 2
+
+
 def test_options_are_range_checked():
     import paper_2111_09547_amd.binding as b
     l = b.lib()

@@ -294,6 +294,13 @@ def test_layer_matches_oracle(cfg, bits, nb):
 
 
 # ------------------------------------------------- update on the matrix cores
+def test_popcount_probe_runs_and_leaves_its_sink_alone():
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    q.qgtc_probe_popcount(64, 4, 10, sink)
+    sync()
+    assert int(sink.abs().sum()) == 0
+
+
 # ------------------------------------------------------------------- fused layer
 def _layer_case(rng, n, d, h, s, t, block, self_term, p_edge=0.06):
     A = np.zeros((n, n), dtype=np.uint8)
