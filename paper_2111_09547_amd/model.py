@@ -88,11 +88,56 @@ class QuantGNN:
 
     # -- helpers -----------------------------------------------------------------
     def _x_view(self, which: int, cols: int) -> B.Bits:
-        """A [N, cols] RIGHT-packed view on one of the activation buffers."""
+        """A [N, cols] RIGHT-packed view on one of the activation buffers.  Every view has
+        the strides of the widest layer, so that a range of rows is the same range of
+        words whatever the layer (independent runs of rows work on the buffers at once)."""
         buf = self.x_bufs[which]
         d, _ = B.describe(self.A.rows, cols, self.s, B.RIGHT)
+        d.ld_words = buf.c.ld_words
+        d.plane_stride_words = buf.c.plane_stride_words
         d.data = buf.words.data_ptr()
         return B.Bits(buf.words, d)
+
+    # -- independent batches of subgraphs -------------------------------------------------
+    def _chunks(self, n_chunks: int):
+        """Splits the batch into runs of whole subgraphs (block-diagonal storage only):
+        per run the row range, a view of A and a view of the tile map.  Subgraphs share
+        no edge (Section 4.1), so the runs are independent from the first layer to the
+        last and can be issued on different streams."""
+        key = (n_chunks, self.map.c.row_cnt if self.map is not None else 0)
+        if getattr(self, "_chunk_cache", (None, None))[0] == key:
+            return self._chunk_cache[1]
+        br = self.A.c.block_rows
+        assert br > 0 and br % 32 == 0, "independent runs need the block-diagonal storage"
+        n = self.A.rows
+        n_blocks = -(-n // br)
+        per = -(-n_blocks // n_chunks) * br
+        out = []
+        for r0 in range(0, n, per):
+            r1 = min(n, r0 + per)
+            a = B._BitsC.from_buffer_copy(self.A.c)
+            a.data = self.A.c.data + r0 * self.A.c.ld_words * 4
+            a.rows = r1 - r0
+            m = None
+            if self.map is not None:
+                mc = B._TileMapC.from_buffer_copy(self.map.c)
+                t0 = r0 // mc.tile_rows
+                mc.n_tile_rows = -(-(r1 - r0) // mc.tile_rows)
+                mc.row_cnt = self.map.c.row_cnt + 4 * t0
+                mc.col_idx = self.map.c.col_idx + 4 * t0 * mc.n_tile_cols
+                mc.deg = self.map.c.deg + 4 * r0
+                m = B.TileMap(self.map.buffer, mc, r1 - r0)
+            out.append((r0, r1, B.Bits(self.A.words, a), m))
+        self._chunk_cache = (key, out)
+        return out
+
+    def _x_rows(self, which: int, cols: int, r0: int, r1: int) -> B.Bits:
+        """Rows [r0, r1) (r0 a multiple of 32) of the [N, cols] view of an activation buffer."""
+        full = self._x_view(which, cols)
+        d = B._BitsC.from_buffer_copy(full.c)
+        d.data = full.c.data + (r0 // 32) * full.c.ld_words * 4
+        d.rows = r1 - r0
+        return B.Bits(full.words, d)
 
     def pack_input(self, X: torch.Tensor, x_range) -> B.Bits:
         return B.qgtc_pack_bits(X, self.s, B.RIGHT, quant=x_range,
@@ -142,9 +187,68 @@ class QuantGNN:
                           ck=lo_w * d, cs=sw, col_i=self.w_colsum[l])
 
     def forward(self, X: torch.Tensor, x_range, ranges, out: torch.Tensor | None = None,
-                want_int: bool = False):
-        """fp32 [N, H_last] (or the last int32 accumulators when want_int)."""
+                want_int: bool = False, streams: int = 1):
+        """fp32 [N, H_last] (or the last int32 accumulators when want_int).
+
+        streams > 1 (block-diagonal storage): the subgraphs are cut into that many
+        independent runs, each issued on a stream of its own, so that the start and the
+        drain of one run's kernels overlap with the other runs' work."""
         xb = self.pack_input(X, x_range)
+        n = self.A.rows
+        if out is None:
+            out = torch.empty((n, self.dims[-1][1]), dtype=torch.int32 if want_int else torch.float32,
+                              device=self.A.words.device)
+        if streams <= 1 or self.A.c.block_rows == 0:
+            self._run_layers(0, n, self.A, self.map, self.deg, xb, x_range, ranges, out, want_int,
+                             self.workspace)
+            return out
+        chunks = self._chunks(streams)
+        if getattr(self, "_streams", None) is None or len(self._streams) < len(chunks):
+            self._streams = [torch.cuda.Stream() for _ in chunks]
+            ws_words = self.workspace.numel()
+            self._chunk_ws = [torch.empty(ws_words, dtype=torch.int32, device=self.A.words.device)
+                              for _ in chunks]
+        cur = torch.cuda.current_stream()
+        packed = torch.cuda.Event()
+        packed.record(cur)
+        for (r0, r1, a, m), st, ws in zip(chunks, self._streams, self._chunk_ws):
+            st.wait_event(packed)
+            with torch.cuda.stream(st):
+                x0 = self._x_rows(0, X.shape[1], r0, r1)
+                self._run_layers(r0, r1, a, m, self.deg[r0:r1], x0, x_range, ranges, out[r0:r1],
+                                 want_int, ws)
+            done = torch.cuda.Event()
+            done.record(st)
+            cur.wait_event(done)
+        return out
+
+    def capture(self, X: torch.Tensor, x_range, ranges, out: torch.Tensor, streams: int = 1,
+                with_static: bool = False, want_int: bool = False) -> torch.cuda.CUDAGraph:
+        """Records one pass (optionally with pack_static in front) into a HIP graph; replay()
+        runs it again on the same buffers: X and out are read and written in place.  The
+        library's launches are plain kernel launches on the current stream (no memset, no
+        synchronization), the runs on side streams fork from and join the capturing stream
+        through events, so the whole pass is one graph launch for the host."""
+        def run():
+            if with_static:
+                self.pack_static()
+            self.forward(X, x_range, ranges, out=out, want_int=want_int, streams=streams)
+
+        cur = torch.cuda.current_stream()
+        side = torch.cuda.Stream()
+        side.wait_stream(cur)
+        with torch.cuda.stream(side):      # warm-up outside the capture: allocations, code loading
+            run()
+            run()
+        cur.wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run()
+        return graph
+
+    def _run_layers(self, r0, r1, A, tmap, deg, xb, x_range, ranges, out, want_int, workspace):
+        """All layers on rows [r0, r1) (whole subgraphs), on the current stream."""
         n_layers = len(self.W)
         x_lo = float(x_range[0])
         x_scale = (float(x_range[1]) - float(x_range[0])) / float(2 ** self.s)
@@ -154,8 +258,8 @@ class QuantGNN:
             if l < n_layers - 1:
                 ep = B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0,
                                 rq_inv_scale=inv_scale(0.0, float(r.out_hi), self.s))
-                xb = B.qgtc_layer(self.A, self.map, xb, W, agg_ep, ep, self.workspace,
-                                  out=self._x_view((l + 1) & 1, self.dims[l][1]))
+                xb = B.qgtc_layer(A, tmap, xb, W, agg_ep, ep, workspace,
+                                  out=self._x_rows((l + 1) & 1, self.dims[l][1], r0, r1))
                 # hidden activations are read as pure scales: x^ = Xq * step
                 lo_w, hi_w = self.w_ranges[l]
                 sw = (hi_w - lo_w) / float(2 ** self.t)
@@ -163,9 +267,9 @@ class QuantGNN:
                     / inv_scale(0.0, float(r.out_hi), self.s)
                 x_lo = 0.0
             elif want_int:
-                return B.qgtc_layer(self.A, self.map, xb, W, agg_ep, B.Epilogue(mode=B.OUT_I32),
-                                    self.workspace, out=out)
+                B.qgtc_layer(A, tmap, xb, W, agg_ep, B.Epilogue(mode=B.OUT_I32), workspace, out=out)
             else:
                 # row_i = None: the layer takes the row sums of its own requantized Y
                 ep = self.last_layer_dequant(l, x_lo, x_scale, r.agg_hi, None)
-                return B.qgtc_layer(self.A, self.map, xb, W, agg_ep, ep, self.workspace, out=out)
+                ep.row_l = deg
+                B.qgtc_layer(A, tmap, xb, W, agg_ep, ep, workspace, out=out)

@@ -75,6 +75,31 @@ def run_model(w, tile_kbits=128):
     got = out.cpu().numpy()
     assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
 
+    # independent runs of subgraphs on several streams give the same bytes
+    if w.storage == "compact":
+        for k in (2, 3):
+            again = net.forward(X, xr, ranges, streams=k)
+            torch.cuda.synchronize()
+            assert torch.equal(again, out), k
+            zk = net.forward(X, xr, ranges, want_int=True, streams=k)
+            torch.cuda.synchronize()
+            assert (as_u32(zk) == trace[-1]["Z"]).all(), k
+
+    # the same pass recorded as a HIP graph: every replay, with eager work of the program
+    # in between, gives the eager result again
+    buf = torch.empty_like(out)
+    for k in ((1, 2) if w.storage == "compact" else (1,)):
+        graph = net.capture(X, xr, ranges, buf, streams=k, with_static=True)
+        for rep in range(3):
+            buf.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(buf, out), (k, rep)
+            eager = net.forward(X, xr, ranges)          # eager launches between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(eager, out), (k, rep)
+        del graph
+
     # layer by layer, teacher forced: feed the oracle's integers to each HIP layer
     for l, tr in enumerate(trace):
         xb = q.qgtc_pack_bits(dev(tr["Xq"].view(np.int32)), w.s, q.RIGHT)
