@@ -129,22 +129,27 @@ def main():
     def layers_only():
         net.forward(X, xr, ranges, out=out)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
 
+    # The step as one HIP graph: the same launches, recorded once, so that the host's
+    # per-launch cost (Python + ctypes, ~25 us each) does not limit a step of ~20 launches.
+    graph_step = net.capture(X, xr, ranges, out, with_static=True)
+    graph_layers = net.capture(X, xr, ranges, out)
+    for _ in range(args.warmup):
+        graph_step.replay()
+    ms_step = timed(graph_step.replay, args.steps)
     # features-to-output only (adjacency, map and weights cached, as the paper does)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        layers_only()
-    torch.cuda.synchronize()
-    ms_layers = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_layers = timed(graph_layers.replay, args.steps)
+    # the same, launched eagerly from Python
+    for _ in range(3):
+        step()
+    ms_step_eager = timed(step, min(args.steps, 50))
 
     # the same steps again with HIP events around every kernel launch
     q.qgtc_prof_enable(True)
@@ -213,6 +218,8 @@ def main():
                    "nonzero_tiles": nnz,
                    "nonzero_tile_ratio": nnz / float(net.map.c.n_tile_rows * net.map.c.n_tile_cols),
                    "step": "pack A + tile map + pack W + pack X + all layers"},
+        "ms_per_step_eager": ms_step_eager,
+        "launch": "one HIP graph per step (the same kernel launches, recorded once)",
         "ms_per_layer": ms_layers / n_layers,
         "ms_layers_only": ms_layers,
         "tops_equiv_dense": dense_macs / (ms_layers * 1e-3) / 1e12,

@@ -239,7 +239,7 @@ qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W,
 /* One layer (Algorithm 1): aggregate, requantize the result to agg_ep->rq_nbits
  * bits (agg_ep must be QGTC_OUT_BITS; its output is internal to the call), then
  * update with upd_ep into out.
- * When all operands have at most 8 bits, X has 33..1024 columns and W at most
+ * When all operands have at most 8 bits, X has at most 1024 columns and W at most
  * 256, the whole layer runs as ONE kernel (inter-layer fusion, Section 4.5,
  * extended across the two products): the requantized aggregation tile goes
  * through LDS as bytes straight into the int8 matrix cores.  Otherwise the

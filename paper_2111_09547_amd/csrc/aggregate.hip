@@ -13,8 +13,9 @@
 //   instruction.  A tile therefore stays in 1..4 VGPRs and is reused for every
 //   plane and every column - the "non-zero tile reuse" of the paper, in
 //   registers instead of shared memory.
-//   With fewer than 64 columns the four DPP rows hold four different row
-//   tiles (CW = 16) or two (CW = 32), so no lane idles.
+//   With at most 32 (16) columns the lanes form 2 (4) groups that take different
+//   words of the same tile at once (K slices) and are summed at the end, so no
+//   lane idles and the tile list stays uniform over the wave.
 // Zero-tile jumping: the loop runs over the precomputed list of non-zero tile
 // columns of the tile row (or over all of them without a map).
 // Small grids: the 1..4 waves of a workgroup split the tile list and add their
@@ -26,90 +27,72 @@ namespace {
 
 #include "agg_core.inc"
 
-// The words that the ballots of bit (p0 + i) of q, i < S, give for one output
-// row of the wave.  CWS >= 5: the two halves of the 64-bit ballot (CW = 64: two
-// consecutive words of the row; CW = 32: the words of the two row groups);
-// CWS == 4: its four 16-bit fields (the words of the four row groups).
-template <int S, int CWS>
+// The two words that the ballots of bit (p0 + i) of q, i < S, give for one output
+// row of the wave: columns 0..31 and 32..63 of the column group.
+template <int S>
 __device__ __forceinline__ void ballot_words(uint32_t q, int p0, uint32_t (&w)[S][4]) {
 #pragma unroll
   for (int i = 0; i < S; ++i) {
     const unsigned long long m = __builtin_amdgcn_ballot_w64(((q >> (p0 + i)) & 1u) != 0u);
-    if constexpr (CWS >= 5) {
-      w[i][0] = (uint32_t)m;
-      w[i][1] = (uint32_t)(m >> 32);
-      w[i][2] = 0u;
-      w[i][3] = 0u;
-    } else {
-      w[i][0] = (uint32_t)(m & 0xffffull);
-      w[i][1] = (uint32_t)((m >> 16) & 0xffffull);
-      w[i][2] = (uint32_t)((m >> 32) & 0xffffull);
-      w[i][3] = (uint32_t)((m >> 48) & 0xffffull);
-    }
+    w[i][0] = (uint32_t)m;
+    w[i][1] = (uint32_t)(m >> 32);
+    w[i][2] = 0u;
+    w[i][3] = 0u;
   }
 }
 
 // Generic path: planes pg .. pg+7 of the rows the wave owns; lane 4*J + k keeps
 // word k of row J.  Planes past qbits give q >> plane == 0 and are not stored.
-template <int J, int CWS>
+template <int J>
 __device__ __forceinline__ void gather_rows(const uint32_t (&q)[16], uint32_t (&ow)[8], int pg,
                                             int km, int wave) {
   if ((J & km) == wave) {
     uint32_t w[8][4];
-    ballot_words<8, CWS>(pg < 32 ? q[J] : 0u, pg, w);
-    lane_pack<8, (CWS >= 5 ? 2 : 4)>::template run<4 * J>(w, ow);
+    ballot_words<8>(pg < 32 ? q[J] : 0u, pg, w);
+    lane_pack<8, 2>::template run<4 * J>(w, ow);
   }
-  if constexpr (J + 1 < 16) gather_rows<J + 1, CWS>(q, ow, pg, km, wave);
+  if constexpr (J + 1 < 16) gather_rows<J + 1>(q, ow, pg, km, wave);
 }
 
 // Fast path of the requantize-and-pack epilogue: as many output planes as
 // feature planes (the layer case), one wave per workgroup, everything unrolled.
-template <int J, int S, int CWS>
+template <int J, int S>
 __device__ __forceinline__ void pack_rows_fast(const uint32_t (&q)[16], uint32_t (&ow)[S]) {
   uint32_t w[S][4];
-  ballot_words<S, CWS>(q[J], 0, w);
-  lane_pack<S, (CWS >= 5 ? 2 : 4)>::template run<4 * J>(w, ow);
-  if constexpr (J + 1 < 16) pack_rows_fast<J + 1, S, CWS>(q, ow);
+  ballot_words<S>(q[J], 0, w);
+  lane_pack<S, 2>::template run<4 * J>(w, ow);
+  if constexpr (J + 1 < 16) pack_rows_fast<J + 1, S>(q, ow);
 }
 
-// TW: words per tile (1, 2, 4) for CWS == 6, where the tile loop is specialized;
-// 0 otherwise (tile width read at run time).
-template <int S, int CWS, bool MULTI, int TW>
+// TW: words per tile (1, 2, 4); KS: K slices per wave (1, 2, 4; KS <= TW).
+template <int S, bool MULTI, int TW, int KS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void aggregate_kernel(const AggParams p) {
-  constexpr bool UNI = CWS == 6;
   extern __shared__ uint32_t lds[];   // [ksplit][16][64] partial sums when ksplit > 1
 
   const unsigned bid = xcd_deal(blockIdx.x, p.chunk_shift);
   if (bid >= p.nblocks) return;       // whole workgroup leaves together
-  const int rt = (int)(bid / (unsigned)p.n_cg);
-  const int cg = (int)(bid % (unsigned)p.n_cg);
+  const int tr = (int)(bid / (unsigned)p.n_cg);     // tile row
+  const int cg = (int)(bid % (unsigned)p.n_cg);     // group of 64 columns
 
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int lane = threadIdx.x & 63;
-  constexpr int cw = 1 << CWS;
-  const int rg = UNI ? 0 : (lane >> CWS);
-  constexpr int rgs = 64 >> CWS;                 // row tiles per wave
-  const int tr = rt * rgs + rg;                     // this lane's tile row
-  const bool tr_ok = tr < p.n_tile_rows;
-  const int c = cg * cw + (lane & (cw - 1));        // this lane's output column
-  const bool c_ok = c < p.cols;
-  const uint32_t col4 = (uint32_t)(c_ok ? c : p.cols - 1) * 4u;
-  const int arow_idx = tr * 16 + (lane & 15);       // adjacency row whose words this lane fetches
-  const bool row_ok = tr_ok && arow_idx < p.rows;
-  const uint32_t* arow = p.A + (int64_t)(row_ok ? arow_idx : 0) * p.lda;
+  constexpr int CW = 64 / KS;                       // columns per wave
+  const int c = cg * 64 + (lane & (CW - 1));        // this lane's output column
+  const bool c_ok = c < p.cols && (KS == 1 || lane < CW);   // lanes of slice 0 write the results
+  const uint32_t col4 = (uint32_t)min(c, p.cols - 1) * 4u;
+  uint32_t va_off, xoff;
+  agg_lane_offsets<TW, KS>(p, lane, col4, &va_off, &xoff);
 
-  int n = 0;
-  if (tr_ok) n = p.row_cnt ? p.row_cnt[tr] : p.n_tile_cols;
-  const int32_t* ci = p.col_idx ? p.col_idx + (int64_t)(tr_ok ? tr : 0) * p.n_tile_cols : nullptr;
-  if (UNI) n = __builtin_amdgcn_readfirstlane(n);
-  const int per_it = 4 / p.tile_words;
-  const int n_it = (n + per_it - 1) / per_it;       // loop iterations this lane needs
+  int n = p.row_cnt ? p.row_cnt[tr] : p.n_tile_cols;
+  n = __builtin_amdgcn_readfirstlane(n);
+  const int32_t* ci = p.col_idx ? p.col_idx + (int64_t)tr * p.n_tile_cols : nullptr;
 
   uint32_t kw_base = 0u;
-  if (p.block_rows > 0 && tr_ok) kw_base = (uint32_t)((tr * 16) / p.block_rows) * (uint32_t)(p.block_rows >> 5);
+  if (p.block_rows > 0) kw_base = (uint32_t)((tr * 16) / p.block_rows) * (uint32_t)(p.block_rows >> 5);
   const uint32_t kw_max = (uint32_t)(p.x_kwords - 1);
 
-  __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)p.X, 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)p.X, 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t ra = agg_row_tile_rsrc(p, tr);
 
   uint32_t y[16];
 #pragma unroll
@@ -120,40 +103,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
     const int plane0 = chunk * S;
     uint32_t acc[16][S];
     zero_acc<S>(acc);
-
-    if constexpr (UNI) {
-      const __amdgpu_buffer_rsrc_t ra = agg_row_tile_rsrc(p, rt);
-      const uint32_t va_off = (uint32_t)(lane & 15) * (uint32_t)(p.lda * 4);
-      agg_loop_uniform<S, (TW > 0 ? TW : 4), MULTI>(acc, p, ra, va_off, rx, col4, ci, n, wave, p.ksplit, kw_base,
-                                                    kw_max, plane0);
-    } else {
-      int it = wave;
-      if (__builtin_amdgcn_ballot_w64(it < n_it) != 0ull) {
-        Step4 cur = load_steps<UNI>(p, arow, row_ok, load_tiles<UNI>(p, ci, n, it), n, kw_base, kw_max);
-        Tiles4 t_nxt = load_tiles<UNI>(p, ci, n, it + p.ksplit);
-        uint32_t x0[S], x1[S];
-        load_x<S, UNI, MULTI>(x0, rx, cur.kw[0], col4, p, plane0);
-        while (true) {
-          const int it_next = it + p.ksplit;
-          const bool more = __builtin_amdgcn_ballot_w64(it_next < n_it) != 0ull;
-          const Tiles4 t_nn = load_tiles<UNI>(p, ci, n, it_next + p.ksplit);   // two iterations ahead
-          Step4 nxt = cur;
-          if (more) nxt = load_steps<UNI>(p, arow, row_ok, t_nxt, n, kw_base, kw_max);
-          load_x<S, UNI, MULTI>(x1, rx, cur.kw[1], col4, p, plane0);
-          popc_rows<S>::run(cur.a[0], x0, acc);
-          load_x<S, UNI, MULTI>(x0, rx, cur.kw[2], col4, p, plane0);
-          popc_rows<S>::run(cur.a[1], x1, acc);
-          load_x<S, UNI, MULTI>(x1, rx, cur.kw[3], col4, p, plane0);
-          popc_rows<S>::run(cur.a[2], x0, acc);
-          load_x<S, UNI, MULTI>(x0, rx, nxt.kw[0], col4, p, plane0);
-          popc_rows<S>::run(cur.a[3], x1, acc);
-          if (!more) break;
-          cur = nxt;
-          t_nxt = t_nn;
-          it = it_next;
-        }
-      }
-    }
+    agg_loop_uniform<S, TW, KS, MULTI>(acc, p, ra, va_off, rx, xoff, ci, n, wave, p.ksplit, kw_base, kw_max,
+                                       plane0);
     // shift-and-add of the per-plane popcounts (Algorithm 1, elementwise reduction)
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
@@ -162,6 +113,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
       for (int i = 0; i < S; ++i) v += acc[j][i] << i;
       y[j] += v << plane0;
     }
+  }
+  if constexpr (KS > 1) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) y[j] = agg_slice_sum<KS>(y[j]);
   }
 
   // ---- epilogue: wave w finishes the rows j with j % ksplit == w ---------------
@@ -213,14 +168,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
       const int row = out_row0 + j;
       int32_t o = (int32_t)y[j];
       if (e.relu && o < 0) o = 0;
-      if (tr_ok && c_ok && row < p.rows) reinterpret_cast<int32_t*>(e.out)[(int64_t)row * e.ld_out + c] = o;
+      if (c_ok && row < p.rows) reinterpret_cast<int32_t*>(e.out)[(int64_t)row * e.ld_out + c] = o;
     }
   } else if (e.mode == QGTC_OUT_F32) {
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       if ((j & km) != wave) continue;
       const int row = out_row0 + j;
-      if (tr_ok && c_ok && row < p.rows)
+      if (c_ok && row < p.rows)
         reinterpret_cast<float*>(e.out)[(int64_t)row * e.ld_out + c] = dequantize_f64(y[j], row, c, e);
     }
   } else {
@@ -229,27 +184,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
     const float qmaxf = (float)qmax;
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
-      const bool ok = tr_ok && c_ok && (out_row0 + j) < p.rows;
+      const bool ok = c_ok && (out_row0 + j) < p.rows;
       y[j] = ok ? requantize_i32(y[j], e, qmax, qmaxf) : 0u;
     }
     if (!MULTI && qbits == S && p.ksplit == 1) {
       uint32_t ow[S];
 #pragma unroll
       for (int i = 0; i < S; ++i) ow[i] = 0u;
-      pack_rows_fast<0, S, CWS>(y, ow);
+      pack_rows_fast<0, S>(y, ow);
       const int sj = lane >> 2;
       const int sk = lane & 3;
-      int srow_out, sword;
-      bool mine;
-      if constexpr (CWS == 6) {
-        srow_out = rt * 16 + sj;
-        sword = cg * 2 + sk;
-        mine = sk < 2;
-      } else {
-        srow_out = (rt * rgs + sk) * 16 + sj;
-        sword = 0;
-        mine = sk < rgs;
-      }
+      const int srow_out = tr * 16 + sj;
+      const int sword = cg * 2 + sk;
+      bool mine = sk < 2;
       mine = mine && srow_out < p.rows && sword < ((p.cols + 31) >> 5);
       if (mine) {
         uint32_t* dst = reinterpret_cast<uint32_t*>(e.out) + (int64_t)srow_out * e.ld_out + sword;
@@ -258,22 +205,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
       }
       return;
     }
-    // lane 4*j + k will store word k of row j.  CW = 64: k = 0, 1 are the two
-    // words of the column group; CW = 32 / 16: k is the row group and every
-    // row has a single word.
+    // lane 4*j + k will store word k (k = 0, 1) of row j of the column group
     const int sj = lane >> 2;
     const int sk = lane & 3;
-    bool mine = (sj & km) == wave;
-    int srow_out, sword;
-    if (CWS == 6) {
-      srow_out = rt * 16 + sj;
-      sword = cg * 2 + sk;
-      mine = mine && sk < 2;
-    } else {
-      srow_out = (rt * rgs + sk) * 16 + sj;
-      sword = 0;
-      mine = mine && sk < rgs;
-    }
+    bool mine = (sj & km) == wave && sk < 2;
+    const int srow_out = tr * 16 + sj;
+    const int sword = cg * 2 + sk;
     mine = mine && srow_out < p.rows && sword < ((p.cols + 31) >> 5);
     uint32_t* dst = reinterpret_cast<uint32_t*>(e.out) + (mine ? (int64_t)srow_out * e.ld_out + sword : 0);
 
@@ -281,7 +218,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
       uint32_t ow[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) ow[i] = 0u;
-      gather_rows<0, CWS>(y, ow, pg, km, wave);
+      gather_rows<0>(y, ow, pg, km, wave);
 #pragma unroll
       for (int i = 0; i < 8; ++i)
         if (mine && pg + i < qbits) dst[(int64_t)(pg + i) * e.ps_out] = ow[i];
@@ -289,35 +226,38 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
   }
 }
 
-template <int S, int CWS, bool MULTI>
-qgtc_status launch(const AggParams& p, hipStream_t stream) {
+template <int S, bool MULTI, int TW, int KS>
+qgtc_status launch_one(const AggParams& p, hipStream_t stream) {
   const unsigned grid = xcd_deal_grid(p.nblocks, p.chunk_shift);
   const size_t lds = p.ksplit > 1 ? (size_t)p.ksplit * 16 * 64 * sizeof(uint32_t) : 0;
-  if constexpr (CWS == 6) {
-    if (p.tile_words == 4)
-      hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI, 4>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
-    else if (p.tile_words == 2)
-      hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI, 2>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
-    else
-      hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI, 1>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
-  } else {
-    hipLaunchKernelGGL((aggregate_kernel<S, CWS, MULTI, 0>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
-  }
+  hipLaunchKernelGGL((aggregate_kernel<S, MULTI, TW, KS>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
   return launch_status();
 }
 
-template <int CWS>
+template <int S, bool MULTI>
+qgtc_status launch(const AggParams& p, hipStream_t stream) {
+  switch (p.tile_words * 8 + p.kslices) {
+    case 4 * 8 + 1: return launch_one<S, MULTI, 4, 1>(p, stream);
+    case 4 * 8 + 2: return launch_one<S, MULTI, 4, 2>(p, stream);
+    case 4 * 8 + 4: return launch_one<S, MULTI, 4, 4>(p, stream);
+    case 2 * 8 + 1: return launch_one<S, MULTI, 2, 1>(p, stream);
+    case 2 * 8 + 2: return launch_one<S, MULTI, 2, 2>(p, stream);
+    case 1 * 8 + 1: return launch_one<S, MULTI, 1, 1>(p, stream);
+    default: return QGTC_ERR_UNSUPPORTED;
+  }
+}
+
 qgtc_status dispatch(const AggParams& p, hipStream_t stream) {
   switch (p.s) {
-    case 1: return launch<1, CWS, false>(p, stream);
-    case 2: return launch<2, CWS, false>(p, stream);
-    case 3: return launch<3, CWS, false>(p, stream);
-    case 4: return launch<4, CWS, false>(p, stream);
-    case 5: return launch<5, CWS, false>(p, stream);
-    case 6: return launch<6, CWS, false>(p, stream);
-    case 7: return launch<7, CWS, false>(p, stream);
-    case 8: return launch<8, CWS, false>(p, stream);
-    default: return launch<8, CWS, true>(p, stream);
+    case 1: return launch<1, false>(p, stream);
+    case 2: return launch<2, false>(p, stream);
+    case 3: return launch<3, false>(p, stream);
+    case 4: return launch<4, false>(p, stream);
+    case 5: return launch<5, false>(p, stream);
+    case 6: return launch<6, false>(p, stream);
+    case 7: return launch<7, false>(p, stream);
+    case 8: return launch<8, false>(p, stream);
+    default: return launch<8, true>(p, stream);
   }
 }
 
@@ -337,14 +277,11 @@ extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* m
   if (st != QGTC_OK) return st;
   if (A->rows == 0 || X->cols == 0) return QGTC_OK;
 
-  p.cw_shift = X->cols > 32 ? 6 : (X->cols > 16 ? 5 : 4);
-  const int cw = 1 << p.cw_shift;
-  const int rgs = 64 / cw;
-  p.n_cg = cdiv(X->cols, cw);
-  p.n_rt = cdiv(p.n_tile_rows, rgs);
-  p.nblocks = (uint32_t)p.n_cg * (uint32_t)p.n_rt;
+  p.kslices = agg_kslices(X->cols, p.tile_words);
+  p.n_cg = cdiv(X->cols, 64);
+  p.nblocks = (uint32_t)p.n_cg * (uint32_t)p.n_tile_rows;
   // few waves: let the four waves of a workgroup split each tile list
-  p.ksplit = p.nblocks >= 4096u ? 1 : 4;
+  p.ksplit = p.nblocks >= 3072u ? 1 : 4;
   // Each XCD takes runs of `chunk` consecutive workgroups, run k going to XCD
   // k % 8.  A run covers all column groups of a few neighbouring tile rows, which
   // read the same word rows of X from the XCD's L2 (with few tiles per row these
@@ -355,6 +292,5 @@ extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* m
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_AGGREGATE, s);
-  if (p.cw_shift == 6) return dispatch<6>(p, s);
-  return p.cw_shift == 5 ? dispatch<5>(p, s) : dispatch<4>(p, s);
+  return dispatch(p, s);
 }

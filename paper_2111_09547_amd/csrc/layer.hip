@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void weight_bytes_kernel(const uint32_t* W, in
 typedef const __attribute__((address_space(4))) LayerParams* LateParams;
 #define QGTC_LATE(ptr) asm volatile("" : "+s"(ptr))
 
-template <int S, int TW>
+template <int S, int TW, int KS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void layer_kernel(const LayerParams p) {
   extern __shared__ uint32_t lds[];
   const AggParams& a = p.a;
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
 
   const int out_row0 = tr * 16;
   const __amdgpu_buffer_rsrc_t ra = agg_row_tile_rsrc(a, tr);
-  const uint32_t va_off = (uint32_t)(lane & 15) * (uint32_t)(a.lda * 4);   // this lane's adjacency row
+  constexpr int CW = 64 / KS;                        // columns per wave (K slices: see agg_core.inc)
   int n = a.row_cnt ? a.row_cnt[tr] : a.n_tile_cols;
   n = __builtin_amdgcn_readfirstlane(n);
   const int32_t* ci = a.col_idx ? a.col_idx + (int64_t)tr * a.n_tile_cols : nullptr;
@@ -136,14 +136,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
   for (int pass = 0; pass < p.n_pass; ++pass) {
     const int cg = pass * p.cgw + wcg;               // wave-uniform
     const bool cg_ok = cg < a.n_cg;
-    const int c = cg * 64 + lane;
-    const bool c_ok = cg_ok && c < a.cols;
-    const uint32_t col4 = (uint32_t)(c_ok ? c : a.cols - 1) * 4u;
+    const int c = cg * 64 + (lane & (CW - 1));
+    const bool c_ok = cg_ok && c < a.cols && (KS == 1 || lane < CW);   // slice 0 hands the results on
+    const uint32_t col4 = (uint32_t)min(c, a.cols - 1) * 4u;
+    uint32_t va_off, xoff;
+    agg_lane_offsets<TW, KS>(a, lane, col4, &va_off, &xoff);
 
     uint32_t acc[16][S];
     zero_acc<S>(acc);
     if (cg_ok)
-      agg_loop_uniform<S, TW, false>(acc, a, ra, va_off, rx, col4, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
+      agg_loop_uniform<S, TW, KS, false>(acc, a, ra, va_off, rx, xoff, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
     // shift-and-add of the per-plane popcounts (Algorithm 1, elementwise reduction)
     uint32_t y[16];
 #pragma unroll
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       uint32_t v = 0u;
 #pragma unroll
       for (int i = 0; i < S; ++i) v += acc[j][i] << i;
-      y[j] = v;
+      y[j] = agg_slice_sum<KS>(v);
     }
 
     LateParams k2 = kp;
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
         if ((j & km) != kpart) continue;
         uint32_t q = requantize_code(y[j], relu, rq_lo, rq_inv, qmax, qmaxf);
         q = (c_ok && j < valid_rows) ? q : 0u;
-        if (cg_ok) yb[j * ys + c] = (uint8_t)q;
+        if (cg_ok) yb[j * ys + cg * 64 + lane] = (uint8_t)q;   // zeros from the lanes past the last column
       }
     }
   }
@@ -363,12 +365,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
 template <int S>
 qgtc_status launch(const LayerParams& p, unsigned nw, size_t lds_bytes, hipStream_t stream) {
   const unsigned grid = xcd_deal_grid(p.a.nblocks, p.a.chunk_shift);
-  if (p.a.tile_words == 4)
-    hipLaunchKernelGGL((layer_kernel<S, 4>), dim3(grid), dim3(64 * nw), lds_bytes, stream, p);
-  else if (p.a.tile_words == 2)
-    hipLaunchKernelGGL((layer_kernel<S, 2>), dim3(grid), dim3(64 * nw), lds_bytes, stream, p);
-  else
-    hipLaunchKernelGGL((layer_kernel<S, 1>), dim3(grid), dim3(64 * nw), lds_bytes, stream, p);
+  const dim3 g(grid), b(64 * nw);
+  switch (p.a.tile_words * 8 + p.a.kslices) {
+    case 4 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 4, 1>), g, b, lds_bytes, stream, p); break;
+    case 4 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 4, 2>), g, b, lds_bytes, stream, p); break;
+    case 4 * 8 + 4: hipLaunchKernelGGL((layer_kernel<S, 4, 4>), g, b, lds_bytes, stream, p); break;
+    case 2 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 2, 1>), g, b, lds_bytes, stream, p); break;
+    case 2 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 2, 2>), g, b, lds_bytes, stream, p); break;
+    case 1 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 1, 1>), g, b, lds_bytes, stream, p); break;
+    default: return QGTC_ERR_UNSUPPORTED;
+  }
   return launch_status();
 }
 
@@ -389,7 +395,7 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   // what the kernel covers; everything else takes the two-kernel path
   if (X->nbits > 8 || W->nbits > 8 || agg_ep->rq_nbits < 1 || agg_ep->rq_nbits > 8) return QGTC_OK;
   if (upd_ep->mode == QGTC_OUT_BITS && upd_ep->rq_nbits > 8) return QGTC_OK;
-  if (X->cols <= 32 || X->cols > 1024 || W->cols < 1 || W->cols > 256) return QGTC_OK;
+  if (X->cols < 1 || X->cols > 1024 || W->cols < 1 || W->cols > 256) return QGTC_OK;
   if (A->rows < 1) return QGTC_OK;
   const bool w_bytes = W->layout == QGTC_RIGHT_BYTES;
   if (!w_bytes && workspace_bytes < layer_fused_workspace_bytes(X->cols, W->cols)) return QGTC_OK;
@@ -413,9 +419,8 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   ea.rq_inv_scale = agg_ep->rq_inv_scale;
 
   AggParams& a = p.a;
-  a.cw_shift = 6;
+  a.kslices = agg_kslices(X->cols, a.tile_words);
   a.n_cg = cdiv(X->cols, 64);
-  a.n_rt = a.n_tile_rows;
   a.nblocks = (uint32_t)a.n_tile_rows;
   p.cgw = a.n_cg <= 4 ? a.n_cg : (a.n_cg % 3 == 0 ? 3 : 4);
   p.n_pass = cdiv(a.n_cg, p.cgw);

@@ -26,7 +26,7 @@ class LayerRanges:
 
 def fused_layer_applies(d: int, h: int, s: int, t: int) -> bool:
     """The shapes and bit widths qgtc_layer runs as one kernel (see qgtc.h)."""
-    return 33 <= d <= 1024 and 1 <= h <= 256 and s <= 8 and t <= 8
+    return 1 <= d <= 1024 and 1 <= h <= 256 and s <= 8 and t <= 8
 
 
 class QuantGNN:

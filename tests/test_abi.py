@@ -112,9 +112,10 @@ def test_argument_validation_happens_before_any_launch():
     assert l.qgtc_layer(C.byref(A), None, C.byref(X), C.byref(W2), C.byref(epb), C.byref(ep),
                         C.c_void_p(0x30000), 16, out, 8, None) == 6
     # weights as bytes are for the fused kernel only: a shape it does not cover is refused
-    Wby = _fake_bits(b, 16, 8, 2, b.RIGHT_BYTES)
+    Wby = _fake_bits(b, 16, 300, 2, b.RIGHT_BYTES)
     assert l.qgtc_layer(C.byref(A), None, C.byref(X), C.byref(Wby), C.byref(epb), C.byref(ep),
-                        C.c_void_p(0x30000), 1 << 20, out, 8, None) == 7
+                        C.c_void_p(0x30000), 1 << 20, out, 300, None) == 7
+    Wby = _fake_bits(b, 16, 8, 2, b.RIGHT_BYTES)
     assert l.qgtc_update(C.byref(Y), C.byref(Wby), C.byref(ep), out, 8, None) == 5
     # pack: fp32 source needs a quantizer with hi > lo
     D = _fake_bits(b, 64, 16, 2, b.RIGHT)

@@ -317,7 +317,8 @@ def _layer_case(rng, n, d, h, s, t, block, self_term, p_edge=0.06):
     return A, Xq, Wq
 
 
-@pytest.mark.parametrize("shape", [(40, 33, 5), (100, 64, 64), (330, 70, 16), (257, 128, 100),
+@pytest.mark.parametrize("shape", [(200, 5, 3), (300, 16, 16), (100, 24, 40), (64, 32, 8),
+                                   (40, 33, 5), (100, 64, 64), (330, 70, 16), (257, 128, 100),
                                    (530, 200, 256), (96, 512, 16), (200, 600, 40), (64, 1024, 24)])
 @pytest.mark.parametrize("st", [(8, 8), (8, 3), (4, 8), (7, 7), (1, 1), (2, 5)])
 def test_fused_layer_all_outputs(shape, st):
