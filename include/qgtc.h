@@ -81,8 +81,15 @@ const char* qgtc_status_string(qgtc_status s);
  * ld_words.  8-bit codes are stored as two parts, their low 7 bits (part 0) and
  * their top bit (part 1), because the instruction multiplies signed bytes;
  * narrower codes have part 0 only.  Zero fill.  data must be 16-byte aligned.
+ *
+ * QGTC_LEFT_BYTES (left operand Y of qgtc_update only; rows x K, nbits <= 8): the
+ * codes themselves, one byte each, row-major: byte(r, k) = bytes[r * 4 * ld_words + k],
+ * ld_words a multiple of 4 with 4 * ld_words >= cols, zero fill up to the end of
+ * the row.  16 consecutive K positions of a row are one operand register group
+ * of the int8 matrix instruction, so the update reads this form without putting
+ * bit planes back together.  data must be 16-byte aligned.
  * ------------------------------------------------------------------------- */
-enum { QGTC_LEFT = 0, QGTC_RIGHT = 1, QGTC_RIGHT_BYTES = 2 };
+enum { QGTC_LEFT = 0, QGTC_RIGHT = 1, QGTC_RIGHT_BYTES = 2, QGTC_LEFT_BYTES = 3 };
 
 typedef struct qgtc_bits {
   uint32_t* data;
@@ -101,6 +108,7 @@ typedef struct qgtc_bits {
  *   LEFT : ld = 4*ceil(cols/128), plane stride = rows*ld
  *   RIGHT: ld = cols,             plane stride = ceil(rows/32)*ld
  *   RIGHT_BYTES: as stated above; the return value covers both parts for 8 bits
+ *   LEFT_BYTES: ld = 4*ceil(cols/16) words, plane stride = rows*ld (one "plane")
  * d->data is left untouched.  Returns 0 on invalid arguments. */
 size_t qgtc_describe(qgtc_bits* d, int32_t rows, int32_t cols, int32_t nbits,
                      int32_t layout, int32_t block_rows);
@@ -125,7 +133,7 @@ enum { QGTC_SRC_F32 = 0, QGTC_SRC_U8 = 1, QGTC_SRC_I32 = 2 };
  * src: device, row-major rows x cols with leading dimension ld_src (elements).
  * dst: descriptor filled by the caller (qgtc_describe) with rows/cols equal to
  * the arguments; every word of the packed matrix, padding included, is written.
- * Any of the three layouts. */
+ * Any of the four layouts. */
 qgtc_status qgtc_pack_bits(const void* src, int32_t src_dtype, int32_t rows,
                            int32_t cols, int64_t ld_src, const qgtc_quant* q,
                            const qgtc_bits* dst, void* stream);
@@ -231,7 +239,8 @@ qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* map,
                            void* out, int64_t ld_out, void* stream);
 
 /* Node update C = Y.W (second half of Algorithm 1).
- * Y: LEFT, s bits, rows x K.  W: RIGHT, t bits, K x cols. */
+ * Y: LEFT, s bits, rows x K, or LEFT_BYTES (then s, t <= 8: the product runs on the
+ * int8 matrix cores).  W: RIGHT, t bits, K x cols. */
 qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W,
                         const qgtc_epilogue* ep, void* out, int64_t ld_out,
                         void* stream);

@@ -227,11 +227,28 @@ def layer(A, Xq, Wq, s: int, rq=None, self_term: bool = False):
     return Y, Yq, Z, rq
 
 
+def layer_update_first(A, Xq, Wq, s: int, rq=None, self_term: bool = False):
+    """The other order of the two products (Section 6.1 of the paper has GIN update the
+    nodes before it aggregates; it pays when the update shrinks the feature dimension):
+    P = Xq @ Wq -> requantize to s bits -> Z = A @ Pq (+ Pq with the GIN self term).
+    Without the requantization in between, Z equals the aggregate-first result
+    (associativity).  Returns (P, Pq, Z, rq), rq calibrated from P when not given."""
+    P = update(Xq, Wq)
+    if rq is None:
+        rq = calibrate_requant(P, s)
+    Pq = requantize(P, rq[0], rq[1], s)
+    Z = aggregate(A, Pq, self_term)
+    return P, Pq, Z, rq
+
+
 def forward(A, X, x_range, Ws, w_ranges, s: int, t: int, self_term: bool,
-            rqs=None):
+            rqs=None, update_first: bool = False):
     """Multi-layer forward pass: every hidden layer ends in ReLU + requantize
     to s bits (the next layer's Xq); the last layer's integer result is
     returned as it is, together with everything needed to dequantize it.
+
+    update_first: every layer runs as layer_update_first; the trace then holds the
+    intermediate product P = Xq @ Wq and its codes under "Y" and "Yq".
 
     x_range / w_ranges are (lo, hi) pairs for Eq. (2).  rqs, when given, is a
     list of (agg_rq, out_rq) per layer; otherwise ranges are calibrated from the
@@ -242,7 +259,8 @@ def forward(A, X, x_range, Ws, w_ranges, s: int, t: int, self_term: bool,
     for l, W in enumerate(Ws):
         Wq = quantize(W, w_ranges[l][0], w_ranges[l][1], t)
         rq_in = None if rqs is None else rqs[l][0]
-        Y, Yq, Z, agg_rq = layer(A, Xq, Wq, s, rq_in, self_term)
+        one_layer = layer_update_first if update_first else layer
+        Y, Yq, Z, agg_rq = one_layer(A, Xq, Wq, s, rq_in, self_term)
         last = l == len(Ws) - 1
         if last:
             out_rq = None

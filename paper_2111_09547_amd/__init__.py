@@ -2,7 +2,7 @@
 of the C-ABI library libqgtc.so.  PyTorch is used for device memory and streams
 only; every step of the path runs in the library's HIP kernels."""
 from .binding import (  # noqa: F401
-    LEFT, RIGHT, RIGHT_BYTES, OUT_I32, OUT_F32, OUT_BITS,
+    LEFT, RIGHT, RIGHT_BYTES, LEFT_BYTES, OUT_I32, OUT_F32, OUT_BITS,
     KERNEL_PACK, KERNEL_TILE_MAP, KERNEL_AGGREGATE, KERNEL_UPDATE, KERNEL_SUMS, KERNEL_LAYER,
     QgtcError, Bits, TileMap, Epilogue, lib, lib_path, describe, alloc_bits,
     qgtc_pack_bits, qgtc_unpack_bits, qgtc_build_tile_map, qgtc_aggregate,

@@ -12,7 +12,7 @@ from dataclasses import dataclass, field
 
 import torch  # first: the HIP runtime PyTorch ships must be the one libqgtc binds to
 
-LEFT, RIGHT, RIGHT_BYTES = 0, 1, 2
+LEFT, RIGHT, RIGHT_BYTES, LEFT_BYTES = 0, 1, 2, 3
 SRC_F32, SRC_U8, SRC_I32 = 0, 1, 2
 OUT_I32, OUT_F32, OUT_BITS = 0, 1, 2
 KERNEL_PACK, KERNEL_TILE_MAP, KERNEL_AGGREGATE, KERNEL_UPDATE, KERNEL_SUMS, KERNEL_LAYER = range(6)
@@ -195,7 +195,7 @@ def describe(rows: int, cols: int, nbits: int, layout: int, block_rows: int = 0)
 def alloc_bits(rows, cols, nbits, layout, block_rows=0, ld_words=None, device="cuda") -> Bits:
     d, words = describe(rows, cols, nbits, layout, block_rows)
     if ld_words is not None:
-        assert layout != RIGHT_BYTES
+        assert layout in (LEFT, RIGHT)
         d.ld_words = ld_words
         k = rows if layout == LEFT else -(-rows // 32)
         d.plane_stride_words = k * ld_words

@@ -10,6 +10,7 @@ namespace qgtc {
 int64_t span_words(const qgtc_bits* b) {
   if (b->rows == 0 || b->cols == 0 || b->nbits == 0) return 0;
   if (b->layout == QGTC_RIGHT_BYTES) return (int64_t)(b->nbits == 8 ? 2 : 1) * b->plane_stride_words;
+  if (b->layout == QGTC_LEFT_BYTES) return (int64_t)(b->rows - 1) * b->ld_words + cdiv(b->cols, 4);
   if (b->layout == QGTC_LEFT)
     return (int64_t)(b->nbits - 1) * b->plane_stride_words + (int64_t)(b->rows - 1) * b->ld_words +
            cdiv(b->cols, 32);
@@ -19,14 +20,20 @@ int64_t span_words(const qgtc_bits* b) {
 
 qgtc_status check_bits(const qgtc_bits* b, int want_layout) {
   if (!b) return QGTC_ERR_NULL;
-  if (b->layout != QGTC_LEFT && b->layout != QGTC_RIGHT && b->layout != QGTC_RIGHT_BYTES)
+  if (b->layout != QGTC_LEFT && b->layout != QGTC_RIGHT && b->layout != QGTC_RIGHT_BYTES &&
+      b->layout != QGTC_LEFT_BYTES)
     return QGTC_ERR_LAYOUT;
   if (b->layout != want_layout) return QGTC_ERR_LAYOUT;
   if (b->nbits < 1 || b->nbits > 32) return QGTC_ERR_BITWIDTH;
   if (b->rows < 0 || b->cols < 0) return QGTC_ERR_SHAPE;
   if (b->rows > 0 && b->cols > 0 && !b->data) return QGTC_ERR_NULL;
   if (((uintptr_t)b->data & 3u) != 0) return QGTC_ERR_ALIGN;
-  if (b->layout == QGTC_RIGHT_BYTES) {
+  if (b->layout == QGTC_LEFT_BYTES) {
+    if (b->nbits > 8) return QGTC_ERR_BITWIDTH;
+    if (((uintptr_t)b->data & 15u) != 0 || (b->ld_words & 3) != 0) return QGTC_ERR_ALIGN;
+    if (b->ld_words * 4 < b->cols) return QGTC_ERR_SHAPE;
+    if (b->block_rows != 0) return QGTC_ERR_LAYOUT;
+  } else if (b->layout == QGTC_RIGHT_BYTES) {
     if (b->nbits > 8) return QGTC_ERR_BITWIDTH;
     if (((uintptr_t)b->data & 15u) != 0) return QGTC_ERR_ALIGN;
     if (b->ld_words != 256 * (int64_t)cdiv(b->rows, 64)) return QGTC_ERR_SHAPE;
@@ -195,15 +202,21 @@ extern "C" qgtc_status qgtc_set_option(int32_t option, int32_t value) {
 extern "C" size_t qgtc_describe(qgtc_bits* d, int32_t rows, int32_t cols, int32_t nbits, int32_t layout,
                                 int32_t block_rows) {
   if (!d || rows < 0 || cols < 0 || nbits < 1 || nbits > 32) return 0;
-  if (layout != QGTC_LEFT && layout != QGTC_RIGHT && layout != QGTC_RIGHT_BYTES) return 0;
+  if (layout != QGTC_LEFT && layout != QGTC_RIGHT && layout != QGTC_RIGHT_BYTES && layout != QGTC_LEFT_BYTES)
+    return 0;
   if (block_rows < 0 || (layout != QGTC_LEFT && block_rows != 0)) return 0;
-  if (layout == QGTC_RIGHT_BYTES && nbits > 8) return 0;
+  if ((layout == QGTC_RIGHT_BYTES || layout == QGTC_LEFT_BYTES) && nbits > 8) return 0;
   d->nbits = nbits;
   d->rows = rows;
   d->cols = cols;
   d->layout = layout;
   d->block_rows = block_rows;
   d->reserved = 0;
+  if (layout == QGTC_LEFT_BYTES) {
+    d->ld_words = 4 * (int64_t)cdiv(cols, 16);
+    d->plane_stride_words = (int64_t)rows * d->ld_words;
+    return (size_t)d->plane_stride_words;
+  }
   if (layout == QGTC_RIGHT_BYTES) {
     d->ld_words = 256 * (int64_t)cdiv(rows, 64);
     d->plane_stride_words = (int64_t)cdiv(cols, 16) * d->ld_words;

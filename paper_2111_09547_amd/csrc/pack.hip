@@ -173,6 +173,28 @@ __global__ __launch_bounds__(256) void pack_bytes_kernel(const PackParams p, int
   }
 }
 
+// LEFT_BYTES: one code per byte, row-major; a thread writes 4 consecutive bytes.
+template <int SRC>
+__global__ __launch_bounds__(256) void pack_left_bytes_kernel(const PackParams p) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;   // dword index
+  const int64_t r = idx / p.ld;
+  const int w = (int)(idx % p.ld);
+  if (r >= p.rows) return;
+  typename src_type<SRC>::type raw[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int c = w * 4 + b;
+    raw[b] = fetch_raw<SRC>(p, c < p.cols ? r * p.ld_src + c : 0);
+  }
+  uint32_t v = 0u;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int c = w * 4 + b;
+    v |= (c < p.cols ? to_code<SRC>(p, raw[b]) : 0u) << (8 * b);
+  }
+  p.dst[idx] = v;
+}
+
 struct UnpackParams {
   const uint32_t* src;
   int64_t ld, ps;
@@ -186,6 +208,10 @@ __global__ __launch_bounds__(256) void unpack_kernel(const UnpackParams p) {
   const int r = blockIdx.y * 4 + (threadIdx.x >> 6);
   if (c >= p.cols || r >= p.rows) return;
   uint32_t v = 0u;
+  if (p.layout == QGTC_LEFT_BYTES) {
+    p.dst[(int64_t)r * p.ld_dst + c] = reinterpret_cast<const uint8_t*>(p.src)[(int64_t)r * p.ld * 4 + c];
+    return;
+  }
   if (p.layout == QGTC_RIGHT_BYTES) {
     const uint8_t* bytes = reinterpret_cast<const uint8_t*>(p.src);
     const int64_t off = (int64_t)(c >> 4) * p.ld * 4 + (int64_t)(r >> 6) * 1024 +
@@ -273,7 +299,10 @@ __global__ __launch_bounds__(256) void col_sums_kernel(const UnpackParams p, int
 
 template <int SRC>
 qgtc_status launch_pack(const PackParams& p, int layout, hipStream_t s) {
-  if (layout == QGTC_RIGHT_BYTES) {
+  if (layout == QGTC_LEFT_BYTES) {
+    hipLaunchKernelGGL((pack_left_bytes_kernel<SRC>), dim3((unsigned)cdiv((int64_t)p.rows * p.ld, 256)), dim3(256),
+                       0, s, p);
+  } else if (layout == QGTC_RIGHT_BYTES) {
     const int n_nt = cdiv(p.cols, 16), n_ks = cdiv(p.rows, 64);
     hipLaunchKernelGGL((pack_bytes_kernel<SRC>), dim3((unsigned)cdiv((int64_t)n_nt * n_ks * 64, 256)), dim3(256),
                        0, s, p, n_nt, n_ks);

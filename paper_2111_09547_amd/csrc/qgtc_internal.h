@@ -64,6 +64,7 @@ qgtc_status make_epilogue(const qgtc_epilogue* ep, void* out, int64_t ld_out,
 // Arguments of the update kernels (popcount and int8-MFMA variants).
 struct UpdParams {
   const uint32_t* Y;
+  int32_t y_bytes;        // Y holds codes as bytes, row-major (ldy words per row)
   int64_t ldy, psy;       // words between rows / planes of Y
   int32_t rows;           // rows of Y (= output rows)
   int32_t s;              // planes of Y

@@ -185,7 +185,8 @@ using namespace qgtc;
 extern "C" qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W, const qgtc_epilogue* ep,
                                    void* out, int64_t ld_out, void* stream) {
   if (!Y || !W || !ep || !out) return QGTC_ERR_NULL;
-  qgtc_status st = check_bits(Y, QGTC_LEFT);
+  const bool y_bytes = Y->layout == QGTC_LEFT_BYTES;
+  qgtc_status st = check_bits(Y, y_bytes ? QGTC_LEFT_BYTES : QGTC_LEFT);
   if (st != QGTC_OK) return st;
   st = check_bits(W, QGTC_RIGHT);
   if (st != QGTC_OK) return st;
@@ -194,6 +195,7 @@ extern "C" qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W, const
 
   UpdParams p{};
   p.Y = Y->data;
+  p.y_bytes = y_bytes ? 1 : 0;
   p.ldy = Y->ld_words;
   p.psy = Y->plane_stride_words;
   p.rows = Y->rows;
@@ -225,6 +227,7 @@ extern "C" qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W, const
   // int8 matrix cores when the operands fit in bytes.  Measured on MI355X, they
   // win from 2 x 2 bits upwards; 1-bit x 1-bit stays on the popcount kernel.
   const int path = update_path_option();
+  if (y_bytes) return update_mfma_eligible(p) ? update_mfma_launch(p, s) : QGTC_ERR_UNSUPPORTED;
   if (path != 1 && update_mfma_eligible(p) && (path == 2 || Y->nbits * W->nbits >= 4))
     return update_mfma_launch(p, s);
   const int b = Y->nbits > W->nbits ? Y->nbits : W->nbits;

@@ -104,15 +104,25 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       const int row = row0 + mt * 16 + ln;
-      uint32_t f[8];
+      uint32_t d[4] = {0u, 0u, 0u, 0u};
+      if (p.y_bytes) {
+        // codes as bytes: the lane's 16 K positions are 16 consecutive bytes of its row
+        const int kb = ks * 64 + g * 16;
+        if (row < p.rows && kb < p.ldy * 4) {
+          const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(p.Y) +
+                                                          (int64_t)row * p.ldy * 4 + kb);
+          d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+        }
+      } else {
+        uint32_t f[8];
 #pragma unroll
-      for (int pl = 0; pl < 8; ++pl) {
-        f[pl] = 0u;
-        if (pl < p.s && row < p.rows && dw < p.kwords)
-          f[pl] = (p.Y[(int64_t)pl * p.psy + (int64_t)row * p.ldy + dw] >> sh) & 0xffffu;
+        for (int pl = 0; pl < 8; ++pl) {
+          f[pl] = 0u;
+          if (pl < p.s && row < p.rows && dw < p.kwords)
+            f[pl] = (p.Y[(int64_t)pl * p.psy + (int64_t)row * p.ldy + dw] >> sh) & 0xffffu;
+        }
+        planes_to_bytes(f, p.s, d);
       }
-      uint32_t d[4];
-      planes_to_bytes(f, p.s, d);
       v4i a7, ab;
       if (SPLIT_Y) {
         uint32_t lo[4], hi[4];

@@ -40,8 +40,13 @@ class QuantGNN:
 
     def __init__(self, A_src, Ws, s: int, t: int, self_term: bool,
                  tile_kbits: int = 128, use_map: bool = True, block_rows: int = 0,
-                 weights_as_bytes: bool = True):
+                 weights_as_bytes: bool = True, update_first: bool = False):
         self.s, self.t = s, t
+        # update_first: every layer computes A.(X.W) instead of (A.X).W (Section 6.1: GIN
+        # updates before it aggregates); it runs as qgtc_update + qgtc_aggregate on planes
+        self.update_first = update_first
+        if update_first:
+            weights_as_bytes = False
         self.self_term = self_term
         self.tile_kbits = tile_kbits
         self.use_map = use_map
@@ -68,6 +73,8 @@ class QuantGNN:
         # ping-pong buffers for the low-bit activations between layers
         hmax = max(h for _, h in self.dims)
         self.x_bufs = [B.alloc_bits(n, max(dmax, hmax), s, B.RIGHT) for _ in range(2)]
+        if update_first:                 # activations between layers as left operands of the update
+            self.xl_bufs = [B.alloc_bits(n, max(dmax, hmax), s, B.LEFT) for _ in range(2)]
         self.pack_static()
 
     def pack_static(self):
@@ -148,10 +155,76 @@ class QuantGNN:
                           rq_inv_scale=inv_scale(0.0, float(agg_hi), self.s),
                           self_term=self.self_term)
 
+    # -- update first ---------------------------------------------------------------------
+    def _xl_view(self, which: int, cols: int) -> B.Bits:
+        buf = self.xl_bufs[which]
+        d, _ = B.describe(self.A.rows, cols, self.s, B.LEFT)
+        d.plane_stride_words = buf.c.plane_stride_words
+        d.data = buf.words.data_ptr()
+        return B.Bits(buf.words, d)
+
+    def _forward_update_first(self, X, x_range, ranges, out, want_int):
+        """Per layer: P = X.W (qgtc_update, planes packed along the nodes out) ->
+        A.P (qgtc_aggregate; hidden layers emit planes packed along the features, the
+        left operand of the next update).  With ranges = None the int32 maxima are
+        collected on the way and returned as LayerRanges (agg_hi: range of P)."""
+        calibrating = ranges is None
+        found = []
+        if self.s <= 8 and self.t <= 8:
+            # the input goes straight to the int8 matrix cores: codes as bytes, no bit planes
+            if getattr(self, "_x_bytes", None) is None:
+                self._x_bytes = B.alloc_bits(X.shape[0], X.shape[1], self.s, B.LEFT_BYTES)
+            xl = B.qgtc_pack_bits(X, self.s, B.LEFT_BYTES, quant=x_range, out=self._x_bytes)
+        else:
+            xl = B.qgtc_pack_bits(X, self.s, B.LEFT, quant=x_range, out=self._xl_view(0, X.shape[1]))
+        n_layers = len(self.W)
+        scale = (float(x_range[1]) - float(x_range[0])) / float(2 ** self.s)
+        for l, W in enumerate(self.W):
+            d, h = self.dims[l]
+            last = l == n_layers - 1
+            if calibrating:
+                p32 = B.qgtc_update(xl, W, B.Epilogue(mode=B.OUT_I32))
+                p_hi = max(1, int(p32.max()))
+            else:
+                p_hi = ranges[l].agg_hi
+            inv_p = inv_scale(0.0, float(p_hi), self.s)
+            pb = B.qgtc_update(xl, W, B.Epilogue(mode=B.OUT_BITS, rq_nbits=self.s, rq_lo=0,
+                                                 rq_inv_scale=inv_p),
+                               out=self._x_view(l & 1, h))
+            lo_w, hi_w = self.w_ranges[l]
+            scale = scale * ((hi_w - lo_w) / float(2 ** self.t)) / inv_p
+            out_hi = None
+            if calibrating or (last and want_int):
+                z32 = B.qgtc_aggregate(self.A, self.map, pb,
+                                       B.Epilogue(mode=B.OUT_I32, self_term=self.self_term),
+                                       out=out if (last and want_int and not calibrating) else None)
+                if calibrating and not last:
+                    out_hi = max(1, int(z32.max()))
+            if calibrating:
+                found.append(LayerRanges(p_hi, out_hi))
+            else:
+                out_hi = ranges[l].out_hi
+            if last:
+                if calibrating:
+                    return found
+                if not want_int:
+                    # codes read as pure scales (no zero points): out = scale * (A.Pq)
+                    B.qgtc_aggregate(self.A, self.map, pb,
+                                     B.Epilogue(mode=B.OUT_F32, cc=scale, self_term=self.self_term), out=out)
+                return out
+            inv_z = inv_scale(0.0, float(out_hi), self.s)
+            xl = B.qgtc_aggregate(self.A, self.map, pb,
+                                  B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0,
+                                             rq_inv_scale=inv_z, self_term=self.self_term),
+                                  out=self._xl_view((l + 1) & 1, h))
+            scale = scale / inv_z
+
     # -- calibration: integer maxima per layer, from int32 outputs ---------------------
     def calibrate(self, X: torch.Tensor, x_range):
         """Runs the stack once with int32 outputs and returns LayerRanges per
         layer (range = [0, max observed accumulator], at least 1)."""
+        if self.update_first:
+            return self._forward_update_first(X, x_range, None, None, False)
         ranges = []
         xb = self.pack_input(X, x_range)
         if self._W_planes is None:          # qgtc_update reads bit planes
@@ -193,11 +266,13 @@ class QuantGNN:
         streams > 1 (block-diagonal storage): the subgraphs are cut into that many
         independent runs, each issued on a stream of its own, so that the start and the
         drain of one run's kernels overlap with the other runs' work."""
-        xb = self.pack_input(X, x_range)
         n = self.A.rows
         if out is None:
             out = torch.empty((n, self.dims[-1][1]), dtype=torch.int32 if want_int else torch.float32,
                               device=self.A.words.device)
+        if self.update_first:
+            return self._forward_update_first(X, x_range, ranges, out, want_int)
+        xb = self.pack_input(X, x_range)
         if streams <= 1 or self.A.c.block_rows == 0:
             self._run_layers(0, n, self.A, self.map, self.deg, xb, x_range, ranges, out, want_int,
                              self.workspace)

@@ -1,0 +1,140 @@
+"""Measurement sweeps beside bench.py (one GPU, synthetic inputs, HIP events):
+
+  table3   the aggregation A(1 bit) x X(s bits) at the shapes of the paper's Table 3
+           (N in {2048, 4096, 8192}, D in {32, 64}, s = 1..4), every tile non-zero,
+           as full-precision-equivalent TFLOP/s = 2 N^2 D / t (the paper's unit)
+  config3  one layer per bit width (s = t in 1..8, 16, 32) on the 8 x 1024 batch
+  config5  the 2-layer GCN on the power-law graph for s = t in {1, 2, 4, 8}, with 128- and
+           32-bit tiles, and in the update-first order A.(X.W)
+
+Run:  python -m paper_2111_09547_amd.sweeps [table3|config3|config5 ...]
+Prints one JSON line per measurement and a markdown table per sweep."""
+from __future__ import annotations
+
+import json
+import os
+import sys
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2111_09547_amd as q                         # noqa: E402
+from paper_2111_09547_amd.model import QuantGNN          # noqa: E402
+
+PEAK_BITOPS = 256 * 64 * 2.4e9 / 2 * 64                  # vector-ALU AND + popcount ceiling, bit-op/s
+
+
+def timeit(fn, n=20, warm=3, reps=5):
+    """Median over `reps` groups of n calls, in microseconds per call."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) / n * 1e3)
+    return sorted(ts)[len(ts) // 2]
+
+
+def table3():
+    rows = []
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    for d in (32, 64):
+        for n in (2048, 4096, 8192):
+            a = (torch.rand((n, n), device="cuda", generator=gen) < 0.5).to(torch.uint8)
+            ab = q.qgtc_pack_bits(a, 1, q.LEFT)
+            tmap = q.qgtc_build_tile_map(ab, 16, 128)
+            assert int(tmap.nnz_tiles.cpu()[0]) == (n // 16) * (n // 128)
+            rec = {"sweep": "table3", "N": n, "D": d}
+            for s in (1, 2, 3, 4):
+                x = torch.randint(0, 2 ** s, (n, d), dtype=torch.int32, device="cuda", generator=gen)
+                xb = q.qgtc_pack_bits(x, s, q.RIGHT)
+                ep = q.Epilogue(mode=q.OUT_I32)
+                out = q.qgtc_aggregate(ab, tmap, xb, ep)
+                t = timeit(lambda: q.qgtc_aggregate(ab, tmap, xb, ep, out=out))
+                rec[f"us_{s}bit"] = round(t, 2)
+                rec[f"tflops_equiv_{s}bit"] = round(2.0 * n * n * d / t / 1e6, 1)
+                rec[f"frac_valu_{s}bit"] = round(2.0 * n * n * d * s / (t * 1e-6) / PEAK_BITOPS, 3)
+            print(json.dumps(rec), flush=True)
+            rows.append(rec)
+    print("\n| N | D | 1-bit | 2-bit | 3-bit | 4-bit |  (TFLOP/s-equivalent = 2 N^2 D / t; in brackets: "
+          "fraction of the vector-ALU popcount ceiling)")
+    print("|---|---|---|---|---|---|")
+    for r in rows:
+        cells = " | ".join(f"{r[f'tflops_equiv_{s}bit']} ({r[f'frac_valu_{s}bit']})" for s in (1, 2, 3, 4))
+        print(f"| {r['N']} | {r['D']} | {cells} |")
+
+
+def _layer_bitops(net, n_nodes, kb):
+    nnz = int(net.map.nnz_tiles.cpu()[0])
+    agg = sum(2.0 * nnz * 16 * kb * d * net.s for d, _ in net.dims)
+    upd = sum(2.0 * n_nodes * d * h * net.s * net.t for d, h in net.dims)
+    return agg, upd
+
+
+def _model_sweep(cfg, bit_list, kb=128, update_first=False):
+    from workloads import make_workload
+    rows = []
+    for bits in bit_list:
+        w = make_workload(cfg, bits=bits)
+        g = w.graph
+        compact = w.storage == "compact"
+        a_src = torch.from_numpy(g.dense_compact() if compact else g.dense()).cuda()
+        ws = [torch.from_numpy(W).cuda() for W in w.W]
+        x = torch.from_numpy(w.X).cuda()
+        xr = (float(w.X.min()), float(w.X.max()))
+        net = QuantGNN(a_src, ws, w.s, w.t, w.model == "gin", tile_kbits=kb,
+                       block_rows=g.block if compact else 0, update_first=update_first)
+        ranges = net.calibrate(x, xr)
+        out = torch.empty((g.n_nodes, net.dims[-1][1]), dtype=torch.float32, device="cuda")
+        t = timeit(lambda: net.forward(x, xr, ranges, out=out), n=10)
+        agg, upd = _layer_bitops(net, g.n_nodes, kb)
+        if update_first:                 # the aggregation then runs on the H output columns
+            nnz = int(net.map.nnz_tiles.cpu()[0])
+            agg = sum(2.0 * nnz * 16 * kb * h * net.s for _, h in net.dims)
+        rec = {"sweep": f"config{cfg}", "order": "update first" if update_first else "aggregate first",
+               "bits": bits, "layers": len(net.dims), "us_forward": round(t, 1),
+               "us_per_layer": round(t / len(net.dims), 1),
+               "tbitops_executed": round((agg + upd) / t / 1e6, 1),
+               "agg_frac_valu": round(agg / (t * 1e-6) / PEAK_BITOPS, 3),
+               "tile_kbits": kb, "nonzero_tiles": int(net.map.nnz_tiles.cpu()[0])}
+        print(json.dumps(rec), flush=True)
+        rows.append(rec)
+        del net, a_src, x
+        torch.cuda.empty_cache()
+    print(f"\nconfig {cfg}, {rows[0]['order']}, tiles of 16 x {kb}:")
+    print(f"\n| s = t | forward (pack X + {rows[0]['layers']} layer(s)) us | executed Tbit-op/s | "
+          "aggregation bit-ops / forward time, fraction of the vector-ALU ceiling |")
+    print("|---|---|---|---|")
+    for r in rows:
+        print(f"| {r['bits']} | {r['us_forward']} | {r['tbitops_executed']} | {r['agg_frac_valu']} |")
+
+
+def config3():
+    _model_sweep(3, (1, 2, 3, 4, 5, 6, 7, 8, 16, 32))
+
+
+def config5():
+    for kb in (128, 32):
+        _model_sweep(5, (1, 2, 4, 8), kb=kb)
+    _model_sweep(5, (1, 2, 4, 8), kb=128, update_first=True)
+
+
+def main():
+    torch.cuda.set_device(0)
+    which = sys.argv[1:] or ["table3", "config3", "config5"]
+    for name in which:
+        {"table3": table3, "config3": config3, "config5": config5}[name]()
+
+
+if __name__ == "__main__":
+    main()

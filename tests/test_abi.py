@@ -47,6 +47,9 @@ def test_describe_and_sizes():
     assert (d.ld_words, d.plane_stride_words, words) == (512, 1024, 2048)
     assert b.lib().qgtc_describe(C.byref(d), 70, 20, 7, b.RIGHT_BYTES, 0) == 1024
     assert b.lib().qgtc_describe(C.byref(d), 70, 20, 9, b.RIGHT_BYTES, 0) == 0
+    words = b.lib().qgtc_describe(C.byref(d), 10, 70, 8, b.LEFT_BYTES, 0)
+    assert (d.ld_words, words) == (20, 200)
+    assert b.lib().qgtc_describe(C.byref(d), 10, 70, 9, b.LEFT_BYTES, 0) == 0
     assert b.lib().qgtc_layer_workspace_bytes(100, 70, 16, 4) >= 100 * 3 * 4 * 4 + 100 * 4
 
 
@@ -117,6 +120,11 @@ def test_argument_validation_happens_before_any_launch():
                         C.c_void_p(0x30000), 1 << 20, out, 300, None) == 7
     Wby = _fake_bits(b, 16, 8, 2, b.RIGHT_BYTES)
     assert l.qgtc_update(C.byref(Y), C.byref(Wby), C.byref(ep), out, 8, None) == 5
+    # codes as bytes on the left: only the matrix-core update takes them (<= 8 bits on both sides)
+    Yby = _fake_bits(b, 64, 64, 8, b.LEFT_BYTES)
+    W9 = _fake_bits(b, 64, 8, 9, b.RIGHT)
+    assert l.qgtc_update(C.byref(Yby), C.byref(W9), C.byref(ep), out, 8, None) == 7
+    assert l.qgtc_aggregate(C.byref(Yby), None, C.byref(X), C.byref(ep), out, 16, None) == 5
     # pack: fp32 source needs a quantizer with hi > lo
     D = _fake_bits(b, 64, 16, 2, b.RIGHT)
     assert l.qgtc_pack_bits(C.c_void_p(0x40000), 0, 64, 16, 16, None, C.byref(D), None) == 1

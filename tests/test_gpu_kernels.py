@@ -301,6 +301,37 @@ def test_popcount_probe_runs_and_leaves_its_sink_alone():
     assert int(sink.abs().sum()) == 0
 
 
+@pytest.mark.parametrize("st", [(8, 8), (8, 3), (5, 8), (1, 1)])
+@pytest.mark.parametrize("shape", [(100, 64, 64), (257, 130, 16), (70, 40, 5), (1000, 512, 16), (33, 7, 70)])
+def test_update_from_bytes(st, shape):
+    """Left operand as one byte per code (QGTC_LEFT_BYTES): layout as the header states
+    it, zero fill, and the update on it against the oracle in all three output modes."""
+    n, d, h = shape
+    s, t = st
+    rng = np.random.default_rng([12, n, d, h, s, t])
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    lo, hi = float(x.min()), float(x.max()) + 1e-3
+    Yq = qgnn.quantize(x, lo, hi, s)
+    Wq = rng.integers(0, 2 ** t, size=(d, h)).astype(np.uint32)
+    Yb = q.alloc_bits(n, d, s, q.LEFT_BYTES)
+    Yb.words.fill_(-1)
+    q.qgtc_pack_bits(dev(x), s, q.LEFT_BYTES, quant=(lo, hi), out=Yb)
+    ld = Yb.c.ld_words * 4
+    assert ld % 16 == 0 and ld >= d
+    raw = Yb.words.cpu().numpy().view(np.uint8)[:n * ld].reshape(n, ld)
+    assert (raw[:, :d] == Yq).all() and (raw[:, d:] == 0).all()
+    assert (as_u32(q.qgtc_unpack_bits(Yb)) == Yq).all()
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    Z = qgnn.update(Yq, Wq)
+    assert (as_u32(q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_I32))) == Z).all()
+    inv = qgnn.inv_scale(0.0, float(max(1, Z.max())), 4)
+    got = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=4, rq_lo=1, rq_inv_scale=float(inv)))
+    assert (words_np(got) == bp.pack(qgnn.requantize(Z, 1, inv, 4, relu=True), 4, bp.RIGHT)).all()
+    got = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_F32, cc=0.37)).cpu().numpy()
+    ref = qgnn.dequantize(Z, cc=0.37)
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+
+
 # ------------------------------------------------------------------- fused layer
 def _layer_case(rng, n, d, h, s, t, block, self_term, p_edge=0.06):
     A = np.zeros((n, n), dtype=np.uint8)

@@ -112,6 +112,38 @@ def run_model(w, tile_kbits=128):
     return net, ranges
 
 
+@pytest.mark.parametrize("cfg,bits,nb", [(5, 8, 4), (5, 4, 4), (4, 8, 2), (5, 8, None)])
+def test_update_first_order(cfg, bits, nb):
+    """A.(X.W) per layer (qgtc_update, then qgtc_aggregate): calibrated ranges, the last
+    int32 accumulators and the scale-only fp32 output against the oracle run in the same
+    order with the same ranges."""
+    w = make_workload(cfg, bits=bits, n_blocks=nb)
+    g = w.graph
+    self_term = w.model == "gin"
+    net = QuantGNN(dev(g.dense_compact()), [dev(W) for W in w.W], w.s, w.t, self_term,
+                   block_rows=g.block, update_first=True)
+    X = dev(w.X)
+    xr = (float(w.X.min()), float(w.X.max()))
+    wr = [(float(W.min()), float(W.max())) for W in w.W]
+    ranges = net.calibrate(X, xr)
+    rqs = [((0, qgnn.inv_scale(0.0, float(r.agg_hi), w.s)),
+            None if r.out_hi is None else (0, qgnn.inv_scale(0.0, float(r.out_hi), w.s))) for r in ranges]
+    trace, _ = qgnn.forward(g.scipy_csr(), w.X, xr, w.W, wr, w.s, w.t, self_term, rqs=rqs,
+                            update_first=True)
+    for r, tr in zip(ranges, trace):
+        assert r.agg_hi == max(1, int(qgnn.as_signed(tr["Y"]).max()))
+    z = net.forward(X, xr, ranges, want_int=True)
+    assert (as_u32(z) == trace[-1]["Z"]).all()
+    out = net.forward(X, xr, ranges).cpu().numpy()
+    scale = (xr[1] - xr[0]) / 2.0 ** w.s
+    for l in range(len(w.W)):
+        scale = scale * ((wr[l][1] - wr[l][0]) / 2.0 ** w.t) / float(rqs[l][0][1])
+        if rqs[l][1] is not None:
+            scale = scale / float(rqs[l][1][1])
+    ref = qgnn.dequantize(trace[-1]["Z"], cc=scale)
+    assert np.allclose(out, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+
+
 @pytest.mark.parametrize("nb", [2, None])
 def test_config4_gin_five_layers(nb):
     w = make_workload(4, n_blocks=nb)

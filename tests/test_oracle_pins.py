@@ -378,6 +378,29 @@ def test_tile_map_brute_force_and_block_structure():
 
 
 # -------------------------------------------------------------- multi-layer
+def test_update_first_equals_aggregate_first_without_requantization():
+    """A (X W) = (A X) W: with an identity requantization in between (range wide
+    enough, scale 1) the two orders of the layer give the same integers."""
+    rng = np.random.default_rng(77)
+    n, d, h, s, t = 40, 24, 7, 3, 2
+    A = (rng.random((n, n)) < 0.2).astype(np.uint8)
+    Xq = rng.integers(0, 2 ** s, size=(n, d)).astype(np.uint32)
+    Wq = rng.integers(0, 2 ** t, size=(d, h)).astype(np.uint32)
+    ident = (0, np.float32(1.0))
+    for self_term in (False, True):
+        _, Yq, Z1, _ = qgnn.layer(A, Xq, Wq, 20, rq=ident, self_term=self_term)
+        _, Pq, Z2, _ = qgnn.layer_update_first(A, Xq, Wq, 20, rq=ident, self_term=self_term)
+        assert (Yq == qgnn.aggregate(A, Xq, self_term)).all() and (Pq == qgnn.update(Xq, Wq)).all()
+        assert (Z1 == Z2).all()
+        want = (A.astype(np.int64) + (np.eye(n, dtype=np.int64) if self_term else 0)) @ Xq.astype(np.int64) \
+            @ Wq.astype(np.int64)
+        assert (Z2 == want.astype(np.uint32)).all()
+    # with a real requantization the orders differ (the rounding happens elsewhere)
+    _, _, Z1, _ = qgnn.layer(A, Xq, Wq, 2)
+    _, _, Z2, _ = qgnn.layer_update_first(A, Xq, Wq, 2)
+    assert (Z1 != Z2).any()
+
+
 def test_forward_chain_is_layerwise_consistent():
     from workloads import make_workload
     w = make_workload(4, n_blocks=1)
