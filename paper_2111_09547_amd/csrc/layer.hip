@@ -156,8 +156,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       y[j] = agg_slice_sum<KS>(v);
     }
 
+    // (the same for the wave-uniform row tests below: computed up front they are kept as
+    // sixteen SGPR pairs across the loop and spilled)
     LateParams k2 = kp;
     QGTC_LATE(k2);
+    int km2 = km, kpart2 = kpart, rows_left = a.rows - out_row0;
+    asm volatile("" : "+s"(km2), "+s"(kpart2), "+s"(rows_left));
     if (pass == p.n_pass - 1) {
       // unit `wave` is output tile `wave`, first chunk of K (see phase 3); a wave
       // without such a unit fetches tile 0 and does not use it
@@ -175,7 +179,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       __syncthreads();
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        if ((j & km) != kpart) continue;             // wave-uniform
+        if ((j & km2) != kpart2) continue;           // wave-uniform
         uint32_t v = 0u;
         for (int kp2 = 0; kp2 < a.ksplit; ++kp2) v += part[((kp2 * p.cgw + wcg) * 16 + j) * 64 + lane];
         y[j] = v;
@@ -212,12 +216,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       const uint32_t qmax = (1u << k2->a.ep.rq_nbits) - 1u;   // at most 8 bits here
       const float qmaxf = (float)qmax;
       const int ys = k2->ys;
-      const int valid_rows = a.rows - out_row0;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        if ((j & km) != kpart) continue;
+        if ((j & km2) != kpart2) continue;
         uint32_t q = requantize_code(y[j], relu, rq_lo, rq_inv, qmax, qmaxf);
-        q = (c_ok && j < valid_rows) ? q : 0u;
+        q = (c_ok && j < rows_left) ? q : 0u;
         if (cg_ok) yb[j * ys + cg * 64 + lane] = (uint8_t)q;   // zeros from the lanes past the last column
       }
     }
@@ -284,7 +287,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
   const int n_out = k4->h;
   const int zs = p.zs;
   const int mode = k4->up.mode;
-  const int valid_rows = a.rows - out_row0;
+  int valid_rows = a.rows - out_row0;
+  asm volatile("" : "+s"(valid_rows));
   for (int hb = wave * 64; hb < n_out; hb += nw * 64) {
     const int h = hb + lane;
     const bool h_ok = h < n_out;
