@@ -18,6 +18,8 @@
  *     failed call launches nothing and returns a status other than QGTC_OK.
  *   - Integer results are defined modulo 2^32 (32-bit accumulators,
  *     Sections 2.3 and 3.2).
+ *   - Empty operands (no rows, or no output columns) are valid: the call returns
+ *     QGTC_OK without launching, and the output pointer may then be NULL.
  */
 #ifndef QGTC_H
 #define QGTC_H

@@ -268,10 +268,11 @@ using namespace qgtc;
 
 extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc_bits* X,
                                       const qgtc_epilogue* ep, void* out, int64_t ld_out, void* stream) {
-  if (!A || !X || !ep || !out) return QGTC_ERR_NULL;
+  if (!A || !X || !ep) return QGTC_ERR_NULL;
   AggParams p{};
   qgtc_status st = agg_fill_params(A, map, X, &p);
   if (st != QGTC_OK) return st;
+  if (!out) return (A->rows == 0 || X->cols == 0) ? QGTC_OK : QGTC_ERR_NULL;   // an empty result needs no buffer
   const bool square = A->block_rows > 0 || A->rows == A->cols;
   st = make_epilogue(ep, out, ld_out, A->rows, X->cols, QGTC_LEFT, square, &p.ep);
   if (st != QGTC_OK) return st;

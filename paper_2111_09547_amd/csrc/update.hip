@@ -184,7 +184,8 @@ using namespace qgtc;
 
 extern "C" qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W, const qgtc_epilogue* ep,
                                    void* out, int64_t ld_out, void* stream) {
-  if (!Y || !W || !ep || !out) return QGTC_ERR_NULL;
+  if (!Y || !W || !ep) return QGTC_ERR_NULL;
+  if (!out && !(Y->rows == 0 || W->cols == 0)) return QGTC_ERR_NULL;   // an empty result needs no buffer
   const bool y_bytes = Y->layout == QGTC_LEFT_BYTES;
   qgtc_status st = check_bits(Y, y_bytes ? QGTC_LEFT_BYTES : QGTC_LEFT);
   if (st != QGTC_OK) return st;
@@ -206,9 +207,9 @@ extern "C" qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W, const
   p.psw = W->plane_stride_words;
   p.t = W->nbits;
   p.cols = W->cols;
+  if (Y->rows == 0 || W->cols == 0) return QGTC_OK;
   st = make_epilogue(ep, out, ld_out, Y->rows, W->cols, QGTC_RIGHT, false, &p.ep);
   if (st != QGTC_OK) return st;
-  if (Y->rows == 0 || W->cols == 0) return QGTC_OK;
 
   p.n_row_waves = cdiv(Y->rows, 64);
   // enough waves to fill 256 CUs x 4 SIMDs a few times over

@@ -301,6 +301,46 @@ def test_popcount_probe_runs_and_leaves_its_sink_alone():
     assert int(sink.abs().sum()) == 0
 
 
+@pytest.mark.parametrize("d", [16, 64, 130])
+def test_degenerate_graphs(d):
+    """Empty tile lists: an adjacency without any edge, one with edges in a single tile
+    row only, and isolated nodes with the GIN self term; aggregation and fused layer."""
+    rng = np.random.default_rng([13, d])
+    n, s, t, h = 200, 4, 3, 24
+    Xq = rng.integers(0, 2 ** s, size=(n, d)).astype(np.uint32)
+    Wq = rng.integers(0, 2 ** t, size=(d, h)).astype(np.uint32)
+    Xb = q.qgtc_pack_bits(dev(Xq.view(np.int32)), s, q.RIGHT)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT_BYTES)
+    one_row = np.zeros((n, n), dtype=np.uint8)
+    one_row[37, [3, 150, 199]] = 1
+    for A in (np.zeros((n, n), dtype=np.uint8), one_row):
+        for self_term in (False, True):
+            Ab = pack_adjacency(A)
+            for kb in (128, 32):
+                m = q.qgtc_build_tile_map(Ab, 16, kb)
+                assert int(m.nnz_tiles.cpu()[0]) == (0 if A.sum() == 0 else len({c // kb for c in (3, 150, 199)}))
+                want = qgnn.aggregate(A, Xq, self_term)
+                got = q.qgtc_aggregate(Ab, m, Xb, q.Epilogue(mode=q.OUT_I32, self_term=self_term))
+                assert (as_u32(got) == want).all(), (self_term, kb)
+                Yq = qgnn.requantize(want, 0, np.float32(0.5), s)
+                agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=s, rq_lo=0, rq_inv_scale=0.5, self_term=self_term)
+                got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32))
+                assert (as_u32(got) == qgnn.update(Yq, Wq)).all(), (self_term, kb)
+
+
+def test_empty_operands_launch_nothing():
+    Ab = q.alloc_bits(0, 64, 1, q.LEFT)
+    Xb = q.alloc_bits(64, 16, 2, q.RIGHT)
+    out = q.qgtc_aggregate(Ab, None, Xb, q.Epilogue(mode=q.OUT_I32))
+    sync()
+    assert tuple(out.shape) == (0, 16)
+    Yb = q.alloc_bits(0, 64, 2, q.LEFT)
+    Wb = q.alloc_bits(64, 8, 2, q.RIGHT)
+    out = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_I32))
+    sync()
+    assert tuple(out.shape) == (0, 8)
+
+
 @pytest.mark.parametrize("st", [(8, 8), (8, 3), (5, 8), (1, 1)])
 @pytest.mark.parametrize("shape", [(100, 64, 64), (257, 130, 16), (70, 40, 5), (1000, 512, 16), (33, 7, 70)])
 def test_update_from_bytes(st, shape):
