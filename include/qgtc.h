@@ -160,6 +160,13 @@ qgtc_status qgtc_col_sums(const qgtc_bits* m, int32_t* out, void* stream);
  *   row_cnt[tr]                      number of non-zero tiles in tile row tr
  *   col_idx[tr*n_tile_cols + i]      their tile-column indices, i < row_cnt[tr]
  *   nnz_tiles[0]                     total number of non-zero tiles
+ *   nnz_tiles[1]                     log2 of the run of consecutive tile rows the
+ *                                    product kernels keep on one XCD, 3..6: the
+ *                                    longest run of 8..64 tile rows for which the
+ *                                    busiest of the 8 XCDs (runs dealt round-robin,
+ *                                    a tile row weighing its tiles + 1) carries at
+ *                                    most 2 % more than the mean.  A hint that only
+ *                                    affects speed; nnz_tiles[2..3] are reserved.
  *   deg[r]                           popcount of row r of A (node degree)
  * Any tile shape with tile_rows in {8, 16, 32, 64} and tile_kbits in {32, 64,
  * 128, 256, 512} can be built (8 x 128 reproduces the statistic of the paper's
@@ -173,7 +180,7 @@ typedef struct qgtc_tile_map {
   int32_t n_tile_cols;  /* ceil(A.cols / tile_kbits) */
   int32_t* row_cnt;     /* [n_tile_rows] */
   int32_t* col_idx;     /* [n_tile_rows * n_tile_cols] */
-  int32_t* nnz_tiles;   /* [1] */
+  int32_t* nnz_tiles;   /* [4] */
   int32_t* deg;         /* [A.rows] */
 } qgtc_tile_map;
 
@@ -307,7 +314,8 @@ qgtc_status qgtc_prof_read(int32_t kind, double* total_ms, int64_t* launches);
  * column groups) go to one XCD, the next run to the next XCD.  Short runs balance
  * graphs whose tiles are concentrated in a few subgraphs; long runs keep one
  * subgraph's X panel in one L2.  Results do not depend on it.
- *   0   default (8 tile rows)
+ *   0   default: the run length the tile-map build chose, nnz_tiles[1] (8 tile
+ *       rows without a map)
  *   >0  that many tile rows (rounded up to a power of two of workgroups)
  *   <0  one contiguous range per XCD
  * QGTC_OPT_LAYER_PATH: 0 = qgtc_layer uses its fused kernel whenever it applies

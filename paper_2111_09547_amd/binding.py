@@ -148,7 +148,7 @@ class TileMap:
         return self._view(self.c.col_idx, self.c.n_tile_rows * self.c.n_tile_cols) \
             .view(self.c.n_tile_rows, self.c.n_tile_cols)
     @property
-    def nnz_tiles(self): return self._view(self.c.nnz_tiles, 1)
+    def nnz_tiles(self): return self._view(self.c.nnz_tiles, 2)
     @property
     def deg(self): return self._view(self.c.deg, self.rows)
 

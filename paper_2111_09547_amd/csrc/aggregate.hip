@@ -69,7 +69,7 @@ template <int S, bool MULTI, int TW, int KS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void aggregate_kernel(const AggParams p) {
   extern __shared__ uint32_t lds[];   // [ksplit][16][64] partial sums when ksplit > 1
 
-  const unsigned bid = xcd_deal(blockIdx.x, p.chunk_shift);
+  const unsigned bid = agg_logical_id(p);
   if (bid >= p.nblocks) return;       // whole workgroup leaves together
   const int tr = (int)(bid / (unsigned)p.n_cg);     // tile row
   const int cg = (int)(bid % (unsigned)p.n_cg);     // group of 64 columns
@@ -289,7 +289,7 @@ extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* m
   // are the diagonal tiles); dealing short runs round-robin spreads the rows of
   // one subgraph over all XCDs, so a subgraph that holds far more tiles than the
   // others (the hubs of a power-law graph) does not leave seven XCDs idle.
-  p.chunk_shift = agg_chunk_shift(p.n_cg, p.nblocks);
+  agg_set_dealing(&p, p.n_cg);
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_AGGREGATE, s);

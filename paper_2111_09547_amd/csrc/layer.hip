@@ -98,9 +98,8 @@ template <int S, int TW, int KS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void layer_kernel(const LayerParams p) {
   extern __shared__ uint32_t lds[];
   const AggParams& a = p.a;
-  const unsigned bid = xcd_deal(blockIdx.x, a.chunk_shift);
-  if (bid >= a.nblocks) return;                      // whole workgroup leaves together
-  const int tr = (int)bid;                           // tile row of this workgroup
+  int tr, n;                                         // tile row of this workgroup, its tile count
+  if (!agg_pick_tile_row(a, &tr, &n)) return;        // whole workgroup leaves together
   LateParams kp = (LateParams)__builtin_amdgcn_kernarg_segment_ptr();
 
   const int nw = (int)(blockDim.x >> 6);
@@ -117,7 +116,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
   const int out_row0 = tr * 16;
   const __amdgpu_buffer_rsrc_t ra = agg_row_tile_rsrc(a, tr);
   constexpr int CW = 64 / KS;                        // columns per wave (K slices: see agg_core.inc)
-  int n = a.row_cnt ? a.row_cnt[tr] : a.n_tile_cols;
   n = __builtin_amdgcn_readfirstlane(n);
   const int32_t* ci = a.col_idx ? a.col_idx + (int64_t)tr * a.n_tile_cols : nullptr;
   uint32_t kw_base = 0u;
@@ -441,7 +439,7 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
     if (p.cgw == 2 && a.ksplit == 1) a.ksplit = 2;
   }
   const unsigned nw = (unsigned)(p.cgw * a.ksplit);
-  a.chunk_shift = agg_chunk_shift(1, a.nblocks);
+  agg_set_dealing(&a, 1);
 
   p.h = W->cols;
   p.n_nt_w = cdiv(W->cols, 16);

@@ -100,18 +100,45 @@ __global__ __launch_bounds__(256) void tile_list16_kernel(const MapParams p) {
   if (lane == 0) p.row_cnt[tr] = count;
 }
 
-// Total number of non-zero tiles: one workgroup, no atomics.
+// Total number of non-zero tiles, and the length of the runs of tile rows that the
+// product kernels deal to one XCD: one workgroup, no atomics.
+//
+// Tile rows next to each other read the same word rows of X (inside a subgraph
+// all of them do), so the longer the run of tile rows that stays on one XCD, the
+// fewer L2s fetch the same rows of X from HBM.  Runs go round-robin to the 8
+// XCDs, and the XCD with the most work ends the kernel: the longest run is
+// chosen whose heaviest XCD carries at most 2 % more than the mean, a tile row
+// counted as its non-zero tiles plus one (the fixed part of a tile row costs
+// about one tile).  nnz[1] = log2 of that run, 3..6 (8..64 tile rows).
 __global__ __launch_bounds__(256) void tile_total_kernel(const MapParams p) {
-  __shared__ int part[256];
-  int acc = 0;
-  for (int i = threadIdx.x; i < p.n_tile_rows; i += 256) acc += p.row_cnt[i];
-  part[threadIdx.x] = acc;
-  __syncthreads();
-  for (int off = 128; off > 0; off >>= 1) {
-    if ((int)threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
-    __syncthreads();
+  __shared__ int part[4 * 8 * 256];              // [candidate][XCD][thread]
+  __shared__ unsigned long long load[4 * 8];
+  const int t = threadIdx.x;
+  for (int i = t; i < 4 * 8 * 256; i += 256) part[i] = 0;   // a thread only touches its own column
+  for (int i = t; i < p.n_tile_rows; i += 256) {
+    const int w = p.row_cnt[i] + 1;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) part[(c * 8 + ((i >> (3 + c)) & 7)) * 256 + t] += w;
   }
-  if (threadIdx.x == 0) p.nnz[0] = part[0];
+  __syncthreads();
+  if (t < 32) {
+    unsigned long long sum = 0ull;
+    for (int j = 0; j < 256; ++j) sum += (unsigned long long)part[t * 256 + ((j + t) & 255)];
+    load[t] = sum;
+  }
+  __syncthreads();
+  if (t == 0) {
+    unsigned long long total = 0ull;
+    for (int x = 0; x < 8; ++x) total += load[x];
+    int best = 3;
+    for (int c = 3; c >= 1; --c) {
+      unsigned long long mx = 0ull;
+      for (int x = 0; x < 8; ++x) mx = load[c * 8 + x] > mx ? load[c * 8 + x] : mx;
+      if (mx * 8ull * 50ull <= total * 51ull) { best = 3 + c; break; }
+    }
+    p.nnz[0] = (int)(total - (unsigned long long)p.n_tile_rows);
+    p.nnz[1] = best;
+  }
 }
 
 // deg[r] = popcount of row r: one wave per row.

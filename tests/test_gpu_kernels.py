@@ -116,6 +116,45 @@ def test_tile_map_matches_brute_force(tile):
     assert (m.deg.cpu().numpy() == deg).all()
 
 
+def expected_run_log2(cnt):
+    """The rule stated for nnz_tiles[1] in qgtc.h, on the host."""
+    w = np.asarray(cnt, dtype=np.int64) + 1
+    for sh in (6, 5, 4):
+        load = np.zeros(8, dtype=np.int64)
+        np.add.at(load, (np.arange(len(w)) >> sh) & 7, w)
+        if load.max() * 8 * 50 <= w.sum() * 51:
+            return sh
+    return 3
+
+
+@pytest.mark.parametrize("case", ["uniform", "hubs_first", "mild_skew", "small", "ragged"])
+def test_tile_map_run_hint(case):
+    """nnz_tiles[1]: long runs for evenly spread tiles, short ones when a few tile rows
+    hold most tiles or when there are too few tile rows for eight long runs."""
+    rng = np.random.default_rng(17)
+    n = {"small": 100 * 16, "ragged": 1000 * 16 + 5}.get(case, 1024 * 16)
+    k = 2048
+    A = np.zeros((n, k), dtype=np.uint8)
+    rows = np.arange(n)
+    A[rows, rows % k] = 1                                     # one tile per tile row at least
+    if case == "hubs_first":
+        A[:64 * 16:16, ::128] = 1                             # the first 64 tile rows hold every tile
+    if case == "mild_skew":
+        for tr in range(0, 1024, 4):
+            A[tr * 16, rng.integers(0, k, size=3)] = 1
+    Ab = pack_adjacency(A)
+    m = q.qgtc_build_tile_map(Ab, 16, 128)
+    sync()
+    cnt = m.row_cnt.cpu().numpy()
+    total, run = m.nnz_tiles.cpu().numpy().tolist()
+    assert total == cnt.sum()
+    assert run == expected_run_log2(cnt)
+    if case == "uniform":
+        assert run == 6
+    if case in ("hubs_first", "small"):
+        assert run == 3
+
+
 # ---------------------------------------------------------------------- aggregate
 def run_aggregate(A, X, s, tile_kbits=None, block=0, ep=None):
     if block:
