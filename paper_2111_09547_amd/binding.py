@@ -240,8 +240,10 @@ def qgtc_row_sums(bits: Bits) -> torch.Tensor:
     return out
 
 
-def qgtc_col_sums(bits: Bits) -> torch.Tensor:
-    out = torch.empty(bits.cols, dtype=torch.int32, device=bits.words.device)
+def qgtc_col_sums(bits: Bits, out: torch.Tensor | None = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty(bits.cols, dtype=torch.int32, device=bits.words.device)
+    assert out.dtype == torch.int32 and out.is_contiguous() and out.numel() >= bits.cols
     _check(lib().qgtc_col_sums(C.byref(bits.c), C.c_void_p(out.data_ptr()), _stream()),
            "qgtc_col_sums")
     return out

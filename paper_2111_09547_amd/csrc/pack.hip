@@ -50,32 +50,43 @@ __device__ __forceinline__ uint32_t fetch(const PackParams& p, int64_t idx) {
 template <int SRC>
 __global__ __launch_bounds__(256) void pack_right_kernel(const PackParams p) {
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
-  const int w = blockIdx.y * 4 + (threadIdx.x >> 6);
+  const int w_row = blockIdx.y * 4 + (threadIdx.x >> 6);
   const int n_wr = (p.rows + 31) >> 5;
-  if (c >= p.cols || w >= n_wr) return;
+  if (c >= p.cols || w_row >= n_wr) return;
   // all 32 loads of the word are issued before the first one is used
   typename src_type<SRC>::type raw[32];
 #pragma unroll
   for (int b = 0; b < 32; ++b) {
-    const int r = min(w * 32 + b, p.rows - 1);          // clamped: no branch around the load
+    const int r = min(w_row * 32 + b, p.rows - 1);      // clamped: no branch around the load
     raw[b] = fetch_raw<SRC>(p, (int64_t)r * p.ld_src + c);
   }
   uint32_t q[32];
 #pragma unroll
-  for (int b = 0; b < 32; ++b) q[b] = (w * 32 + b < p.rows) ? to_code<SRC>(p, raw[b]) : 0u;
+  for (int b = 0; b < 32; ++b) q[b] = (w_row * 32 + b < p.rows) ? to_code<SRC>(p, raw[b]) : 0u;
+  // 8 planes at a time: the codes of 8 rows are an 8 x 8 bit matrix (a byte per row)
+  // whose transpose has a byte per plane; four of them make the 32 rows of a word
   for (int p0 = 0; p0 < p.nbits; p0 += 8) {
-    uint32_t out[8];
+    uint32_t L[4], H[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) out[i] = 0u;
+    for (int g = 0; g < 4; ++g) {
+      uint32_t lo = 0u, hi = 0u;
 #pragma unroll
-    for (int b = 0; b < 32; ++b) {
-      const uint32_t v = q[b] >> p0;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) out[i] |= ((v >> i) & 1u) << b;
+      for (int k = 0; k < 4; ++k) {
+        lo |= ((q[8 * g + k] >> p0) & 0xffu) << (8 * k);
+        hi |= ((q[8 * g + 4 + k] >> p0) & 0xffu) << (8 * k);
+      }
+      transpose_bits_8x8(lo, hi);
+      L[g] = lo;
+      H[g] = hi;
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      if (p0 + i < p.nbits) p.dst[(int64_t)(p0 + i) * p.ps + (int64_t)w * p.ld + c] = out[i];
+    for (int i = 0; i < 8; ++i) {
+      const int sh = 8 * (i & 3);
+      uint32_t w = 0u;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) w |= (((i < 4 ? L[g] : H[g]) >> sh) & 0xffu) << (8 * g);
+      if (p0 + i < p.nbits) p.dst[(int64_t)(p0 + i) * p.ps + (int64_t)w_row * p.ld + c] = w;
+    }
   }
 }
 
@@ -273,17 +284,28 @@ __global__ __launch_bounds__(256) void col_sums_kernel(const UnpackParams p, int
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= p.cols) return;
   if (p.layout == QGTC_RIGHT_BYTES) {
-    // bytes of column c: 16 at a time, both parts
+    // bytes of column c: 16 at a time (one 16-byte load), both parts; rows past the
+    // last one are stored as zeros
     const uint8_t* bytes = reinterpret_cast<const uint8_t*>(p.src);
-    uint32_t sum = 0u;
+    uint32_t sum = 0u, top = 0u;
+#pragma unroll 4
     for (int r0 = 0; r0 < p.rows; r0 += 16) {
       const int64_t off = (int64_t)(c >> 4) * p.ld * 4 + (int64_t)(r0 >> 6) * 1024 +
                           ((c & 15) + 16 * ((r0 & 63) >> 4)) * 16;
-      for (int b = 0; b < 16; ++b) {               // zero fill past the last row
-        sum += bytes[off + b];
-        if (p.nbits == 8) sum += (uint32_t)bytes[p.ps * 4 + off + b] << 7;
+      const uint4 v = *reinterpret_cast<const uint4*>(bytes + off);
+      sum = __builtin_amdgcn_sad_u8(v.x, 0u, sum);
+      sum = __builtin_amdgcn_sad_u8(v.y, 0u, sum);
+      sum = __builtin_amdgcn_sad_u8(v.z, 0u, sum);
+      sum = __builtin_amdgcn_sad_u8(v.w, 0u, sum);
+      if (p.nbits == 8) {
+        const uint4 h = *reinterpret_cast<const uint4*>(bytes + p.ps * 4 + off);
+        top = __builtin_amdgcn_sad_u8(h.x, 0u, top);
+        top = __builtin_amdgcn_sad_u8(h.y, 0u, top);
+        top = __builtin_amdgcn_sad_u8(h.z, 0u, top);
+        top = __builtin_amdgcn_sad_u8(h.w, 0u, top);
       }
     }
+    sum += top << 7;
     out[c] = (int32_t)sum;
     return;
   }

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void tile_list16_kernel(const MapParams p) {
 }
 
 // Total number of non-zero tiles, and the length of the runs of tile rows that the
-// product kernels deal to one XCD: one workgroup, no atomics.
+// product kernels deal to one XCD: one workgroup.
 //
 // Tile rows next to each other read the same word rows of X (inside a subgraph
 // all of them do), so the longer the run of tile rows that stays on one XCD, the
@@ -111,20 +111,40 @@ __global__ __launch_bounds__(256) void tile_list16_kernel(const MapParams p) {
 // counted as its non-zero tiles plus one (the fixed part of a tile row costs
 // about one tile).  nnz[1] = log2 of that run, 3..6 (8..64 tile rows).
 __global__ __launch_bounds__(256) void tile_total_kernel(const MapParams p) {
-  __shared__ int part[4 * 8 * 256];              // [candidate][XCD][thread]
-  __shared__ unsigned long long load[4 * 8];
+  __shared__ unsigned long long load[4 * 8];     // [candidate: run of 8 << c tile rows][XCD]
   const int t = threadIdx.x;
-  for (int i = t; i < 4 * 8 * 256; i += 256) part[i] = 0;   // a thread only touches its own column
-  for (int i = t; i < p.n_tile_rows; i += 256) {
-    const int w = p.row_cnt[i] + 1;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) part[(c * 8 + ((i >> (3 + c)) & 7)) * 256 + t] += w;
+  const int lane = t & 63, wave = t >> 6;
+  if (t < 32) load[t] = 0ull;
+  // Thread t sees tile rows t, t + 256, ...: their runs of 8, 16 and 32 tile rows land
+  // on one XCD each, (t >> 3) & 7, (t >> 4) & 7 and (t >> 5) & 7 (256 is a multiple of
+  // 8 runs of 32), their runs of 64 alternate between two XCDs, wave and wave + 4.
+  unsigned long long even = 0ull, odd = 0ull;
+#pragma unroll 4
+  for (int i = t; i < p.n_tile_rows; i += 512) {     // several independent loads in flight
+    const int j = i + 256;
+    const int ce = p.row_cnt[i];
+    const int co = j < p.n_tile_rows ? p.row_cnt[j] + 1 : 0;
+    even += (unsigned long long)(ce + 1);
+    odd += (unsigned long long)co;
   }
   __syncthreads();
-  if (t < 32) {
-    unsigned long long sum = 0ull;
-    for (int j = 0; j < 256; ++j) sum += (unsigned long long)part[t * 256 + ((j + t) & 255)];
-    load[t] = sum;
+  auto group_sum = [&](unsigned long long v, int width) {   // sum over aligned groups of `width` lanes
+    for (int off = 1; off < width; off <<= 1) {
+      const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)v, off, 64);
+      const unsigned hi = (unsigned)__shfl_xor((int)(unsigned)(v >> 32), off, 64);
+      v += ((unsigned long long)hi << 32) | lo;
+    }
+    return v;
+  };
+  const unsigned long long all = even + odd;
+  const unsigned long long s8 = group_sum(all, 8), s16 = group_sum(all, 16), s32 = group_sum(all, 32);
+  const unsigned long long e64 = group_sum(even, 64), o64 = group_sum(odd, 64);
+  if ((lane & 7) == 0) atomicAdd(&load[0 * 8 + ((t >> 3) & 7)], s8);
+  if ((lane & 15) == 0) atomicAdd(&load[1 * 8 + ((t >> 4) & 7)], s16);
+  if ((lane & 31) == 0) atomicAdd(&load[2 * 8 + ((t >> 5) & 7)], s32);
+  if (lane == 0) {
+    atomicAdd(&load[3 * 8 + wave], e64);
+    atomicAdd(&load[3 * 8 + wave + 4], o64);
   }
   __syncthreads();
   if (t == 0) {

@@ -81,6 +81,19 @@ class QuantGNN:
         """Everything that does not depend on the features: pack A, build its
         zero-tile map, quantize and pack the weights (the paper caches these
         across layers and subgraphs, end of Section 3.2)."""
+        # The weights are a handful of small launches that do not depend on the adjacency:
+        # they go to a second stream (forked from and joined to the current one, also
+        # inside a HIP graph) and run beside the HBM-bound packing of A and its map.
+        cur = torch.cuda.current_stream()
+        if getattr(self, "_w_stream", None) is None:
+            self._w_stream = torch.cuda.Stream()
+            self._w_colsum_buf = torch.empty(self.dims[-1][1], dtype=torch.int32, device=self.A.words.device)
+        self._w_stream.wait_stream(cur)
+        with torch.cuda.stream(self._w_stream):
+            for W, r, dst, lay in zip(self.Ws, self.w_ranges, self.W, self.w_layout):
+                B.qgtc_pack_bits(W, self.t, lay, quant=r, out=dst)
+            # only the last layer dequantizes, so only its column sums are needed
+            self.w_colsum = [None] * (len(self.W) - 1) + [B.qgtc_col_sums(self.W[-1], out=self._w_colsum_buf)]
         if self.A_src is not None:
             B.qgtc_pack_bits(self.A_src, 1, B.LEFT, out=self.A)
         if self.use_map:
@@ -88,10 +101,7 @@ class QuantGNN:
             self.deg = self.map.deg
         else:
             self.deg = B.qgtc_row_sums(self.A)
-        for W, r, dst, lay in zip(self.Ws, self.w_ranges, self.W, self.w_layout):
-            B.qgtc_pack_bits(W, self.t, lay, quant=r, out=dst)
-        # only the last layer dequantizes, so only its column sums are needed
-        self.w_colsum = [None] * (len(self.W) - 1) + [B.qgtc_col_sums(self.W[-1])]
+        cur.wait_stream(self._w_stream)
 
     # -- helpers -----------------------------------------------------------------
     def _x_view(self, which: int, cols: int) -> B.Bits:
