@@ -123,8 +123,8 @@ def main():
     out = torch.empty((g.n_nodes, net.dims[-1][1]), dtype=torch.float32, device="cuda")
 
     def step():
-        net.pack_static()
-        net.forward(X, xr, ranges, out=out)
+        net.pack_static(X, xr)
+        net.forward(X, xr, ranges, out=out, x_packed=True)
 
     def layers_only():
         net.forward(X, xr, ranges, out=out)

@@ -77,10 +77,12 @@ class QuantGNN:
             self.xl_bufs = [B.alloc_bits(n, max(dmax, hmax), s, B.LEFT) for _ in range(2)]
         self.pack_static()
 
-    def pack_static(self):
+    def pack_static(self, X: torch.Tensor | None = None, x_range=None):
         """Everything that does not depend on the features: pack A, build its
         zero-tile map, quantize and pack the weights (the paper caches these
-        across layers and subgraphs, end of Section 3.2)."""
+        across layers and subgraphs, end of Section 3.2).  With X: the input features
+        of the coming forward pass are quantized and packed as well, after the weights
+        on their stream (forward(..., x_packed=True) then skips that step)."""
         # The weights are a handful of small launches that do not depend on the adjacency:
         # they go to a second stream (forked from and joined to the current one, also
         # inside a HIP graph) and run beside the HBM-bound packing of A and its map.
@@ -94,6 +96,8 @@ class QuantGNN:
                 B.qgtc_pack_bits(W, self.t, lay, quant=r, out=dst)
             # only the last layer dequantizes, so only its column sums are needed
             self.w_colsum = [None] * (len(self.W) - 1) + [B.qgtc_col_sums(self.W[-1], out=self._w_colsum_buf)]
+            if X is not None and not self.update_first:
+                self.pack_input(X, x_range)
         if self.A_src is not None:
             B.qgtc_pack_bits(self.A_src, 1, B.LEFT, out=self.A)
         if self.use_map:
@@ -270,7 +274,7 @@ class QuantGNN:
                           ck=lo_w * d, cs=sw, col_i=self.w_colsum[l])
 
     def forward(self, X: torch.Tensor, x_range, ranges, out: torch.Tensor | None = None,
-                want_int: bool = False, streams: int = 1):
+                want_int: bool = False, streams: int = 1, x_packed: bool = False):
         """fp32 [N, H_last] (or the last int32 accumulators when want_int).
 
         streams > 1 (block-diagonal storage): the subgraphs are cut into that many
@@ -282,7 +286,7 @@ class QuantGNN:
                               device=self.A.words.device)
         if self.update_first:
             return self._forward_update_first(X, x_range, ranges, out, want_int)
-        xb = self.pack_input(X, x_range)
+        xb = self._x_view(0, X.shape[1]) if x_packed else self.pack_input(X, x_range)
         if streams <= 1 or self.A.c.block_rows == 0:
             self._run_layers(0, n, self.A, self.map, self.deg, xb, x_range, ranges, out, want_int,
                              self.workspace)
@@ -316,8 +320,9 @@ class QuantGNN:
         through events, so the whole pass is one graph launch for the host."""
         def run():
             if with_static:
-                self.pack_static()
-            self.forward(X, x_range, ranges, out=out, want_int=want_int, streams=streams)
+                self.pack_static(X, x_range)
+            self.forward(X, x_range, ranges, out=out, want_int=want_int, streams=streams,
+                         x_packed=with_static and not self.update_first)
 
         cur = torch.cuda.current_stream()
         side = torch.cuda.Stream()
