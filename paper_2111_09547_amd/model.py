@@ -125,17 +125,26 @@ class QuantGNN:
         per run the row range, a view of A and a view of the tile map.  Subgraphs share
         no edge (Section 4.1), so the runs are independent from the first layer to the
         last and can be issued on different streams."""
-        key = (n_chunks, self.map.c.row_cnt if self.map is not None else 0)
+        key = (str(n_chunks), self.map.c.row_cnt if self.map is not None else 0)
         if getattr(self, "_chunk_cache", (None, None))[0] == key:
             return self._chunk_cache[1]
         br = self.A.c.block_rows
         assert br > 0 and br % 32 == 0, "independent runs need the block-diagonal storage"
         n = self.A.rows
         n_blocks = -(-n // br)
-        per = -(-n_blocks // n_chunks) * br
+        if isinstance(n_chunks, int):                 # equal runs
+            per = -(-n_blocks // n_chunks)
+            sizes = [per] * n_chunks
+        else:                                         # subgraphs per run, in order
+            sizes = list(n_chunks)
+            assert sum(sizes) >= n_blocks
+        bounds, b0 = [], 0
+        for sz in sizes:
+            if b0 < n_blocks and sz > 0:
+                bounds.append((b0 * br, min(n, (b0 + sz) * br)))
+            b0 += sz
         out = []
-        for r0 in range(0, n, per):
-            r1 = min(n, r0 + per)
+        for r0, r1 in bounds:
             a = B._BitsC.from_buffer_copy(self.A.c)
             a.data = self.A.c.data + r0 * self.A.c.ld_words * 4
             a.rows = r1 - r0
@@ -279,7 +288,9 @@ class QuantGNN:
 
         streams > 1 (block-diagonal storage): the subgraphs are cut into that many
         independent runs, each issued on a stream of its own, so that the start and the
-        drain of one run's kernels overlap with the other runs' work."""
+        drain of one run's kernels overlap with the other runs' work.  A list gives the
+        number of subgraphs of each run instead ([48, 16]: the first 48, then 16).
+        x_packed: the features are already packed (pack_static(X, x_range))."""
         n = self.A.rows
         if out is None:
             out = torch.empty((n, self.dims[-1][1]), dtype=torch.int32 if want_int else torch.float32,
@@ -287,7 +298,7 @@ class QuantGNN:
         if self.update_first:
             return self._forward_update_first(X, x_range, ranges, out, want_int)
         xb = self._x_view(0, X.shape[1]) if x_packed else self.pack_input(X, x_range)
-        if streams <= 1 or self.A.c.block_rows == 0:
+        if (isinstance(streams, int) and streams <= 1) or self.A.c.block_rows == 0:
             self._run_layers(0, n, self.A, self.map, self.deg, xb, x_range, ranges, out, want_int,
                              self.workspace)
             return out

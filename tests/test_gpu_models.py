@@ -77,7 +77,10 @@ def run_model(w, tile_kbits=128):
 
     # independent runs of subgraphs on several streams give the same bytes
     if w.storage == "compact":
-        for k in (2, 3):
+        nb = w.graph.n_blocks
+        for k in (2, 3, [nb - nb // 4, nb // 4], [1, nb - 1]):     # equal and uneven runs
+            if not isinstance(k, int) and min(k) < 1:
+                continue
             again = net.forward(X, xr, ranges, streams=k)
             torch.cuda.synchronize()
             assert torch.equal(again, out), k
