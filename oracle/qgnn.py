@@ -165,12 +165,45 @@ def requantize(c_u32, rq_lo: int, rq_inv_scale, nbits: int,
     return q.astype(np.uint32)
 
 
+def fold_batchnorm(gamma, beta, mean, var, eps: float, value_scale: float = 1.0):
+    """Section 4.5: BN(x)_j = (x - mean_j) / sqrt(var_j + eps) * gamma_j + beta_j is the
+    per-column affine map a_j x + b_j; with x = value_scale * C the kernel applies
+    (a_j * value_scale) C + b_j.  Returns (col_a, col_b) as fp32 vectors."""
+    g = np.asarray(gamma, dtype=np.float64) / np.sqrt(np.asarray(var, dtype=np.float64) + float(eps))
+    a = g * float(value_scale)
+    b = np.asarray(beta, dtype=np.float64) - g * np.asarray(mean, dtype=np.float64)
+    return a.astype(np.float32), b.astype(np.float32)
+
+
+def requantize_affine(c_u32, col_a, col_b, rq_lo: int, rq_inv_scale, nbits: int,
+                      relu: bool = False) -> np.ndarray:
+    """Low-bit output behind a per-column affine map (a batch normalization folded
+    into the kernel, Section 4.5): v = fp32(C) * a_j, v = v + b_j (two fp32
+    operations), ReLU, then Eq. (2) with lower bound rq_lo and the clamp."""
+    c = as_signed(c_u32).astype(np.float32)              # one int->fp32 rounding
+    a = np.asarray(col_a, dtype=np.float32)[None, :]
+    b = (np.zeros_like(a) if col_b is None else np.asarray(col_b, dtype=np.float32)[None, :])
+    v = c * a
+    v = v + b
+    assert v.dtype == np.float32
+    if relu:
+        v = np.where(v > 0, v, np.float32(0))
+    t = np.floor((v - np.float32(rq_lo)) * np.float32(rq_inv_scale))
+    assert t.dtype == np.float32
+    qmax = float(2 ** nbits - 1)
+    t64 = t.astype(np.float64)
+    q = np.where(t64 <= 0.0, 0.0, np.where(t64 >= qmax, qmax, t64))
+    return q.astype(np.uint32)
+
+
 def dequantize(c_u32, cc: float, rs: float = 0.0, row_i=None,
                l0a: float = 0.0, l0b: float = 0.0, row_l=None,
                ck: float = 0.0, cs: float = 0.0, col_i=None,
-               relu: bool = False) -> np.ndarray:
+               relu: bool = False, col_a=None, col_b=None) -> np.ndarray:
     """fp32 output of the last layer: the exact real product of the two
-    dequantized operands (see the module docstring), float64 then one rounding."""
+    dequantized operands (see the module docstring), float64 then one rounding.
+    col_a / col_b: a per-column affine map (folded batch normalization) applied to
+    that real value before the ReLU."""
     c = as_signed(c_u32).astype(np.float64)
     n, m = c.shape
     ri = np.zeros(n) if row_i is None else np.asarray(row_i, dtype=np.float64)
@@ -180,6 +213,9 @@ def dequantize(c_u32, cc: float, rs: float = 0.0, row_i=None,
     l0 = np.float64(l0a) + np.float64(l0b) * rl
     t2 = l0[:, None] * (np.float64(ck) + np.float64(cs) * ci)[None, :]
     v = t1 + t2
+    if col_a is not None:
+        cb = np.zeros(m) if col_b is None else np.asarray(col_b, dtype=np.float32).astype(np.float64)
+        v = v * np.asarray(col_a, dtype=np.float32).astype(np.float64)[None, :] + cb[None, :]
     if relu:
         v = np.maximum(v, 0.0)
     return v.astype(np.float32)
@@ -241,8 +277,18 @@ def layer_update_first(A, Xq, Wq, s: int, rq=None, self_term: bool = False):
     return P, Pq, Z, rq
 
 
+def calibrate_requant_affine(c_u32, col_a, col_b, nbits: int):
+    """calibrate_requant for an output behind a per-column affine map and a ReLU:
+    rq_lo = 0, hi = largest value met (at least 1e-6)."""
+    v = as_signed(c_u32).astype(np.float64) * np.asarray(col_a, dtype=np.float64)[None, :]
+    if col_b is not None:
+        v = v + np.asarray(col_b, dtype=np.float64)[None, :]
+    hi = max(1e-6, float(v.max()))
+    return 0, inv_scale(0.0, hi, nbits)
+
+
 def forward(A, X, x_range, Ws, w_ranges, s: int, t: int, self_term: bool,
-            rqs=None, update_first: bool = False):
+            rqs=None, update_first: bool = False, affines=None):
     """Multi-layer forward pass: every hidden layer ends in ReLU + requantize
     to s bits (the next layer's Xq); the last layer's integer result is
     returned as it is, together with everything needed to dequantize it.
@@ -252,7 +298,8 @@ def forward(A, X, x_range, Ws, w_ranges, s: int, t: int, self_term: bool,
 
     x_range / w_ranges are (lo, hi) pairs for Eq. (2).  rqs, when given, is a
     list of (agg_rq, out_rq) per layer; otherwise ranges are calibrated from the
-    values met on the way and returned."""
+    values met on the way and returned.  affines: per layer None or (col_a, col_b),
+    the per-column affine map in front of a hidden layer's ReLU."""
     Xq = quantize(X, x_range[0], x_range[1], s)
     trace = []
     used = []
@@ -265,6 +312,11 @@ def forward(A, X, x_range, Ws, w_ranges, s: int, t: int, self_term: bool,
         if last:
             out_rq = None
             nxt = None
+        elif affines is not None and affines[l] is not None:
+            # a batch normalization folded into the layer's epilogue (Section 4.5)
+            ca, cb = affines[l]
+            out_rq = calibrate_requant_affine(Z, ca, cb, s) if rqs is None else rqs[l][1]
+            nxt = requantize_affine(Z, ca, cb, out_rq[0], out_rq[1], s, relu=True)
         else:
             out_rq = calibrate_requant(Z, s) if rqs is None else rqs[l][1]
             nxt = requantize(Z, out_rq[0], out_rq[1], s, relu=True)

@@ -418,3 +418,56 @@ def test_forward_chain_is_layerwise_consistent():
     # giving the calibrated ranges back reproduces the same integers
     trace2, _ = qgnn.forward(A, w.X, xr, w.W, wr, w.s, w.t, True, rqs=rqs)
     assert all((a["Z"] == b["Z"]).all() for a, b in zip(trace, trace2))
+
+
+# ---------------------------------------------------- folded batch normalization
+def test_affine_requantize_reduces_to_requantize():
+    """a = 1, b = 0: the affine path is the integer rule (all values below 2^24, where
+    fp32(C) - fp32(lo) and the integer difference agree)."""
+    rng = np.random.default_rng(41)
+    C = rng.integers(-5000, 200000, size=(40, 9)).astype(np.int64)
+    c_u32 = (C & 0xFFFFFFFF).astype(np.uint32)
+    ones = np.ones(9, dtype=np.float32)
+    for bits, lo, relu in ((4, 0, True), (8, 17, False), (3, 0, False), (8, 1000, True)):
+        inv = qgnn.inv_scale(float(lo), 180000.0, bits)
+        want = qgnn.requantize(c_u32, lo, inv, bits, relu=relu)
+        got = qgnn.requantize_affine(c_u32, ones, None, lo, inv, bits, relu=relu)
+        assert (got == want).all()
+        got = qgnn.requantize_affine(c_u32, ones, np.zeros(9, dtype=np.float32), lo, inv, bits, relu=relu)
+        assert (got == want).all()
+
+
+def test_batchnorm_fold_matches_the_definition():
+    """Section 4.5: codes produced behind the folded affine map stand for
+    ReLU(BN(x)) computed from its definition (batch statistics, gamma, beta, eps) to
+    within one quantization step; a dropped shift, a missing sqrt or a swapped
+    gamma / beta would be off by far more."""
+    rng = np.random.default_rng(43)
+    n, h, bits = 500, 12, 8
+    C = rng.integers(-30000, 90000, size=(n, h)).astype(np.int64)
+    value_scale = 3.1e-4                                   # x = value_scale * C
+    x = value_scale * C.astype(np.float64)
+    gamma = rng.uniform(0.5, 2.0, size=h)
+    beta = rng.uniform(-1.0, 1.0, size=h)
+    eps = 1e-5
+    mean, var = x.mean(axis=0), x.var(axis=0)
+    bn = (x - mean[None, :]) / np.sqrt(var[None, :] + eps) * gamma[None, :] + beta[None, :]
+    want = np.maximum(bn, 0.0)
+    a, b = qgnn.fold_batchnorm(gamma, beta, mean, var, eps, value_scale)
+    hi = float(want.max())
+    inv = qgnn.inv_scale(0.0, hi, bits)
+    c_u32 = (C & 0xFFFFFFFF).astype(np.uint32)
+    q = qgnn.requantize_affine(c_u32, a, b, 0, inv, bits, relu=True)
+    step = hi / 2 ** bits
+    back = q.astype(np.float64) * step
+    inside = want < hi - step                               # the top code also holds the clamp
+    assert np.all(back[inside] <= want[inside] + 1e-4 * hi)
+    assert np.all(want[inside] - back[inside] < step * (1 + 1e-3) + 1e-4 * hi)
+    assert (q[want == 0.0] == 0).all() and q.max() == 2 ** bits - 1
+    # fp32 output: the affine map acts on the real value, in front of the ReLU
+    base = qgnn.dequantize(c_u32, cc=value_scale)
+    a1, b1 = qgnn.fold_batchnorm(gamma, beta, mean, var, eps, 1.0)
+    got = qgnn.dequantize(c_u32, cc=value_scale, col_a=a1, col_b=b1, relu=True)
+    assert np.allclose(got, want, rtol=1e-5, atol=1e-5 * hi)
+    assert np.allclose(qgnn.dequantize(c_u32, cc=value_scale, col_a=a1, col_b=None),
+                       base.astype(np.float64) * a1[None, :].astype(np.float64), rtol=1e-6, atol=1e-9)
