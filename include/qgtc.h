@@ -221,6 +221,21 @@ qgtc_status qgtc_build_tile_map(const qgtc_bits* A, const qgtc_tile_map* map,
  *
  * self_term (qgtc_aggregate only): adds X[i, j] itself to C, i.e. the GIN
  * aggregation (1 + eps).X + A.X with eps = 0; needs a square adjacency.
+ *
+ * col_scale / col_shift (device, one float per output column, or both NULL): a
+ * per-column affine map in front of the activation, which is how a batch
+ * normalization that follows the layer folds into the kernel (Section 4.5:
+ * BN(x) = (x - E_j) / sqrt(Var_j + eps) * gamma_j + beta_j = a_j x + b_j).
+ * col_shift alone may be NULL (zeros).  With col_scale set,
+ *   QGTC_OUT_BITS: v = fp32(C) * col_scale[j]        (C signed; one rounded multiply)
+ *                  v = v + col_shift[j]              (one rounded add, no fused multiply-add)
+ *                  v = max(v, 0) with relu (NaN -> 0)
+ *                  code = Eq. (2) of v with lower bound fp32(rq_lo) and rq_inv_scale,
+ *                         clamped to [0, 2^rq_nbits - 1] as in qgtc_quant
+ *                  (the caller puts the scale of C into col_scale);
+ *   QGTC_OUT_F32:  out = fp32((t1 + t2) * col_scale[j] + col_shift[j]) in fp64,
+ *                  max(., 0) first with relu;
+ *   QGTC_OUT_I32:  QGTC_ERR_UNSUPPORTED.
  * ------------------------------------------------------------------------- */
 enum { QGTC_OUT_I32 = 0, QGTC_OUT_F32 = 1, QGTC_OUT_BITS = 2 };
 
@@ -235,6 +250,8 @@ typedef struct qgtc_epilogue {
   const int32_t* row_i; /* [rows] or NULL */
   const int32_t* row_l; /* [rows] or NULL */
   const int32_t* col_i; /* [cols] or NULL */
+  const float* col_scale; /* [cols] or NULL */
+  const float* col_shift; /* [cols] or NULL */
 } qgtc_epilogue;
 
 /* Neighbour aggregation C = A.X (first half of Algorithm 1; zero-tile jumping

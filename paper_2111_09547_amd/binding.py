@@ -52,7 +52,8 @@ class _EpilogueC(C.Structure):
                 ("rq_nbits", C.c_int32), ("rq_lo", C.c_int32), ("rq_inv_scale", C.c_float),
                 ("cc", C.c_double), ("rs", C.c_double), ("l0a", C.c_double),
                 ("l0b", C.c_double), ("ck", C.c_double), ("cs", C.c_double),
-                ("row_i", C.c_void_p), ("row_l", C.c_void_p), ("col_i", C.c_void_p)]
+                ("row_i", C.c_void_p), ("row_l", C.c_void_p), ("col_i", C.c_void_p),
+                ("col_scale", C.c_void_p), ("col_shift", C.c_void_p)]
 
 
 _lib = None
@@ -170,6 +171,8 @@ class Epilogue:
     row_i: torch.Tensor | None = None
     row_l: torch.Tensor | None = None
     col_i: torch.Tensor | None = None
+    col_scale: torch.Tensor | None = None      # fp32 [cols]: per-column affine (folded batch norm)
+    col_shift: torch.Tensor | None = None
     _keep: list = field(default_factory=list, repr=False)
 
     def to_c(self) -> _EpilogueC:
@@ -178,10 +181,15 @@ class Epilogue:
                 return None
             assert t.dtype == torch.int32 and t.is_contiguous() and t.is_cuda
             return t.data_ptr()
+        def fptr(t):
+            if t is None:
+                return None
+            assert t.dtype == torch.float32 and t.is_contiguous() and t.is_cuda
+            return t.data_ptr()
         return _EpilogueC(self.mode, int(self.relu), int(self.self_term), self.rq_nbits,
                           self.rq_lo, self.rq_inv_scale, self.cc, self.rs, self.l0a,
                           self.l0b, self.ck, self.cs, ptr(self.row_i), ptr(self.row_l),
-                          ptr(self.col_i))
+                          ptr(self.col_i), fptr(self.col_scale), fptr(self.col_shift))
 
 
 def describe(rows: int, cols: int, nbits: int, layout: int, block_rows: int = 0):

@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const bool ok = c_ok && (out_row0 + j) < p.rows;
-      y[j] = ok ? requantize_i32(y[j], e, qmax, qmaxf) : 0u;
+      y[j] = ok ? requantize_i32(y[j], min(c, p.cols - 1), e, qmax, qmaxf) : 0u;
     }
     if (!MULTI && qbits == S && p.ksplit == 1) {
       uint32_t ow[S];

@@ -82,6 +82,10 @@ qgtc_status make_epilogue(const qgtc_epilogue* ep, void* out, int64_t ld_out, in
   p->row_i = ep->row_i;
   p->row_l = ep->row_l;
   p->col_i = ep->col_i;
+  if (ep->col_shift && !ep->col_scale) return QGTC_ERR_NULL;
+  if (ep->col_scale && ep->mode == QGTC_OUT_I32) return QGTC_ERR_UNSUPPORTED;
+  p->col_a = ep->col_scale;
+  p->col_b = ep->col_shift;
   if (ep->mode == QGTC_OUT_BITS) {
     const qgtc_bits* d = reinterpret_cast<const qgtc_bits*>(out);
     qgtc_status st = check_bits(d, bits_layout);
@@ -255,6 +259,7 @@ extern "C" qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map, 
                                   void* out, int64_t ld_out, void* stream) {
   if (!A || !X || !W || !agg_ep || !upd_ep || !workspace || !out) return QGTC_ERR_NULL;
   if (agg_ep->mode != QGTC_OUT_BITS) return QGTC_ERR_UNSUPPORTED;
+  if (agg_ep->col_scale || agg_ep->col_shift) return QGTC_ERR_UNSUPPORTED;   // the affine map belongs to upd_ep
   if (((uintptr_t)workspace & 15u) != 0) return QGTC_ERR_ALIGN;
   if (agg_ep->rq_nbits < 1 || agg_ep->rq_nbits > 32) return QGTC_ERR_BITWIDTH;
   if (workspace_bytes < qgtc_layer_workspace_bytes(A->rows, X->cols, W->cols, agg_ep->rq_nbits))

@@ -311,6 +311,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       e.cc = k4->up.cc; e.rs = k4->up.rs; e.l0a = k4->up.l0a; e.l0b = k4->up.l0b;
       e.ck = k4->up.ck; e.cs = k4->up.cs;
       e.row_i = k4->up.row_i; e.row_l = k4->up.row_l; e.col_i = k4->up.col_i;
+      e.col_a = k4->up.col_a; e.col_b = k4->up.col_b;
       float* out = reinterpret_cast<float*>(k4->up.out);
       const int64_t ld_out = k4->up.ld_out;
       const int want_rowsum = k4->want_rowsum;
@@ -333,11 +334,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       const uint32_t qmax = (1u << qbits) - 1u;
       const float qmaxf = (float)qmax;
       uint32_t b[4] = {0u, 0u, 0u, 0u};
+      const float* col_a = k4->up.col_a;             // folded batch normalization, or NULL
+      if (col_a) {
+        const float* col_b = k4->up.col_b;
+        const float ca = col_a[hc];
+        const float cb = col_b ? col_b[hc] : 0.0f;
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        uint32_t q = requantize_code(zz[j], relu, rq_lo, rq_inv, qmax, qmaxf);
-        q = (h_ok && j < valid_rows) ? q : 0u;
-        b[j >> 2] |= q << (8 * (j & 3));
+        for (int j = 0; j < 16; ++j) {
+          uint32_t q = requantize_affine(zz[j], ca, cb, relu, rq_lo, rq_inv, qmax, qmaxf);
+          q = (h_ok && j < valid_rows) ? q : 0u;
+          b[j >> 2] |= q << (8 * (j & 3));
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          uint32_t q = requantize_code(zz[j], relu, rq_lo, rq_inv, qmax, qmaxf);
+          q = (h_ok && j < valid_rows) ? q : 0u;
+          b[j >> 2] |= q << (8 * (j & 3));
+        }
       }
       transpose_bits_8x8(b[0], b[1]);                // byte i: bit i of the codes of rows 0..7
       transpose_bits_8x8(b[2], b[3]);                // rows 8..15

@@ -52,6 +52,8 @@ struct EpiParams {
   const int32_t* row_i;
   const int32_t* row_l;
   const int32_t* col_i;
+  const float* col_a;  // per-column affine in front of the activation (NULL: none)
+  const float* col_b;
   void* out;           // int32_t* / float* / planes base (uint32_t*)
   int64_t ld_out;      // elements (I32/F32) or words (BITS)
   int64_t ps_out;      // BITS: plane stride in words
@@ -137,8 +139,22 @@ __device__ __forceinline__ uint32_t requantize_code(uint32_t c_u32, int relu, in
   return (uint32_t)t;
 }
 
-__device__ __forceinline__ uint32_t requantize_i32(uint32_t c_u32, const EpiParams& e,
+// The same behind a per-column affine map (a folded batch normalization); see
+// col_scale in qgtc.h.  Two separately rounded fp32 operations, then Eq. (2).
+__device__ __forceinline__ uint32_t requantize_affine(uint32_t c_u32, float a, float b, int relu,
+                                                      int32_t rq_lo, float rq_inv_scale,
+                                                      uint32_t qmax, float qmaxf) {
+  float v = (float)(int32_t)c_u32 * a;
+  v = v + b;
+  if (relu && !(v > 0.0f)) v = 0.0f;
+  return quantize_f32(v, (float)rq_lo, rq_inv_scale, qmax, qmaxf);
+}
+
+__device__ __forceinline__ uint32_t requantize_i32(uint32_t c_u32, int col, const EpiParams& e,
                                                    uint32_t qmax, float qmaxf) {
+  if (e.col_a)
+    return requantize_affine(c_u32, e.col_a[col], e.col_b ? e.col_b[col] : 0.0f, e.relu, e.rq_lo,
+                             e.rq_inv_scale, qmax, qmaxf);
   return requantize_code(c_u32, e.relu, e.rq_lo, e.rq_inv_scale, qmax, qmaxf);
 }
 
@@ -153,6 +169,7 @@ __device__ __forceinline__ float dequantize_f64_ri(uint32_t c_u32, double ri, in
   const double l0 = e.l0a + e.l0b * rl;
   const double t2 = l0 * (e.ck + e.cs * ci);
   double v = t1 + t2;
+  if (e.col_a) v = v * (double)e.col_a[col] + (e.col_b ? (double)e.col_b[col] : 0.0);
   if (e.relu && v < 0.0) v = 0.0;
   return (float)v;
 }

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void update_kernel(const UpdParams p) {
     } else {
       // RIGHT layout for the next aggregation: 32 consecutive rows per word, so a
       // ballot over the lanes is two finished words of column h.
-      const uint32_t q = row_ok ? requantize_i32(z, e, qmax, qmaxf) : 0u;
+      const uint32_t q = row_ok ? requantize_i32(z, h, e, qmax, qmaxf) : 0u;
       if (fast_bits) {
         // keep them in lane (h - h_begin) until the whole column run is done
         uint32_t lo[B], hi[B];

@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int row = row0 + mt * 16 + g * 4 + r;
-          const uint32_t q = (col_ok && row < p.rows) ? requantize_i32(z[mt][r], e, qmax, qmaxf) : 0u;
+          const uint32_t q = (col_ok && row < p.rows) ? requantize_i32(z[mt][r], min(col, p.cols - 1), e, qmax, qmaxf) : 0u;
           const int bit = mt * 16 + g * 4 + r;
 #pragma unroll
           for (int i = 0; i < 8; ++i) part[i] |= ((q >> i) & 1u) << bit;

@@ -21,7 +21,19 @@ def inv_scale(lo: float, hi: float, nbits: int) -> float:
 @dataclass
 class LayerRanges:
     agg_hi: int          # requantization range [0, agg_hi) of the aggregation result
-    out_hi: int | None   # range [0, out_hi) of the update result (hidden layers)
+    out_hi: float | None # range [0, out_hi) of the update result (hidden layers): in units of
+                         # the accumulator, or of the real value behind a batch normalization
+
+
+@dataclass
+class BatchNorm:
+    """Inference-time batch normalization after a layer (Section 4.5): per output
+    column gamma, beta and the running mean / variance, as sequences of floats."""
+    gamma: object
+    beta: object
+    mean: object
+    var: object
+    eps: float = 1e-5
 
 
 def fused_layer_applies(d: int, h: int, s: int, t: int) -> bool:
@@ -40,8 +52,14 @@ class QuantGNN:
 
     def __init__(self, A_src, Ws, s: int, t: int, self_term: bool,
                  tile_kbits: int = 128, use_map: bool = True, block_rows: int = 0,
-                 weights_as_bytes: bool = True, update_first: bool = False):
+                 weights_as_bytes: bool = True, update_first: bool = False, batchnorm=None):
         self.s, self.t = s, t
+        # batchnorm: per layer None or a BatchNorm; it is folded into the layer's output
+        # epilogue as a per-column affine map (no kernel of its own)
+        self.batchnorm = list(batchnorm) if batchnorm is not None else [None] * len(Ws)
+        assert len(self.batchnorm) == len(Ws)
+        assert not (update_first and any(b is not None for b in self.batchnorm))
+        self._bn_cache = {}
         # update_first: every layer computes A.(X.W) instead of (A.X).W (Section 6.1: GIN
         # updates before it aggregates); it runs as qgtc_update + qgtc_aggregate on planes
         self.update_first = update_first
@@ -242,6 +260,28 @@ class QuantGNN:
                                   out=self._xl_view((l + 1) & 1, h))
             scale = scale / inv_z
 
+    def _bn_fold(self, l: int, value_scale: float):
+        """(col_scale, col_shift) of layer l's batch normalization acting on value_scale * C:
+        a_j = gamma_j / sqrt(var_j + eps), col_scale = a_j * value_scale, col_shift =
+        beta_j - a_j * mean_j, formed in fp64 and rounded once to fp32.  Cached per scale so
+        that a recorded pass allocates nothing."""
+        key = (l, float(value_scale))
+        if key not in self._bn_cache:
+            import numpy as np
+            bn = self.batchnorm[l]
+            g = np.asarray(bn.gamma, dtype=np.float64) / np.sqrt(np.asarray(bn.var, dtype=np.float64) + float(bn.eps))
+            a = (g * float(value_scale)).astype(np.float32)
+            b = (np.asarray(bn.beta, dtype=np.float64) - g * np.asarray(bn.mean, dtype=np.float64)).astype(np.float32)
+            dv = self.A.words.device
+            self._bn_cache[key] = (torch.from_numpy(a).to(dv), torch.from_numpy(b).to(dv))
+        return self._bn_cache[key]
+
+    def _z_scale(self, l: int, x_scale: float, agg_hi) -> float:
+        """Real value of one unit of layer l's update accumulator (codes read as pure scales)."""
+        lo_w, hi_w = self.w_ranges[l]
+        sw = (hi_w - lo_w) / float(2 ** self.t)
+        return (x_scale / inv_scale(0.0, float(agg_hi), self.s)) * sw
+
     # -- calibration: integer maxima per layer, from int32 outputs ---------------------
     def calibrate(self, X: torch.Tensor, x_range):
         """Runs the stack once with int32 outputs and returns LayerRanges per
@@ -253,6 +293,7 @@ class QuantGNN:
         if self._W_planes is None:          # qgtc_update reads bit planes
             self._W_planes = [B.qgtc_pack_bits(W, self.t, B.RIGHT, quant=r)
                               for W, r in zip(self.Ws, self.w_ranges)]
+        x_scale = (float(x_range[1]) - float(x_range[0])) / float(2 ** self.s)
         for l, W in enumerate(self._W_planes):
             y32 = B.qgtc_aggregate(self.A, self.map, xb,
                                    B.Epilogue(mode=B.OUT_I32, self_term=self.self_term))
@@ -260,12 +301,23 @@ class QuantGNN:
             yb = B.qgtc_aggregate(self.A, self.map, xb, self._agg_ep(agg_hi))
             z32 = B.qgtc_update(yb, W, B.Epilogue(mode=B.OUT_I32))
             last = l == len(self.W) - 1
-            out_hi = None if last else max(1, int(z32.max()))
+            if last:
+                ranges.append(LayerRanges(agg_hi, None))
+                break
+            ep = B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0)
+            if self.batchnorm[l] is not None:
+                # range of the normalized value, [0, max(a_j * z + b_j)]
+                ca, cb = self._bn_fold(l, self._z_scale(l, x_scale, agg_hi))
+                v = z32.to(torch.float64) * ca.to(torch.float64)[None, :] + cb.to(torch.float64)[None, :]
+                out_hi = max(1e-6, float(v.max()))
+                ep.col_scale, ep.col_shift = ca, cb
+                x_scale = 1.0 / inv_scale(0.0, out_hi, self.s)
+            else:
+                out_hi = max(1, int(z32.max()))
+                x_scale = self._z_scale(l, x_scale, agg_hi) / inv_scale(0.0, float(out_hi), self.s)
             ranges.append(LayerRanges(agg_hi, out_hi))
-            if not last:
-                ep = B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0,
-                                rq_inv_scale=inv_scale(0.0, float(out_hi), self.s))
-                xb = B.qgtc_update(yb, W, ep, out=self._x_view((l + 1) & 1, self.dims[l][1]))
+            ep.rq_inv_scale = inv_scale(0.0, float(out_hi), self.s)
+            xb = B.qgtc_update(yb, W, ep, out=self._x_view((l + 1) & 1, self.dims[l][1]))
         return ranges
 
     # -- forward ---------------------------------------------------------------------
@@ -359,13 +411,15 @@ class QuantGNN:
             if l < n_layers - 1:
                 ep = B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0,
                                 rq_inv_scale=inv_scale(0.0, float(r.out_hi), self.s))
+                # hidden activations are read as pure scales: x^ = Xq * step
+                z_scale = self._z_scale(l, x_scale, r.agg_hi)
+                if self.batchnorm[l] is not None:
+                    ep.col_scale, ep.col_shift = self._bn_fold(l, z_scale)
+                    x_scale = 1.0 / inv_scale(0.0, float(r.out_hi), self.s)
+                else:
+                    x_scale = z_scale / inv_scale(0.0, float(r.out_hi), self.s)
                 xb = B.qgtc_layer(A, tmap, xb, W, agg_ep, ep, workspace,
                                   out=self._x_rows((l + 1) & 1, self.dims[l][1], r0, r1))
-                # hidden activations are read as pure scales: x^ = Xq * step
-                lo_w, hi_w = self.w_ranges[l]
-                sw = (hi_w - lo_w) / float(2 ** self.t)
-                x_scale = (x_scale / inv_scale(0.0, float(r.agg_hi), self.s)) * sw \
-                    / inv_scale(0.0, float(r.out_hi), self.s)
                 x_lo = 0.0
             elif want_int:
                 B.qgtc_layer(A, tmap, xb, W, agg_ep, B.Epilogue(mode=B.OUT_I32), workspace, out=out)
@@ -373,4 +427,6 @@ class QuantGNN:
                 # row_i = None: the layer takes the row sums of its own requantized Y
                 ep = self.last_layer_dequant(l, x_lo, x_scale, r.agg_hi, None)
                 ep.row_l = deg
+                if self.batchnorm[l] is not None:      # acts on the real output value
+                    ep.col_scale, ep.col_shift = self._bn_fold(l, 1.0)
                 B.qgtc_layer(A, tmap, xb, W, agg_ep, ep, workspace, out=out)

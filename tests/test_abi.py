@@ -125,6 +125,19 @@ def test_argument_validation_happens_before_any_launch():
     W9 = _fake_bits(b, 64, 8, 9, b.RIGHT)
     assert l.qgtc_update(C.byref(Yby), C.byref(W9), C.byref(ep), out, 8, None) == 7
     assert l.qgtc_aggregate(C.byref(Yby), None, C.byref(X), C.byref(ep), out, 16, None) == 5
+    # per-column affine map: not for int32 outputs, a shift needs a scale, and in
+    # qgtc_layer it belongs to the update's epilogue
+    epa = b.Epilogue(mode=b.OUT_I32).to_c()
+    epa.col_scale = 0x60000
+    assert l.qgtc_aggregate(C.byref(A), None, C.byref(X), C.byref(epa), out, 16, None) == 7
+    assert l.qgtc_update(C.byref(Y), C.byref(_fake_bits(b, 32, 8, 3, b.RIGHT)), C.byref(epa), out, 8, None) == 7
+    epa = b.Epilogue(mode=b.OUT_F32, cc=1.0).to_c()
+    epa.col_shift = 0x60000
+    assert l.qgtc_aggregate(C.byref(A), None, C.byref(X), C.byref(epa), out, 16, None) == 1
+    epb2 = b.Epilogue(mode=b.OUT_BITS, rq_nbits=2, rq_inv_scale=1.0).to_c()
+    epb2.col_scale = 0x60000
+    assert l.qgtc_layer(C.byref(A), None, C.byref(X), C.byref(W2), C.byref(epb2), C.byref(ep),
+                        C.c_void_p(0x30000), 1 << 20, out, 8, None) == 7
     # pack: fp32 source needs a quantizer with hi > lo
     D = _fake_bits(b, 64, 16, 2, b.RIGHT)
     assert l.qgtc_pack_bits(C.c_void_p(0x40000), 0, 64, 16, 16, None, C.byref(D), None) == 1

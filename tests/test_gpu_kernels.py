@@ -503,6 +503,91 @@ def test_fused_layer_all_outputs(shape, st):
         q.qgtc_set_option(q.OPT_LAYER_KSPLIT, 0)
 
 
+# ------------------------------------------------- folded batch normalization
+@pytest.mark.parametrize("shape", [(200, 24, 40), (330, 70, 16), (257, 128, 100), (96, 512, 16), (64, 64, 64)])
+@pytest.mark.parametrize("st", [(8, 8), (4, 4), (3, 5), (11, 11)])
+def test_column_affine_epilogue(shape, st):
+    """A per-column affine map in front of the activation (a batch normalization folded
+    into the kernel): low-bit and fp32 outputs of qgtc_aggregate, of both update kernels
+    and of qgtc_layer as one and as two kernels, against the oracle."""
+    n, d, h = shape
+    s, t = st
+    rng = np.random.default_rng([29, n, d, h, s, t])
+    block = 96 if n % 2 == 0 else 0
+    A, Xq, Wq = _layer_case(rng, n, d, h, s, t, block, False)
+    Y = qgnn.aggregate(A, Xq)
+    rq_bits = min(s, 8)
+    y_inv = qgnn.inv_scale(0.0, float(max(1, qgnn.as_signed(Y).max())), rq_bits)
+    Yq = qgnn.requantize(Y, 0, y_inv, rq_bits)
+    Z = qgnn.update(Yq, Wq)
+    out_bits = min(s, 8)
+
+    def bn_params(C, cols, value_scale):
+        x = value_scale * qgnn.as_signed(C).astype(np.float64)
+        gamma = rng.uniform(0.5, 2.0, size=cols)
+        beta = rng.uniform(-1.0, 1.0, size=cols)
+        return qgnn.fold_batchnorm(gamma, beta, x.mean(axis=0), x.var(axis=0) + 1e-3, 1e-5, value_scale), \
+            qgnn.fold_batchnorm(gamma, beta, x.mean(axis=0), x.var(axis=0) + 1e-3, 1e-5, 1.0)
+
+    Ab = pack_adjacency(A)
+    m = q.qgtc_build_tile_map(Ab, 16, 128)
+    Xb = q.qgtc_pack_bits(dev(Xq.view(np.int32)), s, q.RIGHT)
+
+    # aggregation: codes along the columns (LEFT) and fp32
+    (a, b), (a1, b1) = bn_params(Y, d, 2.0e-3)
+    v = qgnn.as_signed(Y) * a[None, :].astype(np.float64) + b[None, :]
+    inv = qgnn.inv_scale(0.0, float(max(1e-3, v.max())), out_bits)
+    want = qgnn.requantize_affine(Y, a, b, 0, inv, out_bits, relu=True)
+    ep = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=out_bits, rq_lo=0, rq_inv_scale=float(inv),
+                    col_scale=dev(a), col_shift=dev(b))
+    got = q.qgtc_aggregate(Ab, m, Xb, ep)
+    assert (words_np(got) == bp.pack(want, out_bits, bp.LEFT)).all()
+    ep = q.Epilogue(mode=q.OUT_F32, cc=2.0e-3, relu=True, col_scale=dev(a1), col_shift=dev(b1))
+    got = q.qgtc_aggregate(Ab, m, Xb, ep).cpu().numpy()
+    ref = qgnn.dequantize(Y, cc=2.0e-3, relu=True, col_a=a1, col_b=b1)
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+
+    # update and layer: codes along the rows (RIGHT) and fp32; the shift may be absent
+    (a, b), (a1, b1) = bn_params(Z, h, 1.0e-4)
+    v = qgnn.as_signed(Z) * a[None, :].astype(np.float64) + b[None, :]
+    inv = qgnn.inv_scale(0.0, float(max(1e-3, v.max())), out_bits)
+    want_bits = bp.pack(qgnn.requantize_affine(Z, a, b, 0, inv, out_bits, relu=True), out_bits, bp.RIGHT)
+    want_noshift = bp.pack(qgnn.requantize_affine(Z, a, None, 0, inv, out_bits, relu=False), out_bits, bp.RIGHT)
+    rs = Yq.sum(axis=1, dtype=np.int64)
+    kw = dict(cc=1.0e-4, rs=-2.0e-3)
+    want_f32 = qgnn.dequantize(Z, row_i=rs, relu=True, col_a=a1, col_b=b1, **kw)
+    ep_bits = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=out_bits, rq_lo=0, rq_inv_scale=float(inv),
+                         col_scale=dev(a), col_shift=dev(b))
+    ep_noshift = q.Epilogue(mode=q.OUT_BITS, rq_nbits=out_bits, rq_lo=0, rq_inv_scale=float(inv),
+                            col_scale=dev(a))
+    Yb = q.qgtc_pack_bits(dev(Yq.view(np.int32)), rq_bits, q.LEFT)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    try:
+        for path in (q.UPDATE_POPCOUNT, q.UPDATE_MATRIX_CORES):
+            q.qgtc_set_option(q.OPT_UPDATE_PATH, path)
+            assert (words_np(q.qgtc_update(Yb, Wb, ep_bits)) == want_bits).all(), path
+            assert (words_np(q.qgtc_update(Yb, Wb, ep_noshift)) == want_noshift).all(), path
+            ep = q.Epilogue(mode=q.OUT_F32, row_i=dev(rs.astype(np.int32)), relu=True,
+                            col_scale=dev(a1), col_shift=dev(b1), **kw)
+            got = q.qgtc_update(Yb, Wb, ep).cpu().numpy()
+            assert np.allclose(got, want_f32, rtol=1e-6, atol=1e-6 * np.abs(want_f32).max()), path
+    finally:
+        q.qgtc_set_option(q.OPT_UPDATE_PATH, q.UPDATE_AUTO)
+    agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=rq_bits, rq_lo=0, rq_inv_scale=float(y_inv))
+    try:
+        for path in (q.LAYER_FUSED, q.LAYER_TWO_KERNELS):
+            q.qgtc_set_option(q.OPT_LAYER_PATH, path)
+            dst = q.alloc_bits(n, h, out_bits, q.RIGHT)
+            dst.words.fill_(-1)
+            assert (words_np(q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep_bits, out=dst)) == want_bits).all(), path
+            assert (words_np(q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep_noshift)) == want_noshift).all(), path
+            ep = q.Epilogue(mode=q.OUT_F32, row_i=None, relu=True, col_scale=dev(a1), col_shift=dev(b1), **kw)
+            got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep).cpu().numpy()
+            assert np.allclose(got, want_f32, rtol=1e-6, atol=1e-6 * np.abs(want_f32).max()), path
+    finally:
+        q.qgtc_set_option(q.OPT_LAYER_PATH, q.LAYER_FUSED)
+
+
 @pytest.mark.parametrize("st", [(1, 1), (2, 3), (4, 4), (7, 7), (8, 8), (8, 2), (3, 8), (8, 7)])
 @pytest.mark.parametrize("shape", [(100, 64, 64), (257, 128, 16), (70, 40, 5), (1000, 512, 16), (64, 300, 70),
                                    (4096, 64, 64), (33, 16, 130)])
