@@ -140,6 +140,22 @@ qgtc_status qgtc_pack_bits(const void* src, int32_t src_dtype, int32_t rows,
                            int32_t cols, int64_t ld_src, const qgtc_quant* q,
                            const qgtc_bits* dst, void* stream);
 
+/* Bandwidth-optimized subgraph packing (Section 4.6): the same packing on the CPU,
+ * so that a batch crosses the host-device link as low-bit planes in one transfer.
+ * src and dst->data are HOST memory; dst is a LEFT or RIGHT descriptor (others:
+ * QGTC_ERR_UNSUPPORTED).  Same arguments, checks and arithmetic as qgtc_pack_bits,
+ * and the same words in dst.  threads: worker threads to use (0: one per hardware
+ * thread).  Synchronous; never touches the GPU. */
+qgtc_status qgtc_pack_bits_host(const void* src, int32_t src_dtype, int32_t rows,
+                                int32_t cols, int64_t ld_src, const qgtc_quant* q,
+                                const qgtc_bits* dst, int32_t threads);
+/* Places n objects of bytes[i] bytes one after the other in one buffer, each at a
+ * multiple of 256 bytes: writes their offsets and returns the size of the buffer
+ * (the "compound memory object" of Section 4.6: allocate it once in pinned host
+ * memory and once on the device, point the descriptors of the packed adjacency and
+ * features into it, pack on the host, copy once).  Host-only. */
+size_t qgtc_compound_layout(const size_t* bytes, int32_t n, size_t* offsets);
+
 /* Decode a packed matrix (any layout) back to one uint32 per entry
  * ("Tensor.to_val", Section 5).  dst: device, row-major rows x cols, leading
  * dimension ld_dst. */

@@ -81,6 +81,8 @@ def lib():
         "qgtc_describe": (sz, [P(_BitsC), i32, i32, i32, i32, i32]),
         "qgtc_pack_bits": (C.c_int, [vp, i32, i32, i32, i64, P(_QuantC), P(_BitsC), vp]),
         "qgtc_unpack_bits": (C.c_int, [P(_BitsC), vp, i64, vp]),
+        "qgtc_pack_bits_host": (C.c_int, [vp, i32, i32, i32, i64, P(_QuantC), P(_BitsC), i32]),
+        "qgtc_compound_layout": (sz, [P(sz), i32, P(sz)]),
         "qgtc_row_sums": (C.c_int, [P(_BitsC), vp, vp]),
         "qgtc_col_sums": (C.c_int, [P(_BitsC), vp, vp]),
         "qgtc_tile_map_bytes": (sz, [i32, i32, i32, i32]),

@@ -335,21 +335,28 @@ class QuantGNN:
                           ck=lo_w * d, cs=sw, col_i=self.w_colsum[l])
 
     def forward(self, X: torch.Tensor, x_range, ranges, out: torch.Tensor | None = None,
-                want_int: bool = False, streams: int = 1, x_packed: bool = False):
+                want_int: bool = False, streams: int = 1, x_packed: bool = False,
+                x_bits: B.Bits | None = None):
         """fp32 [N, H_last] (or the last int32 accumulators when want_int).
 
         streams > 1 (block-diagonal storage): the subgraphs are cut into that many
         independent runs, each issued on a stream of its own, so that the start and the
         drain of one run's kernels overlap with the other runs' work.  A list gives the
         number of subgraphs of each run instead ([48, 16]: the first 48, then 16).
-        x_packed: the features are already packed (pack_static(X, x_range))."""
+        x_packed: the features are already packed (pack_static(X, x_range)).
+        x_bits: the features as packed planes that live elsewhere (a SubgraphPacket's,
+        packed on the host with the same x_range); X is then not read (single run only)."""
         n = self.A.rows
         if out is None:
             out = torch.empty((n, self.dims[-1][1]), dtype=torch.int32 if want_int else torch.float32,
                               device=self.A.words.device)
         if self.update_first:
             return self._forward_update_first(X, x_range, ranges, out, want_int)
-        xb = self._x_view(0, X.shape[1]) if x_packed else self.pack_input(X, x_range)
+        if x_bits is not None:
+            assert isinstance(streams, int) and streams <= 1
+            xb = x_bits
+        else:
+            xb = self._x_view(0, X.shape[1]) if x_packed else self.pack_input(X, x_range)
         if (isinstance(streams, int) and streams <= 1) or self.A.c.block_rows == 0:
             self._run_layers(0, n, self.A, self.map, self.deg, xb, x_range, ranges, out, want_int,
                              self.workspace)

@@ -7,7 +7,11 @@
   config5  the 2-layer GCN on the power-law graph for s = t in {1, 2, 4, 8}, with 128- and
            32-bit tiles, and in the update-first order A.(X.W)
 
-Run:  python -m paper_2111_09547_amd.sweeps [table3|config3|config5 ...]
+  transfer host -> device cost of a batch (Section 4.6): dense fp32 adjacency + fp32
+           features in two copies against the low-bit compound buffer packed on the host
+           and copied once (configs 4 and 5; pinned memory on both sides)
+
+Run:  python -m paper_2111_09547_amd.sweeps [table3|config3|config5|transfer ...]
 Prints one JSON line per measurement and a markdown table per sweep."""
 from __future__ import annotations
 
@@ -131,11 +135,54 @@ def config5():
     _model_sweep(5, (1, 2, 4, 8), kb=128, update_first=True)
 
 
+def transfer():
+    import time
+    from workloads import make_workload
+    from .packing import SubgraphPacket
+    rows = []
+    for cfg in (4, 5):
+        w = make_workload(cfg)
+        g = w.graph
+        a_u8 = torch.from_numpy(g.dense_compact())
+        x = torch.from_numpy(w.X)
+        xr = (float(w.X.min()), float(w.X.max()))
+        a_f32 = a_u8.to(torch.float32).pin_memory()
+        x_pin = x.pin_memory()
+        da, dx = torch.empty_like(a_f32, device="cuda"), torch.empty_like(x_pin, device="cuda")
+
+        def dense():
+            da.copy_(a_f32, non_blocking=True)
+            dx.copy_(x_pin, non_blocking=True)
+        t_dense = timeit(dense, n=3, warm=1, reps=3)
+        pk = SubgraphPacket(g.n_nodes, g.block, x.shape[1], w.s, block_rows=g.block)
+        t_pack = float("inf")
+        for _ in range(3):
+            t0 = time.perf_counter()
+            pk.pack(a_u8, x, xr, threads=16)
+            t_pack = min(t_pack, (time.perf_counter() - t0) * 1e6)
+        t_low = timeit(pk.upload, n=3, warm=1, reps=3)
+        dense_bytes = a_f32.numel() * 4 + x_pin.numel() * 4
+        rec = {"sweep": "transfer", "config": cfg, "dense_fp32_MiB": round(dense_bytes / 2 ** 20, 1),
+               "dense_us": round(t_dense, 1), "dense_GBps": round(dense_bytes / t_dense / 1e3, 1),
+               "packed_MiB": round(pk.nbytes / 2 ** 20, 1), "packed_copy_us": round(t_low, 1),
+               "packed_GBps": round(pk.nbytes / t_low / 1e3, 1), "host_pack_us_16_threads": round(t_pack, 1)}
+        print(json.dumps(rec), flush=True)
+        rows.append(rec)
+        del a_f32, x_pin, da, dx, pk
+        torch.cuda.empty_cache()
+    print("\n| config | dense fp32 A + X, two copies | packed A + X, one copy | host packing (16 threads) |")
+    print("|---|---|---|---|")
+    for r in rows:
+        print(f"| {r['config']} | {r['dense_fp32_MiB']} MiB, {r['dense_us']} us ({r['dense_GBps']} GB/s) | "
+              f"{r['packed_MiB']} MiB, {r['packed_copy_us']} us ({r['packed_GBps']} GB/s) | "
+              f"{r['host_pack_us_16_threads']} us |")
+
+
 def main():
     torch.cuda.set_device(0)
-    which = sys.argv[1:] or ["table3", "config3", "config5"]
+    which = sys.argv[1:] or ["table3", "config3", "config5", "transfer"]
     for name in which:
-        {"table3": table3, "config3": config3, "config5": config5}[name]()
+        {"table3": table3, "config3": config3, "config5": config5, "transfer": transfer}[name]()
 
 
 if __name__ == "__main__":

@@ -257,3 +257,34 @@ def test_batchnorm_folded_into_the_layers(cfg, nb, last_bn):
         graph.replay()
         torch.cuda.synchronize()
         assert np.array_equal(buf.cpu().numpy(), out)
+
+
+@pytest.mark.parametrize("cfg,nb", [(4, 2), (5, 4)])
+def test_host_packed_batch_in_one_transfer(cfg, nb):
+    """Section 4.6: adjacency and features packed on the host into one pinned buffer and
+    copied once give the words the device packing gives, and the same model output."""
+    from paper_2111_09547_amd.packing import SubgraphPacket
+    from gpu_util import words_np
+    w = make_workload(cfg, n_blocks=nb)
+    g = w.graph
+    self_term = w.model == "gin"
+    a_host = torch.from_numpy(g.dense_compact())
+    x_host = torch.from_numpy(w.X)
+    xr = (float(w.X.min()), float(w.X.max()))
+    pk = SubgraphPacket(g.n_nodes, g.block, w.X.shape[1], w.s, block_rows=g.block)
+    pk.pack(a_host, x_host, xr)
+    a_bits, x_bits = pk.upload()
+    ref_a = q.qgtc_pack_bits(a_host.cuda(), 1, q.LEFT, block_rows=g.block)
+    ref_x = q.qgtc_pack_bits(x_host.cuda(), w.s, q.RIGHT, quant=xr)
+    torch.cuda.synchronize()
+    assert (words_np(a_bits) == words_np(ref_a)).all()
+    assert (words_np(x_bits) == words_np(ref_x)).all()
+
+    Ws = [dev(W) for W in w.W]
+    ref_net = QuantGNN(dev(g.dense_compact()), Ws, w.s, w.t, self_term, block_rows=g.block)
+    ranges = ref_net.calibrate(dev(w.X), xr)
+    want = ref_net.forward(dev(w.X), xr, ranges)
+    net = QuantGNN(a_bits, Ws, w.s, w.t, self_term, block_rows=g.block)      # the packed adjacency as it is
+    got = net.forward(None, xr, ranges, x_bits=x_bits)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
