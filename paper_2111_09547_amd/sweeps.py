@@ -7,11 +7,16 @@
   config5  the 2-layer GCN on the power-law graph for s = t in {1, 2, 4, 8}, with 128- and
            32-bit tiles, and in the update-first order A.(X.W)
 
+  sizes    the 1-bit x 1-bit aggregation over N in {128 .. 32768} and D in {16 .. 1024}
+           (the paper's adjacency-matrix-size study, Fig. 9), every tile non-zero
+  reuse    the paper's tile-reuse study (Fig. 10): D = 1024, N in {1024 .. 8192}, X with 4,
+           8 and 16 bits, A read once for all planes (one launch) against once per plane
+           (s one-bit launches)
   transfer host -> device cost of a batch (Section 4.6): dense fp32 adjacency + fp32
            features in two copies against the low-bit compound buffer packed on the host
            and copied once (configs 4 and 5; pinned memory on both sides)
 
-Run:  python -m paper_2111_09547_amd.sweeps [table3|config3|config5|transfer ...]
+Run:  python -m paper_2111_09547_amd.sweeps [table3|config3|config5|sizes|reuse|transfer ...]
 Prints one JSON line per measurement and a markdown table per sweep."""
 from __future__ import annotations
 
@@ -135,6 +140,75 @@ def config5():
     _model_sweep(5, (1, 2, 4, 8), kb=128, update_first=True)
 
 
+def _random_bits(rows, cols, nbits, layout, gen):
+    """Packed operand of uniformly random bits (no dense source: N = 32768 would need 1 GiB)."""
+    b = q.alloc_bits(rows, cols, nbits, layout)
+    b.words.copy_(torch.randint(-2 ** 31, 2 ** 31 - 1, b.words.shape, dtype=torch.int64, device="cuda",
+                                generator=gen).to(torch.int32))
+    if layout == q.LEFT and cols % 32:              # padding bits of the last word stay zero
+        raise ValueError("columns must fill whole words")
+    return b
+
+
+def sizes():
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    ns = (128, 256, 512, 1024, 2048, 4096, 8192, 16384, 32768)
+    ds = (16, 32, 64, 128, 256, 512, 1024)
+    table = {}
+    for n in ns:
+        ab = _random_bits(n, n, 1, q.LEFT, gen)
+        tmap = q.qgtc_build_tile_map(ab, 16, 128)
+        for d in ds:
+            xb = _random_bits(n, d, 1, q.RIGHT, gen)
+            ep = q.Epilogue(mode=q.OUT_I32)
+            out = q.qgtc_aggregate(ab, tmap, xb, ep)
+            t = timeit(lambda: q.qgtc_aggregate(ab, tmap, xb, ep, out=out), n=10 if n >= 8192 else 20)
+            rec = {"sweep": "sizes", "N": n, "D": d, "us": round(t, 2),
+                   "tflops_equiv": round(2.0 * n * n * d / t / 1e6, 1),
+                   "frac_valu": round(2.0 * n * n * d / (t * 1e-6) / PEAK_BITOPS, 3)}
+            print(json.dumps(rec), flush=True)
+            table[(n, d)] = rec
+            del xb, out
+        del ab, tmap
+        torch.cuda.empty_cache()
+    print("\n1-bit x 1-bit aggregation, TFLOP/s-equivalent = 2 N^2 D / t (fraction of the vector-ALU ceiling):")
+    print("\n| N \\ D | " + " | ".join(str(d) for d in ds) + " |")
+    print("|---|" + "---|" * len(ds))
+    for n in ns:
+        print(f"| {n} | " + " | ".join(f"{table[(n, d)]['tflops_equiv']} ({table[(n, d)]['frac_valu']})" for d in ds) + " |")
+
+
+def reuse():
+    gen = torch.Generator(device="cuda").manual_seed(10)
+    d = 1024
+    rows = []
+    for n in (1024, 2048, 4096, 8192):
+        ab = _random_bits(n, n, 1, q.LEFT, gen)
+        tmap = q.qgtc_build_tile_map(ab, 16, 128)
+        ep = q.Epilogue(mode=q.OUT_I32)
+        x1 = _random_bits(n, d, 1, q.RIGHT, gen)
+        out = q.qgtc_aggregate(ab, tmap, x1, ep)
+        t1 = timeit(lambda: q.qgtc_aggregate(ab, tmap, x1, ep, out=out), n=10)
+        rec = {"sweep": "reuse", "N": n, "D": d, "us_1bit": round(t1, 1)}
+        for s_bits in (4, 8, 16):
+            xs = _random_bits(n, d, s_bits, q.RIGHT, gen)
+            ts = timeit(lambda: q.qgtc_aggregate(ab, tmap, xs, ep, out=out), n=10)
+            rec[f"us_{s_bits}bit_one_launch"] = round(ts, 1)
+            rec[f"us_{s_bits}bit_plane_by_plane"] = round(s_bits * t1, 1)
+            rec[f"tflops_equiv_{s_bits}bit"] = round(2.0 * n * n * d / ts / 1e6, 1)
+            del xs
+        print(json.dumps(rec), flush=True)
+        rows.append(rec)
+        del ab, tmap, x1, out
+        torch.cuda.empty_cache()
+    print("\nA read once for all planes (one launch) against once per plane (s launches of the 1-bit kernel), us:")
+    print("\n| N | 4 bit: one launch / per plane | 8 bit | 16 bit |")
+    print("|---|---|---|---|")
+    for r in rows:
+        print(f"| {r['N']} | " + " | ".join(f"{r[f'us_{b}bit_one_launch']} / {r[f'us_{b}bit_plane_by_plane']}"
+                                             for b in (4, 8, 16)) + " |")
+
+
 def transfer():
     import time
     from workloads import make_workload
@@ -180,9 +254,10 @@ def transfer():
 
 def main():
     torch.cuda.set_device(0)
-    which = sys.argv[1:] or ["table3", "config3", "config5", "transfer"]
+    which = sys.argv[1:] or ["table3", "config3", "config5", "sizes", "reuse", "transfer"]
     for name in which:
-        {"table3": table3, "config3": config3, "config5": config5, "transfer": transfer}[name]()
+        {"table3": table3, "config3": config3, "config5": config5, "sizes": sizes, "reuse": reuse,
+         "transfer": transfer}[name]()
 
 
 if __name__ == "__main__":
