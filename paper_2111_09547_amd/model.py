@@ -36,6 +36,28 @@ class BatchNorm:
     eps: float = 1e-5
 
 
+# Relative cost of one adjacency bit column by tile width (measured on configs 4 and 5: 64-bit
+# tiles cost what 128-bit tiles cost per bit, 32-bit tiles 1.0-1.4 times as much)
+TILE_COST = {128: 1.0, 64: 1.0, 32: 1.3}
+
+
+def choose_tile_kbits(A: "B.Bits") -> int:
+    """Tile width for the zero-tile map of a packed adjacency: the one with the least
+    executed work, non-zero tiles x tile width x TILE_COST; within 2 % the wider tile wins.
+    Narrow tiles skip more zeros (the paper's second kind of zero tiles, gaps inside a
+    subgraph, Section 6.3) but cost more per bit.  Builds the three maps and reads their
+    tile counts back (synchronizes)."""
+    cost = {}
+    for kb in (128, 64, 32):
+        m = B.qgtc_build_tile_map(A, 16, kb)
+        cost[kb] = int(m.nnz_tiles[0].item()) * kb * TILE_COST[kb]
+    best = 128
+    for kb in (64, 32):
+        if cost[kb] < 0.98 * cost[best]:
+            best = kb
+    return best
+
+
 def fused_layer_applies(d: int, h: int, s: int, t: int) -> bool:
     """The shapes and bit widths qgtc_layer runs as one kernel (see qgtc.h)."""
     return 1 <= d <= 1024 and 1 <= h <= 256 and s <= 8 and t <= 8
@@ -51,7 +73,7 @@ class QuantGNN:
     """
 
     def __init__(self, A_src, Ws, s: int, t: int, self_term: bool,
-                 tile_kbits: int = 128, use_map: bool = True, block_rows: int = 0,
+                 tile_kbits: int | str = 128, use_map: bool = True, block_rows: int = 0,
                  weights_as_bytes: bool = True, update_first: bool = False, batchnorm=None):
         self.s, self.t = s, t
         # batchnorm: per layer None or a BatchNorm; it is folded into the layer's output
@@ -77,6 +99,10 @@ class QuantGNN:
             self.A_src = A_src
             self.A = B.alloc_bits(A_src.shape[0], A_src.shape[1], 1, B.LEFT, block_rows)
         self.map = None
+        if tile_kbits == "auto":            # needs the packed adjacency: pack it now, choose once
+            if self.A_src is not None:
+                B.qgtc_pack_bits(self.A_src, 1, B.LEFT, out=self.A)
+            self.tile_kbits = choose_tile_kbits(self.A)
         # Weights are cached in the form their layer's kernel reads: bytes in
         # matrix-core operand order where the fused layer kernel applies, bit planes
         # for the two-kernel path.

@@ -288,3 +288,23 @@ def test_host_packed_batch_in_one_transfer(cfg, nb):
     got = net.forward(None, xr, ranges, x_bits=x_bits)
     torch.cuda.synchronize()
     assert torch.equal(got, want)
+
+
+def test_tile_width_is_chosen_from_the_zero_tile_maps():
+    """tile_kbits="auto": dense subgraphs keep 128-bit tiles, the power-law graph (gaps inside
+    the subgraphs) gets 32-bit tiles; the output does not depend on the choice."""
+    from paper_2111_09547_amd.model import choose_tile_kbits
+    for cfg, nb, want in ((4, 2, 128), (5, 8, 32)):
+        w = make_workload(cfg, n_blocks=nb)
+        g = w.graph
+        Ws = [dev(W) for W in w.W]
+        auto = QuantGNN(dev(g.dense_compact()), Ws, w.s, w.t, w.model == "gin", tile_kbits="auto",
+                        block_rows=g.block)
+        assert auto.tile_kbits == want == choose_tile_kbits(auto.A)
+        assert auto.map.c.tile_kbits == want
+        ref = QuantGNN(dev(g.dense_compact()), Ws, w.s, w.t, w.model == "gin", tile_kbits=128,
+                       block_rows=g.block)
+        X = dev(w.X)
+        xr = (float(w.X.min()), float(w.X.max()))
+        ranges = ref.calibrate(X, xr)
+        assert torch.equal(auto.forward(X, xr, ranges), ref.forward(X, xr, ranges))
