@@ -5,6 +5,8 @@
 
 #include "qgtc_internal.h"
 
+#include <cmath>
+
 namespace qgtc {
 
 int64_t span_words(const qgtc_bits* b) {
@@ -93,7 +95,7 @@ qgtc_status make_epilogue(const qgtc_epilogue* ep, void* out, int64_t ld_out, in
     if (d->rows != rows || d->cols != cols) return QGTC_ERR_SHAPE;
     if (ep->rq_nbits < 1 || ep->rq_nbits > 32 || d->nbits != ep->rq_nbits) return QGTC_ERR_BITWIDTH;
     if (d->block_rows != 0) return QGTC_ERR_LAYOUT;
-    if (!(ep->rq_inv_scale > 0.0f)) return QGTC_ERR_SHAPE;
+    if (!(ep->rq_inv_scale > 0.0f) || !(ep->rq_inv_scale < INFINITY)) return QGTC_ERR_SHAPE;   // finite, positive
     p->out = d->data;
     p->ld_out = d->ld_words;
     p->ps_out = d->plane_stride_words;

@@ -25,6 +25,8 @@
 //      (32 nodes per word, so a 16-row tile owns half a word).
 #include "qgtc_internal.h"
 
+#include <cmath>
+
 namespace qgtc {
 namespace {
 
@@ -208,16 +210,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
     }
 
     {
-      const int relu = k2->a.ep.relu;
+      const int32_t relu_floor = k2->a.ep.relu ? 0 : (int32_t)0x80000000;
       const int32_t rq_lo = k2->a.ep.rq_lo;
       const float rq_inv = k2->a.ep.rq_inv_scale;
-      const uint32_t qmax = (1u << k2->a.ep.rq_nbits) - 1u;   // at most 8 bits here
-      const float qmaxf = (float)qmax;
+      const float qmaxf = (float)((1u << k2->a.ep.rq_nbits) - 1u);   // at most 8 bits here
       const int ys = k2->ys;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         if ((j & km2) != kpart2) continue;
-        uint32_t q = requantize_code(y[j], relu, rq_lo, rq_inv, qmax, qmaxf);
+        uint32_t q = requantize_code_small(y[j], relu_floor, rq_lo, rq_inv, qmaxf);
         q = (c_ok && j < rows_left) ? q : 0u;
         if (cg_ok) yb[j * ys + cg * 64 + lane] = (uint8_t)q;   // zeros from the lanes past the last column
       }
@@ -348,7 +349,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void l
       } else {
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-          uint32_t q = requantize_code(zz[j], relu, rq_lo, rq_inv, qmax, qmaxf);
+          uint32_t q = requantize_code_small(zz[j], relu ? 0 : (int32_t)0x80000000, rq_lo, rq_inv, qmaxf);
           q = (h_ok && j < valid_rows) ? q : 0u;
           b[j >> 2] |= q << (8 * (j & 3));
         }
@@ -415,7 +416,7 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   if (A->rows < 1) return QGTC_OK;
   const bool w_bytes = W->layout == QGTC_RIGHT_BYTES;
   if (!w_bytes && workspace_bytes < layer_fused_workspace_bytes(X->cols, W->cols)) return QGTC_OK;
-  if (!(agg_ep->rq_inv_scale > 0.0f)) return QGTC_OK;
+  if (!(agg_ep->rq_inv_scale > 0.0f) || !(agg_ep->rq_inv_scale < INFINITY)) return QGTC_OK;
 
   LayerParams p{};
   if (agg_fill_params(A, map, X, &p.a) != QGTC_OK) return QGTC_OK;
