@@ -412,6 +412,17 @@ def test_update_from_bytes(st, shape):
 
 
 # ------------------------------------------------------------------- fused layer
+def _compact_rows(A, block):
+    """Block-diagonal storage: row r keeps the columns of its own diagonal block."""
+    n = A.shape[0]
+    out = np.zeros((n, block), dtype=np.uint8)
+    for r in range(n):
+        b0 = (r // block) * block
+        seg = A[r, b0:b0 + block]
+        out[r, :seg.size] = seg
+    return out
+
+
 def _layer_case(rng, n, d, h, s, t, block, self_term, p_edge=0.06):
     A = np.zeros((n, n), dtype=np.uint8)
     if block:
@@ -623,3 +634,51 @@ def test_update_matrix_core_path_equals_popcount_and_oracle(st, shape):
         assert (bits == bp.pack(qgnn.requantize(Z, 0, inv, 5, relu=True), 5, bp.RIGHT)).all(), path
         ref = qgnn.dequantize(Z, row_i=rs, row_l=rs, col_i=cs, **kw)
         assert np.allclose(f, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max()), path
+
+
+# ------------------------------------------------------------ seeded random shapes
+@pytest.mark.parametrize("seed", range(48))
+def test_layer_on_random_shapes(seed):
+    """qgtc_layer on shapes and bit widths drawn from a seeded generator (single rows and
+    columns, ragged tails, widths above 8 bits that leave the fused kernel, every storage
+    and tile width), int32 and low-bit outputs against the oracle."""
+    rng = np.random.default_rng([61, seed])
+    n = int(rng.choice([1, 2, 15, 16, 17, 31, 33, 64, 100, 129, 255, 400]))
+    d = int(rng.choice([1, 2, 7, 16, 17, 32, 33, 63, 64, 65, 130, 260]))
+    h = int(rng.choice([1, 3, 15, 16, 17, 40, 64, 100, 256, 260]))
+    s = int(rng.choice([1, 2, 3, 5, 8, 8, 8, 9, 12]))
+    t = int(rng.choice([1, 2, 4, 7, 8, 8, 10]))
+    block = int(rng.choice([0, 0, 32, 64, 96]))
+    kb = [None, 32, 64, 128][int(rng.integers(0, 4))]
+    self_term = bool(rng.integers(0, 2))
+    A, Xq, Wq = _layer_case(rng, n, d, h, s, t, block, self_term, p_edge=float(rng.choice([0.0, 0.02, 0.3])))
+    Y = qgnn.aggregate(A, Xq, self_term)
+    rq_bits = min(s, int(rng.choice([s, 8, 4])))
+    rq_inv = qgnn.inv_scale(0.0, float(max(1, qgnn.as_signed(Y).max())), rq_bits)
+    Yq = qgnn.requantize(Y, 0, rq_inv, rq_bits)
+    Z = qgnn.update(Yq, Wq)
+    out_bits = int(rng.choice([1, 3, 8, min(s, 8)]))
+    z_inv = qgnn.inv_scale(0.0, float(max(1, qgnn.as_signed(Z).max())), out_bits)
+    want_bits = bp.pack(qgnn.requantize(Z, 1, z_inv, out_bits, relu=True), out_bits, bp.RIGHT)
+
+    if block:
+        Ab = q.qgtc_pack_bits(dev(_compact_rows(A, block)), 1, q.LEFT, block_rows=block)
+    else:
+        Ab = pack_adjacency(A)
+    m = q.qgtc_build_tile_map(Ab, 16, kb) if kb else None
+    Xb = q.qgtc_pack_bits(dev(Xq.view(np.int32)), s, q.RIGHT)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=rq_bits, rq_lo=0, rq_inv_scale=float(rq_inv),
+                        self_term=self_term)
+    tag = dict(n=n, d=d, h=h, s=s, t=t, block=block, kb=kb, self_term=self_term, rq_bits=rq_bits, out_bits=out_bits)
+    got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32))
+    assert (as_u32(got) == Z).all(), tag
+    ep = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=out_bits, rq_lo=1, rq_inv_scale=float(z_inv))
+    dst = q.alloc_bits(n, h, out_bits, q.RIGHT)
+    dst.words.fill_(-1)
+    got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep, out=dst)
+    assert (words_np(got) == want_bits).all(), tag
+    if s <= 8 and t <= 8 and d <= 1024 and h <= 256:            # weights as bytes: the fused kernel only
+        Wby = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT_BYTES)
+        got = q.qgtc_layer(Ab, m, Xb, Wby, agg_ep, q.Epilogue(mode=q.OUT_I32))
+        assert (as_u32(got) == Z).all(), tag
