@@ -66,7 +66,7 @@ __device__ __forceinline__ void pack_rows_fast(const uint32_t (&q)[16], uint32_t
 
 // TW: words per tile (1, 2, 4); KS: K slices per wave (1, 2, 4; KS <= TW).
 template <int S, bool MULTI, int TW, int KS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void aggregate_kernel(const AggParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_per_simd(S)))) void aggregate_kernel(const AggParams p) {
   extern __shared__ uint32_t lds[];   // [ksplit][16][64] partial sums when ksplit > 1
 
   const unsigned bid = agg_logical_id(p);

@@ -97,7 +97,7 @@ typedef const __attribute__((address_space(4))) LayerParams* LateParams;
 #define QGTC_LATE(ptr) asm volatile("" : "+s"(ptr))
 
 template <int S, int TW, int KS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void layer_kernel(const LayerParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_per_simd(S)))) void layer_kernel(const LayerParams p) {
   extern __shared__ uint32_t lds[];
   const AggParams& a = p.a;
   int tr, n;                                         // tile row of this workgroup, its tile count
