@@ -99,6 +99,7 @@ typedef const __attribute__((address_space(4))) LayerParams* LateParams;
 template <int S, int TW, int KS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_per_simd(S)))) void layer_kernel(const LayerParams p) {
   extern __shared__ uint32_t lds[];
+  __builtin_amdgcn_s_setprio(2);
   const AggParams& a = p.a;
   int tr, n;                                         // tile row of this workgroup, its tile count
   if (!agg_pick_tile_row(a, &tr, &n)) return;        // whole workgroup leaves together
@@ -144,8 +145,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
 
     uint32_t acc[16][S];
     zero_acc<S>(acc);
+    // The tile loop runs at the lowest issue priority, everything around it (short chains
+    // of dependent loads, LDS traffic and matrix instructions) above it: those sections
+    // have few instructions, and the sooner they are through, the sooner the wave's slot
+    // takes the next tile row.
+    __builtin_amdgcn_s_setprio(0);
     if (cg_ok)
       agg_loop_uniform<S, TW, KS, false>(acc, a, ra, va_off, rx, xoff, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
+    __builtin_amdgcn_s_setprio(2);
     // shift-and-add of the per-plane popcounts (Algorithm 1, elementwise reduction)
     uint32_t y[16];
 #pragma unroll
