@@ -32,7 +32,7 @@ PEAK_BITOPS = VALU_LANE_OPS / 2 * 64          # 1.258e15 bit-op/s
 # HBM bytes per launch of the dominant kernel (read + write), from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarized under profiles/ (counters cannot be read
 # from inside this process); keyed by (config, bits).  None: not profiled.
-TRAFFIC = {(4, 8): 32.5e6}    # profiles/layer_kernel_bench_config4_hbm_traffic.md
+TRAFFIC = {(4, 8): 32.4e6}    # profiles/layer_kernel_bench_config4_hbm_traffic.md
 
 
 def workload_bitops(net, n_nodes, tile_kbits):
