@@ -119,7 +119,12 @@ void run_parallel(int n_items, int threads, F fn) {
   const int per = (n_items + threads - 1) / threads;
   for (int t = 0; t < threads; ++t) {
     const int a = t * per, b = std::min(n_items, a + per);
-    if (a < b) pool.emplace_back(fn, a, b);
+    if (a >= b) continue;
+    try {
+      pool.emplace_back(fn, a, b);
+    } catch (...) {                                  // no more threads to be had: do the range here
+      fn(a, b);
+    }
   }
   for (auto& th : pool) th.join();
 }
