@@ -682,3 +682,48 @@ def test_layer_on_random_shapes(seed):
         Wby = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT_BYTES)
         got = q.qgtc_layer(Ab, m, Xb, Wby, agg_ep, q.Epilogue(mode=q.OUT_I32))
         assert (as_u32(got) == Z).all(), tag
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_aggregate_and_update_on_random_shapes(seed):
+    """qgtc_aggregate and qgtc_update by themselves on seeded random shapes and bit widths
+    up to 32 (results modulo 2^32), every output mode, against the oracle."""
+    rng = np.random.default_rng([67, seed])
+    n = int(rng.choice([1, 5, 16, 31, 48, 65, 128, 200, 333]))
+    k = n
+    d = int(rng.choice([1, 3, 16, 20, 32, 50, 64, 70, 129, 300]))
+    h = int(rng.choice([1, 2, 15, 16, 33, 64, 90]))
+    s = int(rng.choice([1, 2, 4, 7, 8, 9, 13, 16, 24, 32]))
+    t = int(rng.choice([1, 3, 8, 8, 11, 16, 32]))
+    self_term = bool(rng.integers(0, 2))
+    kb = [None, 32, 64, 128][int(rng.integers(0, 4))]
+    A = rand_graph(rng, n, k, float(rng.choice([0.0, 0.05, 0.5])))
+    Xq = rng.integers(0, 2 ** s, size=(k, d), dtype=np.uint64).astype(np.uint32)
+    tag = dict(n=n, d=d, h=h, s=s, t=t, self_term=self_term, kb=kb)
+    Y = qgnn.aggregate(A, Xq, self_term)
+    Ab = pack_adjacency(A)
+    m = q.qgtc_build_tile_map(Ab, 16, kb) if kb else None
+    Xb = q.qgtc_pack_bits(dev(Xq.view(np.int32)), s, q.RIGHT)
+    got = q.qgtc_aggregate(Ab, m, Xb, q.Epilogue(mode=q.OUT_I32, self_term=self_term))
+    assert (as_u32(got) == Y).all(), tag
+    rq_bits = int(rng.choice([1, 4, 8, 12]))
+    hi = float(max(1, qgnn.as_signed(Y).max()))
+    inv = qgnn.inv_scale(0.0, hi, rq_bits)
+    Yq = qgnn.requantize(Y, 0, inv, rq_bits, relu=True)
+    ep = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=rq_bits, rq_lo=0, rq_inv_scale=float(inv),
+                    self_term=self_term)
+    Yb = q.qgtc_aggregate(Ab, m, Xb, ep)
+    assert (words_np(Yb) == bp.pack(Yq, rq_bits, bp.LEFT)).all(), tag
+    got = q.qgtc_aggregate(Ab, m, Xb, q.Epilogue(mode=q.OUT_F32, cc=0.013, self_term=self_term)).cpu().numpy()
+    ref = qgnn.dequantize(Y, cc=0.013)
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * max(1e-30, np.abs(ref).max())), tag
+
+    Wq = rng.integers(0, 2 ** t, size=(d, h), dtype=np.uint64).astype(np.uint32)
+    Z = qgnn.update(Yq, Wq)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    got = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_I32, relu=True))
+    assert (as_u32(got) == qgnn.int_output(Z, relu=True).view(np.uint32)).all(), tag
+    out_bits = int(rng.choice([1, 5, 8, 16]))
+    z_inv = qgnn.inv_scale(0.0, float(max(1, qgnn.as_signed(Z).max())), out_bits)
+    got = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_BITS, rq_nbits=out_bits, rq_lo=0, rq_inv_scale=float(z_inv)))
+    assert (words_np(got) == bp.pack(qgnn.requantize(Z, 0, z_inv, out_bits), out_bits, bp.RIGHT)).all(), tag
