@@ -312,6 +312,28 @@ qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map,
                        void* workspace, size_t workspace_bytes, void* out,
                        int64_t ld_out, void* stream);
 
+/* qgtc_layer for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * checks and results as qgtc_layer, without the workspace: the layer's intermediate
+ * data (see qgtc_layer) lives in a device array of QGTC_LAYER_STATIC_MAX_BYTES that
+ * is part of the library's code object; every GPU the process uses holds one copy
+ * until the process ends.  The call allocates and frees nothing (with the optional
+ * kernel timing below switched off, its default).
+ * Limit: QGTC_ERR_WORKSPACE when qgtc_layer_workspace_bytes(rows of A, columns of X,
+ * columns of W, agg_ep->rq_nbits) exceeds QGTC_LAYER_STATIC_MAX_BYTES.  The fused
+ * kernel (all operands <= 8 bits) needs at most 512 KiB and always fits; the
+ * two-kernel path needs rows * ceil(columns of X / 32) * rq_nbits * 4 + rows * 4
+ * bytes.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on the same
+ * GPU (different streams or threads) race; calls on one stream are ordered and safe.
+ * The address of the array is looked up on the first call on each device (with that
+ * device current, hipGetSymbolAddress) and kept. */
+#define QGTC_LAYER_STATIC_MAX_BYTES (16 * 1024 * 1024)
+qgtc_status qgtc_layer_static(const qgtc_bits* A, const qgtc_tile_map* map,
+                              const qgtc_bits* X, const qgtc_bits* W,
+                              const qgtc_epilogue* agg_ep, const qgtc_epilogue* upd_ep,
+                              void* out, int64_t ld_out, void* stream);
+
 /* ---------------------------------------------------------------------------
  * Optional per-kernel timing.  While enabled, every kernel launch is bracketed
  * by HIP events recorded on the launch stream.  qgtc_prof_read synchronizes

@@ -6,7 +6,7 @@ from .binding import (  # noqa: F401
     KERNEL_PACK, KERNEL_TILE_MAP, KERNEL_AGGREGATE, KERNEL_UPDATE, KERNEL_SUMS, KERNEL_LAYER,
     QgtcError, Bits, TileMap, Epilogue, lib, lib_path, describe, alloc_bits,
     qgtc_pack_bits, qgtc_unpack_bits, qgtc_build_tile_map, qgtc_aggregate,
-    qgtc_update, qgtc_layer, qgtc_row_sums, qgtc_col_sums,
+    qgtc_update, qgtc_layer, qgtc_layer_static, LAYER_STATIC_MAX_BYTES, qgtc_row_sums, qgtc_col_sums,
     qgtc_set_option, OPT_UPDATE_PATH, OPT_AGG_XCD_RUN, OPT_LAYER_PATH, OPT_LAYER_KSPLIT,
     LAYER_FUSED, LAYER_TWO_KERNELS, UPDATE_AUTO, UPDATE_POPCOUNT, UPDATE_MATRIX_CORES,
     qgtc_probe_popcount, qgtc_prof_enable, qgtc_prof_reset, qgtc_prof_read, qgtc_version,

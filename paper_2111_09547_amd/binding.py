@@ -93,6 +93,8 @@ def lib():
         "qgtc_layer_workspace_bytes": (sz, [i32, i32, i32, i32]),
         "qgtc_layer": (C.c_int, [P(_BitsC), P(_TileMapC), P(_BitsC), P(_BitsC), P(_EpilogueC),
                                  P(_EpilogueC), vp, sz, vp, i64, vp]),
+        "qgtc_layer_static": (C.c_int, [P(_BitsC), P(_TileMapC), P(_BitsC), P(_BitsC), P(_EpilogueC),
+                                        P(_EpilogueC), vp, i64, vp]),
         "qgtc_set_option": (C.c_int, [i32, i32]),
         "qgtc_probe_popcount": (C.c_int, [i32, i32, i32, C.c_void_p, C.c_void_p]),
         "qgtc_prof_enable": (C.c_int, [i32]),
@@ -317,6 +319,21 @@ def qgtc_layer(A: Bits, tmap: TileMap | None, X: Bits, W: Bits, agg_ep: Epilogue
     _check(lib().qgtc_layer(C.byref(A.c), m, C.byref(X.c), C.byref(W.c), C.byref(a), C.byref(u),
                             C.c_void_p(workspace.data_ptr()), workspace.numel() * 4, ptr, ld,
                             _stream()), "qgtc_layer")
+    return res
+
+
+LAYER_STATIC_MAX_BYTES = 16 * 1024 * 1024
+
+
+def qgtc_layer_static(A: Bits, tmap: TileMap | None, X: Bits, W: Bits, agg_ep: Epilogue,
+                      upd_ep: Epilogue, out=None):
+    """qgtc_layer without a workspace argument (the library's own static device array
+    serves); pass `out` to keep the whole call free of allocations."""
+    res, ptr, ld = _out_arg(upd_ep, A.rows, W.cols, out, RIGHT, X.words.device)
+    a, u = agg_ep.to_c(), upd_ep.to_c()
+    m = C.byref(tmap.c) if tmap is not None else None
+    _check(lib().qgtc_layer_static(C.byref(A.c), m, C.byref(X.c), C.byref(W.c), C.byref(a),
+                                   C.byref(u), ptr, ld, _stream()), "qgtc_layer_static")
     return res
 
 

@@ -308,6 +308,51 @@ extern "C" qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map, 
   return qgtc_update(&Y, W, &upd, out, ld_out, stream);
 }
 
+// ---- qgtc_layer for callers that cannot allocate -----------------------------------
+// The workspace of qgtc_layer (weights in operand order for the fused kernel; packed
+// planes of Y and their row sums for the two-kernel path) in device memory that comes
+// with the code object instead of from the caller.  Every GPU the library runs on holds
+// its own copy of the array, at its own address, until the process ends.
+static __device__ __align__(256) unsigned char scratch[QGTC_LAYER_STATIC_MAX_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` per device, set on first use
+
+// Device address of the current device's copy of `scratch` (the array's name is a
+// host-side handle only, never an address to hand to a kernel).
+qgtc_status scratch_address(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return QGTC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return QGTC_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return QGTC_OK;
+}
+}  // namespace
+
+extern "C" qgtc_status qgtc_layer_static(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc_bits* X,
+                                         const qgtc_bits* W, const qgtc_epilogue* agg_ep,
+                                         const qgtc_epilogue* upd_ep, void* out, int64_t ld_out,
+                                         void* stream) {
+  if (!A || !X || !W || !agg_ep || !upd_ep || !out) return QGTC_ERR_NULL;
+  if (agg_ep->rq_nbits < 1 || agg_ep->rq_nbits > 32) return QGTC_ERR_BITWIDTH;
+  const size_t need = qgtc_layer_workspace_bytes(A->rows, X->cols, W->cols, agg_ep->rq_nbits);
+  if (need == 0 || need > (size_t)QGTC_LAYER_STATIC_MAX_BYTES) return QGTC_ERR_WORKSPACE;
+  void* ws = nullptr;
+  qgtc_status st = scratch_address(&ws);
+  if (st != QGTC_OK) return st;
+  // every word of the workspace that a kernel of the layer reads has been written by an
+  // earlier kernel of the same call, so nothing needs clearing between calls
+  return qgtc_layer(A, map, X, W, agg_ep, upd_ep, ws, (size_t)QGTC_LAYER_STATIC_MAX_BYTES, out, ld_out,
+                    stream);
+}
+
 extern "C" qgtc_status qgtc_prof_enable(int32_t on) {
   std::lock_guard<std::mutex> lock(g_prof_mutex);
   g_prof_on = on != 0;
