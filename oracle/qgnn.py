@@ -288,7 +288,7 @@ def calibrate_requant_affine(c_u32, col_a, col_b, nbits: int):
 
 
 def forward(A, X, x_range, Ws, w_ranges, s: int, t: int, self_term: bool,
-            rqs=None, update_first: bool = False, affines=None):
+            rqs=None, update_first: bool = False, affines=None, batchnorms=None):
     """Multi-layer forward pass: every hidden layer ends in ReLU + requantize
     to s bits (the next layer's Xq); the last layer's integer result is
     returned as it is, together with everything needed to dequantize it.
@@ -299,29 +299,94 @@ def forward(A, X, x_range, Ws, w_ranges, s: int, t: int, self_term: bool,
     x_range / w_ranges are (lo, hi) pairs for Eq. (2).  rqs, when given, is a
     list of (agg_rq, out_rq) per layer; otherwise ranges are calibrated from the
     values met on the way and returned.  affines: per layer None or (col_a, col_b),
-    the per-column affine map in front of a hidden layer's ReLU."""
+    the per-column affine map in front of a hidden layer's ReLU.  batchnorms: per
+    layer None or a dict(gamma, beta, mean, var, eps); a hidden layer's entry is folded
+    into that layer's affine map here (fold_batchnorm with the real value of one unit
+    of the layer's accumulator), so give either affines or batchnorms for a layer.
+
+    Scales (the reading of low-bit activations between layers): the codes a hidden layer
+    emits are read as pure scales, value = x_scale * code with no zero point.  Each trace
+    entry carries "x_scale", the real value of one unit of its Xq, and "z_scale", the real
+    value of one unit of its accumulator Z under that reading:
+        aggregate first:  z_scale = (x_scale / inv_agg) * sw          (Yq = floor(Y * inv_agg))
+        update first:     z_scale = (x_scale * sw) / inv_p            (Pq = floor(P * inv_p))
+        next x_scale   =  z_scale / inv_out,  or 1 / inv_out behind a folded batch
+                          normalization (its codes quantize the normalized value itself)."""
     Xq = quantize(X, x_range[0], x_range[1], s)
+    x_scale = scale(float(x_range[0]), float(x_range[1]), s)
     trace = []
     used = []
     for l, W in enumerate(Ws):
         Wq = quantize(W, w_ranges[l][0], w_ranges[l][1], t)
+        sw = scale(float(w_ranges[l][0]), float(w_ranges[l][1]), t)
         rq_in = None if rqs is None else rqs[l][0]
         one_layer = layer_update_first if update_first else layer
         Y, Yq, Z, agg_rq = one_layer(A, Xq, Wq, s, rq_in, self_term)
+        z_scale = (x_scale / float(agg_rq[1])) * sw if not update_first else (x_scale * sw) / float(agg_rq[1])
         last = l == len(Ws) - 1
+        affine = None if affines is None else affines[l]
+        if not last and batchnorms is not None and batchnorms[l] is not None:
+            assert affine is None
+            bn = batchnorms[l]
+            affine = fold_batchnorm(bn["gamma"], bn["beta"], bn["mean"], bn["var"], bn["eps"], z_scale)
         if last:
             out_rq = None
             nxt = None
-        elif affines is not None and affines[l] is not None:
+            x_next = None
+        elif affine is not None:
             # a batch normalization folded into the layer's epilogue (Section 4.5)
-            ca, cb = affines[l]
+            ca, cb = affine
             out_rq = calibrate_requant_affine(Z, ca, cb, s) if rqs is None else rqs[l][1]
             nxt = requantize_affine(Z, ca, cb, out_rq[0], out_rq[1], s, relu=True)
+            x_next = 1.0 / float(out_rq[1])
         else:
             out_rq = calibrate_requant(Z, s) if rqs is None else rqs[l][1]
             nxt = requantize(Z, out_rq[0], out_rq[1], s, relu=True)
+            x_next = z_scale / float(out_rq[1])
         trace.append({"Xq": Xq, "Wq": Wq, "Y": Y, "Yq": Yq, "Z": Z,
-                      "Xq_next": nxt})
+                      "Xq_next": nxt, "x_scale": x_scale, "z_scale": z_scale, "affine": affine})
         used.append((agg_rq, out_rq))
         Xq = nxt
+        x_scale = x_next
     return trace, used
+
+
+def forward_dequantized(A, X, x_range, Ws, w_ranges, s: int, t: int, self_term: bool,
+                        rqs=None, update_first: bool = False, affines=None, batchnorms=None):
+    """forward(), then the fp32 output of the last layer (Section 4.5: hidden layers
+    emit low-bit codes, the last one full precision).  Returns (out, trace, rqs).
+
+    Aggregate first: the exact real product (see dequantize) of
+        left operand   Y^[i, :] = l0[i] + sl * Yq[i, :],  sl = x_scale / inv_agg,
+                       l0[i] = x_scale * rq_lo + x_lo * (deg[i] + 1 if self_term else deg[i])
+        right operand  W^ = lo_w + sw * Wq
+    where x_lo is the zero point of the features the last layer reads: the lower bound of
+    x_range for a one-layer network, 0 behind a hidden layer (pure-scale reading, see
+    forward).  A batch normalization given for the last layer acts on that real value
+    (fold_batchnorm with value scale 1).
+    Update first: out = z_scale * Z (every code a pure scale; zero points do not factor
+    through the aggregation that follows the update)."""
+    trace, used = forward(A, X, x_range, Ws, w_ranges, s, t, self_term, rqs=rqs,
+                          update_first=update_first, affines=affines, batchnorms=batchnorms)
+    L = len(Ws) - 1
+    tr = trace[L]
+    col_a = col_b = None
+    if batchnorms is not None and batchnorms[L] is not None:
+        bn = batchnorms[L]
+        col_a, col_b = fold_batchnorm(bn["gamma"], bn["beta"], bn["mean"], bn["var"], bn["eps"], 1.0)
+    elif affines is not None and affines[L] is not None:
+        col_a, col_b = affines[L]
+    if update_first:
+        return dequantize(tr["Z"], cc=tr["z_scale"], col_a=col_a, col_b=col_b), trace, used
+    rq_lo, inv_agg = used[L][0]
+    lo_w = float(w_ranges[L][0])
+    sw = scale(lo_w, float(w_ranges[L][1]), t)
+    sl = tr["x_scale"] / float(inv_agg)
+    x_lo = float(x_range[0]) if L == 0 else 0.0
+    out = dequantize(tr["Z"], cc=sl * sw, rs=sl * lo_w,
+                     row_i=tr["Yq"].sum(axis=1, dtype=np.int64),
+                     l0a=tr["x_scale"] * int(rq_lo) + (x_lo if self_term else 0.0), l0b=x_lo,
+                     row_l=degrees(A),
+                     ck=lo_w * np.asarray(Ws[L]).shape[0], cs=sw,
+                     col_i=tr["Wq"].sum(axis=0, dtype=np.int64), col_a=col_a, col_b=col_b)
+    return out, trace, used

@@ -42,3 +42,23 @@ def words_np(bits: q.Bits) -> np.ndarray:
 
 def sync():
     torch.cuda.synchronize()
+
+
+def assert_fp32_close(got, ref, what=""):
+    """The fp32 parity rule, elementwise: |got - ref| <= 1e-6 * max(|ref|, max|ref|), i.e.
+    1e-6 relative with an absolute floor of 1e-6 * max|ref| for entries near zero.  Prints
+    the largest error met, relative to max|ref| and (for entries above 1e-3 of the largest)
+    relative to the entry itself."""
+    got = np.asarray(got, dtype=np.float64)
+    ref64 = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref64.shape
+    top = float(np.abs(ref64).max()) if ref64.size else 0.0
+    err = np.abs(got - ref64)
+    worst = float(err.max()) if err.size else 0.0
+    big = np.abs(ref64) > 1e-3 * top
+    rel = float((err[big] / np.abs(ref64[big])).max()) if big.any() else 0.0
+    print(f"fp32 parity {what}: max|err| = {worst:.3e} = {worst / top if top else 0.0:.3e} of max|ref|, "
+          f"max relative error on entries above 1e-3 of the largest = {rel:.3e}, "
+          f"{int((err == 0).sum())} of {err.size} entries identical")
+    assert np.isfinite(got).all()
+    assert worst <= 1e-6 * top, (what, worst, top)

@@ -10,7 +10,7 @@ from workloads import make_workload
 pytestmark = pytest.mark.gpu
 
 q = pytest.importorskip("paper_2111_09547_amd")
-from gpu_util import dev, as_u32, pack_adjacency, words_np, sync  # noqa: E402
+from gpu_util import assert_fp32_close, dev, as_u32, pack_adjacency, words_np, sync  # noqa: E402
 
 
 def rand_graph(rng, n, k, p):
@@ -250,12 +250,25 @@ def test_aggregate_bits_and_f32_epilogues(d, rq_bits):
     want = qgnn.requantize(Y, rq_lo, inv, rq_bits)
     assert (words_np(got) == bp.pack(want, rq_bits, bp.LEFT)).all()
     assert (as_u32(q.qgtc_unpack_bits(got)) == want).all()
+    # a destination with the default LEFT strides (rows padded to 128 bits), poisoned: the
+    # zero padding is part of what the epilogue writes, so the result can serve as the left
+    # operand of a kernel that reads whole 128-bit rows
+    dst = q.alloc_bits(n, d, rq_bits, q.LEFT)
+    assert dst.c.ld_words % 4 == 0 and dst.c.ld_words >= -(-d // 32)
+    dst.words.fill_(-1)
+    Ab = pack_adjacency(A)
+    q.qgtc_aggregate(Ab, q.qgtc_build_tile_map(Ab, 16, 128), q.qgtc_pack_bits(dev(X.view(np.int32)), s, q.RIGHT),
+                     ep, out=dst)
+    raw = dst.words.cpu().numpy().view(np.uint32)[:rq_bits * n * dst.c.ld_words].reshape(rq_bits, n, -1)
+    kw = -(-d // 32)
+    assert (raw[:, :, :kw] == bp.pack(want, rq_bits, bp.LEFT)).all()
+    assert (raw[:, :, kw:] == 0).all()
     # fp32: sx * Y + lo_x * deg
     deg = A.sum(axis=1).astype(np.int32)
     ep = q.Epilogue(mode=q.OUT_F32, cc=0.37, rs=-1.25, row_i=dev(deg))
     got, _ = run_aggregate(A, X, s, 128, ep=ep)
     ref = qgnn.dequantize(Y, cc=0.37, rs=-1.25, row_i=deg)
-    assert np.allclose(got.cpu().numpy(), ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+    assert_fp32_close(got.cpu().numpy(), ref, '')
     # int32 with ReLU on the signed accumulator (wrapped values count as negative)
     Xbig = np.full((n, d), 2 ** 31 - 1, dtype=np.uint32)
     ep = q.Epilogue(mode=q.OUT_I32, relu=True)
@@ -300,7 +313,7 @@ def test_update_bits_and_f32_epilogues(rq_bits):
         ep = q.Epilogue(mode=q.OUT_F32, relu=relu, row_i=dev(rs), row_l=dev(rl), col_i=dev(cs), **kw)
         got = q.qgtc_update(Yb, Wb, ep).cpu().numpy()
         ref = qgnn.dequantize(Z, row_i=rs, row_l=rl, col_i=cs, relu=relu, **kw)
-        assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+        assert_fp32_close(got, ref, '')
 
 
 # -------------------------------------------------------------------------- layer
@@ -408,7 +421,7 @@ def test_update_from_bytes(st, shape):
     assert (words_np(got) == bp.pack(qgnn.requantize(Z, 1, inv, 4, relu=True), 4, bp.RIGHT)).all()
     got = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_F32, cc=0.37)).cpu().numpy()
     ref = qgnn.dequantize(Z, cc=0.37)
-    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+    assert_fp32_close(got, ref, '')
 
 
 # ------------------------------------------------------------------- fused layer
@@ -508,7 +521,7 @@ def test_fused_layer_all_outputs(shape, st):
                 assert (words_np(got) == want_bits).all(), tag
                 ep = q.Epilogue(mode=q.OUT_F32, row_i=None, row_l=dev(rl), col_i=dev(cs), **kw)
                 got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep).cpu().numpy()
-                assert np.allclose(got, want_f32, rtol=1e-6, atol=1e-6 * np.abs(want_f32).max()), tag
+                assert_fp32_close(got, want_f32, str(tag))
     finally:
         q.qgtc_set_option(q.OPT_LAYER_PATH, q.LAYER_FUSED)
         q.qgtc_set_option(q.OPT_LAYER_KSPLIT, 0)
@@ -556,7 +569,7 @@ def test_column_affine_epilogue(shape, st):
     ep = q.Epilogue(mode=q.OUT_F32, cc=2.0e-3, relu=True, col_scale=dev(a1), col_shift=dev(b1))
     got = q.qgtc_aggregate(Ab, m, Xb, ep).cpu().numpy()
     ref = qgnn.dequantize(Y, cc=2.0e-3, relu=True, col_a=a1, col_b=b1)
-    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+    assert_fp32_close(got, ref, '')
 
     # update and layer: codes along the rows (RIGHT) and fp32; the shift may be absent
     (a, b), (a1, b1) = bn_params(Z, h, 1.0e-4)
@@ -581,7 +594,7 @@ def test_column_affine_epilogue(shape, st):
             ep = q.Epilogue(mode=q.OUT_F32, row_i=dev(rs.astype(np.int32)), relu=True,
                             col_scale=dev(a1), col_shift=dev(b1), **kw)
             got = q.qgtc_update(Yb, Wb, ep).cpu().numpy()
-            assert np.allclose(got, want_f32, rtol=1e-6, atol=1e-6 * np.abs(want_f32).max()), path
+            assert_fp32_close(got, want_f32, str(path))
     finally:
         q.qgtc_set_option(q.OPT_UPDATE_PATH, q.UPDATE_AUTO)
     agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=rq_bits, rq_lo=0, rq_inv_scale=float(y_inv))
@@ -594,7 +607,7 @@ def test_column_affine_epilogue(shape, st):
             assert (words_np(q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep_noshift)) == want_noshift).all(), path
             ep = q.Epilogue(mode=q.OUT_F32, row_i=None, relu=True, col_scale=dev(a1), col_shift=dev(b1), **kw)
             got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep).cpu().numpy()
-            assert np.allclose(got, want_f32, rtol=1e-6, atol=1e-6 * np.abs(want_f32).max()), path
+            assert_fp32_close(got, want_f32, str(path))
     finally:
         q.qgtc_set_option(q.OPT_LAYER_PATH, q.LAYER_FUSED)
 
@@ -633,7 +646,7 @@ def test_update_matrix_core_path_equals_popcount_and_oracle(st, shape):
         assert (z == Z).all(), path
         assert (bits == bp.pack(qgnn.requantize(Z, 0, inv, 5, relu=True), 5, bp.RIGHT)).all(), path
         ref = qgnn.dequantize(Z, row_i=rs, row_l=rs, col_i=cs, **kw)
-        assert np.allclose(f, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max()), path
+        assert_fp32_close(f, ref, str(path))
 
 
 # ------------------------------------------------------------ seeded random shapes
@@ -716,7 +729,7 @@ def test_aggregate_and_update_on_random_shapes(seed):
     assert (words_np(Yb) == bp.pack(Yq, rq_bits, bp.LEFT)).all(), tag
     got = q.qgtc_aggregate(Ab, m, Xb, q.Epilogue(mode=q.OUT_F32, cc=0.013, self_term=self_term)).cpu().numpy()
     ref = qgnn.dequantize(Y, cc=0.013)
-    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * max(1e-30, np.abs(ref).max())), tag
+    assert_fp32_close(got, ref, str(tag))
 
     Wq = rng.integers(0, 2 ** t, size=(d, h), dtype=np.uint64).astype(np.uint32)
     Z = qgnn.update(Yq, Wq)

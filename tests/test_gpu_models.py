@@ -12,15 +12,7 @@ pytestmark = pytest.mark.gpu
 
 q = pytest.importorskip("paper_2111_09547_amd")
 from paper_2111_09547_amd.model import QuantGNN, LayerRanges  # noqa: E402
-from gpu_util import dev, as_u32, pack_adjacency  # noqa: E402
-
-
-def oracle_ranges(rqs, s):
-    """(rq_lo, inv) pairs of the oracle's calibration -> integer range ends."""
-    out = []
-    for (agg, o) in rqs:
-        out.append((agg, o))
-    return out
+from gpu_util import dev, as_u32, pack_adjacency, assert_fp32_close  # noqa: E402
 
 
 def run_model(w, tile_kbits=128):
@@ -57,23 +49,9 @@ def run_model(w, tile_kbits=128):
     out = net.forward(X, xr, ranges)
     torch.cuda.synchronize()
 
-    # fp32 reference from the oracle with the same scalars
-    L = len(w.W) - 1
-    x_lo, x_scale = xr[0], (xr[1] - xr[0]) / 2.0 ** w.s
-    for l in range(L):
-        sw = (wr[l][1] - wr[l][0]) / 2.0 ** w.t
-        x_scale = (x_scale / float(rqs[l][0][1])) * sw / float(rqs[l][1][1])
-        x_lo = 0.0
-    sw = (wr[L][1] - wr[L][0]) / 2.0 ** w.t
-    sl = x_scale / float(rqs[L][0][1])
-    deg = g.degrees()
-    ref = qgnn.dequantize(trace[L]["Z"], cc=sl * sw, rs=sl * wr[L][0],
-                          row_i=trace[L]["Yq"].sum(axis=1, dtype=np.int64),
-                          l0a=(x_lo if self_term else 0.0), l0b=x_lo, row_l=deg,
-                          ck=wr[L][0] * w.W[L].shape[0], cs=sw,
-                          col_i=trace[L]["Wq"].sum(axis=0, dtype=np.int64))
-    got = out.cpu().numpy()
-    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+    # the oracle's fp32 output for the same user-set ranges
+    ref, _, _ = qgnn.forward_dequantized(A, w.X, xr, w.W, wr, w.s, w.t, self_term, rqs=rqs)
+    assert_fp32_close(out.cpu().numpy(), ref, f"config {w.cfg} s={w.s} end to end")
 
     # independent runs of subgraphs on several streams give the same bytes
     if w.storage == "compact":
@@ -115,7 +93,8 @@ def run_model(w, tile_kbits=128):
     return net, ranges
 
 
-@pytest.mark.parametrize("cfg,bits,nb", [(5, 8, 4), (5, 4, 4), (4, 8, 2), (5, 8, None)])
+@pytest.mark.parametrize("cfg,bits,nb", [(5, 8, 4), (5, 4, 4), (4, 8, 2), (5, 8, None), (5, 4, None), (5, 2, None),
+                                         (5, 1, None), (4, 8, None)])
 def test_update_first_order(cfg, bits, nb):
     """A.(X.W) per layer (qgtc_update, then qgtc_aggregate): calibrated ranges, the last
     int32 accumulators and the scale-only fp32 output against the oracle run in the same
@@ -131,20 +110,14 @@ def test_update_first_order(cfg, bits, nb):
     ranges = net.calibrate(X, xr)
     rqs = [((0, qgnn.inv_scale(0.0, float(r.agg_hi), w.s)),
             None if r.out_hi is None else (0, qgnn.inv_scale(0.0, float(r.out_hi), w.s))) for r in ranges]
-    trace, _ = qgnn.forward(g.scipy_csr(), w.X, xr, w.W, wr, w.s, w.t, self_term, rqs=rqs,
-                            update_first=True)
+    ref, trace, _ = qgnn.forward_dequantized(g.scipy_csr(), w.X, xr, w.W, wr, w.s, w.t, self_term, rqs=rqs,
+                                             update_first=True)
     for r, tr in zip(ranges, trace):
         assert r.agg_hi == max(1, int(qgnn.as_signed(tr["Y"]).max()))
     z = net.forward(X, xr, ranges, want_int=True)
     assert (as_u32(z) == trace[-1]["Z"]).all()
     out = net.forward(X, xr, ranges).cpu().numpy()
-    scale = (xr[1] - xr[0]) / 2.0 ** w.s
-    for l in range(len(w.W)):
-        scale = scale * ((wr[l][1] - wr[l][0]) / 2.0 ** w.t) / float(rqs[l][0][1])
-        if rqs[l][1] is not None:
-            scale = scale / float(rqs[l][1][1])
-    ref = qgnn.dequantize(trace[-1]["Z"], cc=scale)
-    assert np.allclose(out, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+    assert_fp32_close(out, ref, f"config {cfg} s={bits} update first")
 
 
 @pytest.mark.parametrize("nb", [2, None])
@@ -153,7 +126,8 @@ def test_config4_gin_five_layers(nb):
     run_model(w)
 
 
-@pytest.mark.parametrize("bits,nb,kb", [(1, 4, 128), (2, 4, 64), (4, 4, 32), (8, 4, 128), (8, None, 128), (4, None, 32)])
+@pytest.mark.parametrize("bits,nb,kb", [(1, 4, 128), (2, 4, 64), (4, 4, 32), (8, 4, 128), (8, None, 128), (4, None, 32),
+                                        (1, None, 128), (2, None, 128), (2, None, 32), (1, None, 32)])
 def test_config5_gcn_two_layers(bits, nb, kb):
     w = make_workload(5, bits=bits, n_blocks=nb)
     run_model(w, tile_kbits=kb)
@@ -207,48 +181,23 @@ def test_batchnorm_folded_into_the_layers(cfg, nb, last_bn):
     wr = [(float(W.min()), float(W.max())) for W in w.W]
     ranges = net.calibrate(X, xr)
 
-    # the oracle's side: scale of one accumulator unit per layer, fold, ranges
-    rqs, affines = [], []
-    x_scale = (xr[1] - xr[0]) / 2.0 ** w.s
-    for l, r in enumerate(ranges):
-        agg = (0, qgnn.inv_scale(0.0, float(r.agg_hi), w.s))
-        sw = (wr[l][1] - wr[l][0]) / 2.0 ** w.t
-        z_scale = (x_scale / float(agg[1])) * sw
-        if l == n_layers - 1:
-            rqs.append((agg, None))
-            affines.append(None)
-            break
-        out = (0, qgnn.inv_scale(0.0, float(r.out_hi), w.s))
-        rqs.append((agg, out))
-        p = params[l]
-        affines.append(qgnn.fold_batchnorm(p["gamma"], p["beta"], p["mean"], p["var"], p["eps"], z_scale))
-        x_scale = 1.0 / float(out[1])
-    trace, _ = qgnn.forward(g.scipy_csr(), w.X, xr, w.W, wr, w.s, w.t, self_term, rqs=rqs, affines=affines)
+    # the oracle's side: the same user-set ranges and the same batch-normalization parameters;
+    # it folds them itself, with the real value of one accumulator unit of each layer
+    rqs = [((0, qgnn.inv_scale(0.0, float(r.agg_hi), w.s)),
+            None if r.out_hi is None else (0, qgnn.inv_scale(0.0, float(r.out_hi), w.s))) for r in ranges]
+    ref, trace, _ = qgnn.forward_dequantized(g.scipy_csr(), w.X, xr, w.W, wr, w.s, w.t, self_term, rqs=rqs,
+                                             batchnorms=params)
     for l, (r, tr) in enumerate(zip(ranges, trace)):
         assert r.agg_hi == max(1, int(qgnn.as_signed(tr["Y"]).max())), l
         if l < n_layers - 1:                      # the range the HIP path calibrated is the oracle's
-            ca, cb = affines[l]
-            v = qgnn.as_signed(tr["Z"]).astype(np.float64) * ca.astype(np.float64)[None, :] + cb.astype(np.float64)[None, :]
-            assert r.out_hi == max(1e-6, float(v.max())), l
+            ca, cb = tr["affine"]
+            assert float(qgnn.calibrate_requant_affine(tr["Z"], ca, cb, w.s)[1]) == float(rqs[l][1][1]), l
             assert tr["Xq_next"].max() == 2 ** w.s - 1
 
     z = net.forward(X, xr, ranges, want_int=True)
     assert (as_u32(z) == trace[-1]["Z"]).all()
     out = net.forward(X, xr, ranges).cpu().numpy()
-    L = n_layers - 1
-    sw = (wr[L][1] - wr[L][0]) / 2.0 ** w.t
-    sl = x_scale / float(rqs[L][0][1])
-    extra = {}
-    if last_bn:
-        p = params[L]
-        a1, b1 = qgnn.fold_batchnorm(p["gamma"], p["beta"], p["mean"], p["var"], p["eps"], 1.0)
-        extra = dict(col_a=a1, col_b=b1)
-    ref = qgnn.dequantize(trace[L]["Z"], cc=sl * sw, rs=sl * wr[L][0],
-                          row_i=trace[L]["Yq"].sum(axis=1, dtype=np.int64),
-                          l0a=0.0, l0b=0.0, row_l=g.degrees(),
-                          ck=wr[L][0] * w.W[L].shape[0], cs=sw,
-                          col_i=trace[L]["Wq"].sum(axis=0, dtype=np.int64), **extra)
-    assert np.allclose(out, ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+    assert_fp32_close(out, ref, f"config {cfg} with batch normalization")
     # the recorded pass gives the same bytes
     buf = torch.empty_like(net.forward(X, xr, ranges))
     graph = net.capture(X, xr, ranges, buf, with_static=True)

@@ -471,3 +471,233 @@ def test_batchnorm_fold_matches_the_definition():
     assert np.allclose(got, want, rtol=1e-5, atol=1e-5 * hi)
     assert np.allclose(qgnn.dequantize(c_u32, cc=value_scale, col_a=a1, col_b=None),
                        base.astype(np.float64) * a1[None, :].astype(np.float64), rtol=1e-6, atol=1e-9)
+
+
+# ------------------------------------------- int32 output, calibration, sparse inputs
+def test_int_output_reads_the_accumulator_as_signed():
+    """bitMM2Int: the 32-bit accumulator is handed out as int32; ReLU acts on that
+    signed value, so a wrapped (negative) accumulator becomes 0, not a large positive."""
+    c = np.array([[0, 7, 2 ** 31 - 1, 2 ** 31, 2 ** 32 - 3, 2 ** 32 - 1]], dtype=np.uint32)
+    got = qgnn.int_output(c)
+    assert got.dtype == np.int32
+    assert got.tolist() == [[0, 7, 2 ** 31 - 1, -2 ** 31, -3, -1]]
+    relu = qgnn.int_output(c, relu=True)
+    assert relu.dtype == np.int32
+    assert relu.tolist() == [[0, 7, 2 ** 31 - 1, 0, 0, 0]]
+    assert c.tolist() == [[0, 7, 2 ** 31 - 1, 2 ** 31, 2 ** 32 - 3, 2 ** 32 - 1]]     # input untouched
+    assert qgnn.as_signed(c).tolist() == got.tolist()
+
+
+def test_calibrated_ranges_by_hand():
+    """Range a user would set from observed values: lower bound 0, upper bound the largest
+    signed accumulator (Eq. (2)'s empirical bounds) - a wrapped value is negative and never
+    the maximum; behind a per-column affine map, the largest mapped value."""
+    c = np.array([[5, 2 ** 32 - 5], [12, 3]], dtype=np.uint32)      # signed: 5, -5, 12, 3
+    lo, inv = qgnn.calibrate_requant(c, 3)
+    assert lo == 0 and inv == np.float32(8.0 / 12.0) and isinstance(inv, np.float32)
+    assert qgnn.calibrate_requant(np.array([[2 ** 32 - 1]], dtype=np.uint32), 4) == (0, np.float32(16.0))
+    # v = C * a + b per column: [[5*0.5+1, -5*2-30], [12*0.5+1, 3*2-30]] = [[3.5, -40], [7, -24]]
+    a, b = np.array([0.5, 2.0], dtype=np.float32), np.array([1.0, -30.0], dtype=np.float32)
+    lo, inv = qgnn.calibrate_requant_affine(c, a, b, 4)
+    assert lo == 0 and inv == np.float32(16.0 / 7.0)
+    # no shift: [[2.5, -10], [6, 6]]
+    assert qgnn.calibrate_requant_affine(c, a, None, 4)[1] == np.float32(16.0 / 6.0)
+    # a swapped scale / shift would give 12 * 1 + 0.5 = 12.5
+    assert qgnn.calibrate_requant_affine(c, a, b, 4)[1] != np.float32(16.0 / 12.5)
+    # nothing positive: the floor of 1e-6 keeps the scale finite
+    neg = np.array([[2 ** 32 - 4, 2 ** 32 - 9]], dtype=np.uint32)
+    assert qgnn.calibrate_requant_affine(neg, np.ones(2, dtype=np.float32), None, 2)[1] == np.float32(4.0 / 1e-6)
+    # the range it returns is used fully by the codes it is made for
+    rng = np.random.default_rng(5)
+    C = rng.integers(-1000, 50000, size=(30, 6)).astype(np.int64)
+    cu = (C & 0xFFFFFFFF).astype(np.uint32)
+    ca = rng.uniform(0.5, 2.0, size=6).astype(np.float32)
+    cb = rng.uniform(-3.0, 3.0, size=6).astype(np.float32)
+    lo, inv = qgnn.calibrate_requant_affine(cu, ca, cb, 5)
+    assert qgnn.requantize_affine(cu, ca, cb, lo, inv, 5, relu=True).max() == 31
+
+
+@pytest.mark.parametrize("self_term", [False, True])
+def test_sparse_adjacency_branches_against_brute_force(self_term):
+    """A scipy sparse adjacency goes through its own product: against the textbook triple
+    loop on Python integers (directed graph, so a transposed product fails), with the GIN
+    self term, and with 32-bit features whose neighbour sums pass 2^32 (wrap)."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng([21, int(self_term)])
+    n, d = 23, 5
+    A = (rng.random((n, n)) < 0.3).astype(np.uint8)
+    A[3, :] = 0                                             # an isolated row
+    assert (A != A.T).any()
+    for bits in (3, 32):
+        X = rng.integers(0, 2 ** bits, size=(n, d), dtype=np.uint64).astype(np.uint32)
+        if bits == 32:
+            X[:, 0] = 2 ** 32 - 1                           # every neighbour sum of column 0 wraps
+        ref = py_matmul(A.tolist(), X.tolist())
+        if self_term:
+            ref = [[v + int(X[i][j]) for j, v in enumerate(r)] for i, r in enumerate(ref)]
+        want = [[v % 2 ** 32 for v in r] for r in ref]
+        if bits == 32:
+            assert max(max(r) for r in ref) >= 2 ** 32
+        for fmt in (sp.csr_matrix, sp.coo_matrix, sp.csc_matrix):
+            As = fmt(A.astype(np.uint64))
+            got = qgnn.aggregate(As, X, self_term=self_term)
+            assert got.dtype == np.uint32 and got.tolist() == want
+        assert qgnn.aggregate(A, X, self_term=self_term).tolist() == want        # dense branch agrees
+    deg = [sum(int(v) for v in row) for row in A.tolist()]
+    assert deg[3] == 0
+    for fmt in (sp.csr_matrix, sp.coo_matrix):
+        assert qgnn.degrees(fmt(A)).tolist() == deg         # row sums, not column sums
+        assert qgnn.degrees(fmt(A.astype(np.uint64))).tolist() == deg
+    assert qgnn.degrees(A).tolist() == deg
+    assert qgnn.degrees(sp.csr_matrix(A)).tolist() != qgnn.degrees(sp.csr_matrix(A.T)).tolist()
+
+
+# ----------------------------------------------------- end-to-end fp32 output
+def _golden_net():
+    g = load_golden("gcn_2layer_3nodes.txt")
+    A = np.array(g["A"], dtype=np.uint8)
+    X = np.array(g["X"], dtype=np.float32)
+    Ws = [np.array(g["W1"], dtype=np.float32), np.array(g["W2"], dtype=np.float32).reshape(2, 1)]
+    xr = (g["x_lo"][0], g["x_hi"][0])
+    wr = [(g["w_lo"][0], g["w_hi"][0])] * 2
+    return g, A, X, Ws, xr, wr
+
+
+def test_two_layer_network_worked_by_hand():
+    """Every integer of a 2-layer GCN, the scale each stands for and the fp32 output,
+    against a hand calculation (tests/golden/gcn_2layer_3nodes.txt), in both orders of the
+    two products, with calibrated and with given ranges."""
+    g, A, X, Ws, xr, wr = _golden_net()
+    s, t = g["s"][0], g["t"][0]
+    col = lambda key: np.array(g[key]).reshape(-1, 1).tolist()
+    # the ranges of the hand calculation, given by the user
+    inv = lambda hi: qgnn.inv_scale(0.0, float(hi), s)
+    rqs = [((0, inv(g["agg1_hi"][0])), (0, inv(g["out1_hi"][0]))), ((0, inv(g["agg2_hi"][0])), None)]
+    out, trace, used = qgnn.forward_dequantized(A, X, xr, Ws, wr, s, t, False, rqs=rqs)
+    assert trace[0]["Xq"].tolist() == g["Xq"] and trace[0]["Wq"].tolist() == g["W1q"]
+    assert trace[0]["Y"].tolist() == g["Y1"] and trace[0]["Yq"].tolist() == g["Y1q"]
+    assert trace[0]["Z"].tolist() == g["Z1"] and trace[0]["Xq_next"].tolist() == g["X1q"]
+    assert trace[0]["x_scale"] == 1.0 and trace[0]["z_scale"] == g["z1_scale"][0]
+    assert trace[1]["x_scale"] == g["x1_scale"][0]
+    assert trace[1]["Y"].tolist() == g["Y2"] and trace[1]["Yq"].tolist() == g["Y2q"]
+    assert trace[1]["Wq"].tolist() == col("W2q") and trace[1]["Z"].tolist() == col("Z2")
+    assert out.dtype == np.float32 and out.tolist() == col("out")
+    # the other order of the two products
+    rqs_u = [((0, inv(g["p1_hi"][0])), (0, inv(g["zu1_hi"][0]))), ((0, inv(g["p2_hi"][0])), None)]
+    out_u, tr_u, _ = qgnn.forward_dequantized(A, X, xr, Ws, wr, s, t, False, rqs=rqs_u, update_first=True)
+    assert tr_u[0]["Y"].tolist() == g["P1"] and tr_u[0]["Yq"].tolist() == g["P1q"]
+    assert tr_u[0]["Z"].tolist() == g["ZU1"] and tr_u[0]["Xq_next"].tolist() == g["XU1q"]
+    assert tr_u[1]["Y"].tolist() == col("P2") and tr_u[1]["Yq"].tolist() == col("P2q")
+    assert tr_u[1]["Z"].tolist() == col("ZU2")
+    assert out_u.tolist() == col("out_update_first")
+    # forward() alone gives the same integers
+    tr2, _ = qgnn.forward(A, X, xr, Ws, wr, s, t, False, rqs=rqs)
+    assert all((a["Z"] == b["Z"]).all() for a, b in zip(trace, tr2))
+
+
+@pytest.mark.parametrize("self_term", [False, True])
+def test_one_layer_network_output_is_the_real_product(self_term):
+    """One layer: the fp32 output is the product of the dequantized operands, zero points
+    included, taken directly in float64 (A.(lo_x + sx Xq) requantized, times lo_w + sw Wq)."""
+    rng = np.random.default_rng([31, int(self_term)])
+    n, d, h, s, t = 40, 12, 5, 6, 3
+    A = _rand_graph(rng, n, 0.15)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    W = rng.uniform(-0.1, 0.1, size=(d, h)).astype(np.float32)
+    xr, wr = (float(X.min()), float(X.max())), (float(W.min()), float(W.max()))
+    out, trace, used = qgnn.forward_dequantized(A, X, xr, [W], [wr], s, t, self_term)
+    tr = trace[0]
+    sx, sw = qgnn.scale(*xr, s), qgnn.scale(*wr, t)
+    deg = A.sum(axis=1).astype(np.float64) + (1.0 if self_term else 0.0)
+    (rq_lo, rq_inv), _ = used[0]
+    Yh = (sx * rq_lo + xr[0] * deg)[:, None] + (sx / float(rq_inv)) * tr["Yq"].astype(np.float64)
+    ref = Yh @ (wr[0] + sw * tr["Wq"].astype(np.float64))
+    assert np.allclose(out, ref, rtol=0, atol=2e-6 * np.abs(ref).max())
+    # and Yh is the requantized image of the real aggregation: within one step of it
+    Xh = xr[0] + sx * tr["Xq"].astype(np.float64)
+    Yreal = (A.astype(np.float64) + (np.eye(n) if self_term else 0.0)) @ Xh
+    step = sx / float(rq_inv)
+    below = tr["Yq"] < 2 ** s - 1
+    assert (np.abs(Yh - Yreal)[below] <= step * (1 + 1e-6)).all()
+
+
+@pytest.mark.parametrize("update_first", [False, True])
+@pytest.mark.parametrize("self_term", [False, True])
+def test_scale_chain_of_a_deep_network(update_first, self_term):
+    """The pure-scale reading of hidden codes, layer by layer, against a float64 pass over
+    real values: with x~ = x_scale * Xq the real aggregation, its requantized image, the real
+    update and the next layer's real activations each lie within one quantization step of
+    what the integers stand for.  A wrong factor anywhere in the chain (a dropped weight
+    step, an inverted scale) is off by far more than a step.  The last layer's output is
+    then the exact float64 product."""
+    rng = np.random.default_rng([37, int(update_first), int(self_term)])
+    n, dims, s, t = 50, [10, 8, 6, 4], 7, 6
+    A = _rand_graph(rng, n, 0.12)
+    Ad = A.astype(np.float64) + (np.eye(n) if self_term else 0.0)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    Ws = [rng.uniform(-0.1, 0.1, size=(dims[l], dims[l + 1])).astype(np.float32) for l in range(3)]
+    xr = (float(X.min()), float(X.max()))
+    wr = [(float(W.min()), float(W.max())) for W in Ws]
+    out, trace, used = qgnn.forward_dequantized(A, X, xr, Ws, wr, s, t, self_term, update_first=update_first)
+    top = 2 ** s - 1
+    x_real = qgnn.scale(*xr, s) * trace[0]["Xq"].astype(np.float64)        # pure scale: no zero point
+    for l, tr in enumerate(trace):
+        sw = qgnn.scale(*wr[l], t)
+        w_real = sw * tr["Wq"].astype(np.float64)                          # hidden layers: pure scale
+        (rq_lo, inv_mid), out_rq = used[l]
+        assert rq_lo == 0
+        first = (x_real @ w_real) if update_first else (Ad @ x_real)       # P or Y, real
+        unit_mid = (tr["x_scale"] * sw if update_first else tr["x_scale"]) / float(inv_mid)
+        mid_real = unit_mid * tr["Yq"].astype(np.float64)
+        ok = tr["Yq"] < top
+        assert (np.abs(mid_real - np.maximum(first, 0))[ok] <= unit_mid * (1 + 1e-6)).all(), l
+        assert np.isclose(tr["z_scale"], unit_mid if update_first else unit_mid * sw, rtol=1e-12)
+        if l == len(trace) - 1:
+            if update_first:
+                ref = Ad @ mid_real
+            else:
+                ref = mid_real @ (wr[l][0] + w_real)                       # last layer: W with its zero point
+            assert np.allclose(out, ref, rtol=0, atol=2e-6 * np.abs(ref).max())
+            break
+        second = (Ad @ mid_real) if update_first else (mid_real @ w_real)  # Z, real
+        assert np.allclose(second, tr["z_scale"] * qgnn.as_signed(tr["Z"]), rtol=1e-9, atol=1e-12)
+        unit_out = tr["z_scale"] / float(out_rq[1])
+        assert np.isclose(trace[l + 1]["x_scale"], unit_out, rtol=1e-12)
+        x_real = unit_out * tr["Xq_next"].astype(np.float64)
+        ok = tr["Xq_next"] < top
+        assert (np.abs(x_real - np.maximum(second, 0))[ok] <= unit_out * (1 + 1e-6)).all(), l
+
+
+def test_network_with_batchnorm_layers_against_the_definition():
+    """batchnorms given to the oracle are folded per layer with the real value of one
+    accumulator unit: the hidden codes then stand for ReLU(BN(z_scale * Z)) computed from
+    the definition of batch normalization, within one step; the last layer's normalization
+    acts on the real fp32 value."""
+    rng = np.random.default_rng(47)
+    n, dims, s, t = 60, [9, 7, 5], 8, 8
+    A = _rand_graph(rng, n, 0.1)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    Ws = [rng.uniform(-0.1, 0.1, size=(dims[l], dims[l + 1])).astype(np.float32) for l in range(2)]
+    xr = (float(X.min()), float(X.max()))
+    wr = [(float(W.min()), float(W.max())) for W in Ws]
+    bns = [dict(gamma=rng.uniform(0.5, 1.5, size=dims[l + 1]), beta=rng.uniform(-0.2, 0.5, size=dims[l + 1]),
+                mean=rng.uniform(-0.3, 0.3, size=dims[l + 1]), var=rng.uniform(0.5, 2.0, size=dims[l + 1]),
+                eps=1e-5) for l in range(2)]
+    out, trace, used = qgnn.forward_dequantized(A, X, xr, Ws, wr, s, t, True, batchnorms=bns)
+    plain, trace0, _ = qgnn.forward_dequantized(A, X, xr, Ws, wr, s, t, True)
+    assert (trace[0]["Z"] == trace0[0]["Z"]).all()                         # same first accumulators
+    bn = bns[0]
+    z_real = trace[0]["z_scale"] * qgnn.as_signed(trace[0]["Z"])
+    want = np.maximum((z_real - bn["mean"]) / np.sqrt(bn["var"] + bn["eps"]) * bn["gamma"] + bn["beta"], 0.0)
+    unit = 1.0 / float(used[0][1][1])
+    assert np.isclose(trace[1]["x_scale"], unit, rtol=1e-12)
+    got = unit * trace[0]["Xq_next"].astype(np.float64)
+    ok = trace[0]["Xq_next"] < 2 ** s - 1
+    assert (np.abs(got - want)[ok] <= unit * (1 + 1e-3) + 1e-5 * want.max()).all()
+    # last layer: BN of the real product, from the definition
+    tr = trace[1]
+    sl = tr["x_scale"] / float(used[1][0][1])
+    real = (sl * tr["Yq"].astype(np.float64)) @ (wr[1][0] + qgnn.scale(*wr[1], t) * tr["Wq"].astype(np.float64))
+    bn = bns[1]
+    ref = (real - bn["mean"]) / np.sqrt(bn["var"] + bn["eps"]) * bn["gamma"] + bn["beta"]
+    assert np.allclose(out, ref, rtol=1e-5, atol=1e-5 * np.abs(ref).max())
