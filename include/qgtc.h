@@ -234,6 +234,8 @@ qgtc_status qgtc_build_tile_map(const qgtc_bits* A, const qgtc_tile_map* map,
  *                   code = min(floor(fp32(max(d, 0)) * rq_inv_scale), 2^rq_nbits - 1)
  *                 out: const qgtc_bits* describing the destination
  *                 (qgtc_aggregate: LEFT; qgtc_update: RIGHT; nbits == rq_nbits).
+ *                 Every word of the destination is written, the zero words
+ *                 between the end of a LEFT row and its ld_words included.
  *
  * self_term (qgtc_aggregate only): adds X[i, j] itself to C, i.e. the GIN
  * aggregation (1 + eps).X + A.X with eps = 0; needs a square adjacency.

@@ -182,6 +182,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
     const int qbits = e.rq_nbits;
     const uint32_t qmax = qbits >= 32 ? 0xffffffffu : ((1u << qbits) - 1u);
     const float qmaxf = (float)qmax;
+    // A LEFT operand has zeros in the words between the last data word of a row and its
+    // leading dimension; the workgroup of the last column group writes them for its rows.
+    const int data_words = (p.cols + 31) >> 5;
+    const int pad_words = (int)e.ld_out - data_words;
+    if (pad_words > 0 && cg == p.n_cg - 1) {
+      const int rows_here = min(16, p.rows - out_row0);
+      for (int idx = (int)threadIdx.x; idx < qbits * rows_here * pad_words; idx += (int)blockDim.x) {
+        const int w = idx % pad_words;
+        const int rj = (idx / pad_words) % rows_here;
+        const int pl = idx / (pad_words * rows_here);
+        reinterpret_cast<uint32_t*>(e.out)[(int64_t)pl * e.ps_out + (int64_t)(out_row0 + rj) * e.ld_out +
+                                          data_words + w] = 0u;
+      }
+    }
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const bool ok = c_ok && (out_row0 + j) < p.rows;

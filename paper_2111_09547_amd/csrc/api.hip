@@ -109,6 +109,23 @@ qgtc_status make_epilogue(const qgtc_epilogue* ep, void* out, int64_t ld_out, in
   return QGTC_OK;
 }
 
+// ---- device facts --------------------------------------------------------------------
+namespace {
+std::mutex g_device_mutex;
+int g_device_cus[64] = {};
+}
+int device_compute_units() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  std::lock_guard<std::mutex> lock(g_device_mutex);
+  if (g_device_cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    g_device_cus[dev] = n;
+  }
+  return g_device_cus[dev];
+}
+
 // ---- library options ---------------------------------------------------------------
 namespace {
 int g_update_path = 0;

@@ -130,23 +130,41 @@ __device__ __forceinline__ uint32_t squeeze4(uint32_t d) {
   return t & 0xfu;
 }
 
+// A unit is 1024 columns of one row (64 lanes x 16 bytes); a wave takes kU8Units units
+// at a time, all of their loads in flight together, and walks over the matrix with the
+// stride of the grid, so that a launch is a few thousand long-lived waves rather than
+// one short wave per row.
+constexpr int kU8Units = 8;
+
 __global__ __launch_bounds__(256) void pack_left_u8_kernel(const PackParams p) {
   const int lane = threadIdx.x & 63;
-  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= p.rows) return;                       // whole wave
-  const uint8_t* srow = reinterpret_cast<const uint8_t*>(p.src) + (int64_t)r * p.ld_src;
-  uint32_t* drow = p.dst + (int64_t)r * p.ld;
   const int n_words = (int)p.ld;
-  for (int w0 = 0; w0 < n_words; w0 += 32) {     // 32 words = 1024 columns per pass
-    const int c = w0 * 32 + lane * 16;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (c < p.cols) v = *reinterpret_cast<const uint4*>(srow + c);
-    uint32_t h = squeeze4(v.x) | (squeeze4(v.y) << 4) | (squeeze4(v.z) << 8) | (squeeze4(v.w) << 12);
-    // odd lane's half moves down to the even lane (wave shift left by one lane)
-    const uint32_t up = (uint32_t)__shfl_down((int)h, 1, 64);
-    const uint32_t word = h | (up << 16);
-    const int w = w0 + (lane >> 1);
-    if ((lane & 1) == 0 && w < n_words) drow[w] = word;
+  const int n_pass = (n_words + 31) >> 5;          // units per row
+  const int64_t n_units = (int64_t)p.rows * n_pass;
+  const int64_t wave_id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t n_waves = (int64_t)gridDim.x * 4;
+  const uint8_t* src = reinterpret_cast<const uint8_t*>(p.src);
+  for (int64_t u0 = wave_id * kU8Units; u0 < n_units; u0 += n_waves * kU8Units) {
+    uint4 v[kU8Units];
+#pragma unroll
+    for (int k = 0; k < kU8Units; ++k) {
+      const int64_t u = u0 + k;
+      const int64_t r = u / n_pass;
+      const int c = (int)(u % n_pass) * 1024 + lane * 16;
+      v[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (u < n_units && c < p.cols) v[k] = *reinterpret_cast<const uint4*>(src + r * p.ld_src + c);
+    }
+#pragma unroll
+    for (int k = 0; k < kU8Units; ++k) {
+      const int64_t u = u0 + k;
+      const int64_t r = u / n_pass;
+      const int w = (int)(u % n_pass) * 32 + (lane >> 1);
+      const uint32_t h = squeeze4(v[k].x) | (squeeze4(v[k].y) << 4) | (squeeze4(v[k].z) << 8) |
+                         (squeeze4(v[k].w) << 12);
+      // odd lane's half moves down to the even lane (wave shift left by one lane)
+      const uint32_t up = (uint32_t)__shfl_down((int)h, 1, 64);
+      if ((lane & 1) == 0 && u < n_units && w < n_words) p.dst[r * p.ld + w] = h | (up << 16);
+    }
   }
 }
 
@@ -333,7 +351,9 @@ qgtc_status launch_pack(const PackParams& p, int layout, hipStream_t s) {
     hipLaunchKernelGGL((pack_right_kernel<SRC>), grid, dim3(256), 0, s, p);
   } else if (SRC == QGTC_SRC_U8 && p.nbits == 1 && (p.cols & 15) == 0 && (p.ld_src & 15) == 0 &&
              ((uintptr_t)p.src & 15u) == 0) {
-    hipLaunchKernelGGL(pack_left_u8_kernel, dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p);
+    const int64_t units = (int64_t)p.rows * cdiv(p.ld, 32);
+    const int64_t blocks = cdiv(units, 4 * kU8Units);
+    hipLaunchKernelGGL(pack_left_u8_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, p);
   } else {
     hipLaunchKernelGGL((pack_left_kernel<SRC>), dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p);
   }

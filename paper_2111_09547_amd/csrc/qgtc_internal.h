@@ -20,6 +20,10 @@ qgtc_status check_adjacency(const qgtc_bits* A);
 // Number of 32-bit words spanned by the descriptor (last addressed word + 1).
 int64_t span_words(const qgtc_bits* b);
 
+// Compute units of the current device (asked from the runtime once per device and kept);
+// 256 on MI355X, which the launch shapes are tuned for.
+int device_compute_units();
+
 // Status of the launch that was just issued.
 inline qgtc_status launch_status() {
   return hipGetLastError() == hipSuccess ? QGTC_OK : QGTC_ERR_HIP;
@@ -68,6 +72,7 @@ struct UpdParams {
   const uint32_t* Y;
   int32_t y_bytes;        // Y holds codes as bytes, row-major (ldy words per row)
   int64_t ldy, psy;       // words between rows / planes of Y
+  int64_t y_span_bytes;   // bytes from the first to the last addressed word of Y
   int32_t rows;           // rows of Y (= output rows)
   int32_t s;              // planes of Y
   int32_t kwords;         // 32-bit words along the contraction dimension

@@ -199,6 +199,7 @@ extern "C" qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W, const
   p.y_bytes = y_bytes ? 1 : 0;
   p.ldy = Y->ld_words;
   p.psy = Y->plane_stride_words;
+  p.y_span_bytes = span_words(Y) * 4;
   p.rows = Y->rows;
   p.s = Y->nbits;
   p.kwords = cdiv(Y->cols, 32);
