@@ -257,6 +257,32 @@ qgtc_status qgtc_build_tile_map(const qgtc_bits* A, const qgtc_tile_map* map,
  * ------------------------------------------------------------------------- */
 enum { QGTC_OUT_I32 = 0, QGTC_OUT_F32 = 1, QGTC_OUT_BITS = 2 };
 
+/* Optional choices of a call that only affect speed, never results.  A NULL pointer or
+ * zeros leave every choice to the library (the rules of qgtc_plan_layer below).
+ *   update_path   which kernel qgtc_update (and the two-kernel path of qgtc_layer) uses
+ *                 when both operands have at most 8 bits.  The paper composes every product
+ *                 from 1-bit products (Section 3.1) because its matrix unit is 1-bit;
+ *                 CDNA4's matrix cores start at int8, where one instruction covers up to
+ *                 8 x 8 bit planes, so the update can re-assemble the planes into bytes in
+ *                 registers and run there.  0 = automatic, 1 = popcount kernel,
+ *                 2 = matrix cores whenever the operands fit.
+ *   agg_xcd_run   how qgtc_aggregate deals its workgroups to the 8 XCDs (each with an L2
+ *                 of its own): runs of that many consecutive tile rows go to one XCD, the
+ *                 next run to the next XCD.  0 = the run length the tile-map build chose
+ *                 (8 tile rows without a map), > 0 = that many tile rows (at most 4096),
+ *                 < 0 = one contiguous range per XCD.
+ *   layer_path    0 = qgtc_layer uses its fused kernel whenever it applies, 1 = always
+ *                 aggregate and update as two kernels.
+ *   layer_ksplit  waves of a workgroup of the fused kernel that split one tile list:
+ *                 0 = automatic (more when the grid is small), 1, 2 or 4.
+ * Values outside these ranges: QGTC_ERR_UNSUPPORTED. */
+typedef struct qgtc_tuning {
+  int32_t update_path;
+  int32_t agg_xcd_run;
+  int32_t layer_path;
+  int32_t layer_ksplit;
+} qgtc_tuning;
+
 typedef struct qgtc_epilogue {
   int32_t mode;
   int32_t relu;
@@ -270,6 +296,7 @@ typedef struct qgtc_epilogue {
   const int32_t* col_i; /* [cols] or NULL */
   const float* col_scale; /* [cols] or NULL */
   const float* col_shift; /* [cols] or NULL */
+  const qgtc_tuning* tuning; /* HOST pointer or NULL; qgtc_layer reads upd_ep's */
 } qgtc_epilogue;
 
 /* Neighbour aggregation C = A.X (first half of Algorithm 1; zero-tile jumping
@@ -320,7 +347,7 @@ qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map,
  * data (see qgtc_layer) lives in a device array of QGTC_LAYER_STATIC_MAX_BYTES that
  * is part of the library's code object; every GPU the process uses holds one copy
  * until the process ends.  The call allocates and frees nothing (with the optional
- * kernel timing below switched off, its default).
+ * kernel timing of qgtc_bench.h switched off, its default).
  * Limit: QGTC_ERR_WORKSPACE when qgtc_layer_workspace_bytes(rows of A, columns of X,
  * columns of W, agg_ep->rq_nbits) exceeds QGTC_LAYER_STATIC_MAX_BYTES.  The fused
  * kernel (all operands <= 8 bits) needs at most 512 KiB and always fits; the
@@ -337,65 +364,111 @@ qgtc_status qgtc_layer_static(const qgtc_bits* A, const qgtc_tile_map* map,
                               void* out, int64_t ld_out, void* stream);
 
 /* ---------------------------------------------------------------------------
- * Optional per-kernel timing.  While enabled, every kernel launch is bracketed
- * by HIP events recorded on the launch stream.  qgtc_prof_read synchronizes
- * with the recorded events and returns, for one kernel kind, the summed
- * duration in milliseconds and the number of launches since the last reset.
+ * Non-zero tiles of A at the three tile widths qgtc_aggregate takes, in one pass over
+ * the packed adjacency (the second kind of zero tiles of the paper's Section 6.3, gaps
+ * inside a subgraph, shows as fewer non-zero tiles at narrower widths):
+ *   counts[0..2] = number of non-zero 16 x 32, 16 x 64 and 16 x 128 tiles,
+ *   counts[3]    = number of rows of tiles, ceil(A.rows / 16).
+ * counts: device, 4 x int32, written by the call (no need to clear it).  The host reads
+ * it when it plans (qgtc_plan_layer), once per adjacency.
  * ------------------------------------------------------------------------- */
-enum {
-  QGTC_KERNEL_PACK = 0,
-  QGTC_KERNEL_TILE_MAP = 1,
-  QGTC_KERNEL_AGGREGATE = 2,
-  QGTC_KERNEL_UPDATE = 3,
-  QGTC_KERNEL_SUMS = 4,
-  QGTC_KERNEL_LAYER = 5, /* fused layer kernel (with its weight re-ordering) */
-  QGTC_KERNEL_KINDS = 6
-};
-qgtc_status qgtc_prof_enable(int32_t on);
-qgtc_status qgtc_prof_reset(void);
-qgtc_status qgtc_prof_read(int32_t kind, double* total_ms, int64_t* launches);
+qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void* stream);
 
 /* ---------------------------------------------------------------------------
- * Library options (process-wide, not thread-safe against running calls).
- * QGTC_OPT_UPDATE_PATH: which kernel qgtc_update (and qgtc_layer) uses when both
- * operands have at most 8 bits.  The paper composes every product from 1-bit
- * products (Section 3.1) because its matrix unit is 1-bit; CDNA4's matrix cores
- * start at int8, where one instruction covers up to 8 x 8 bit planes, so the
- * update can re-assemble the planes into bytes in registers and run there.  Both
- * paths give the same integers.
- *   0  automatic: matrix cores where they were measured faster (default)
- *   1  popcount kernel only
- *   2  matrix cores whenever the operands fit
- * QGTC_OPT_AGG_XCD_RUN: how qgtc_aggregate deals its workgroups to the 8 XCDs
- * (each with an L2 of its own).  Runs of `value` consecutive tile rows (all their
- * column groups) go to one XCD, the next run to the next XCD.  Short runs balance
- * graphs whose tiles are concentrated in a few subgraphs; long runs keep one
- * subgraph's X panel in one L2.  Results do not depend on it.
- *   0   default: the run length the tile-map build chose, nnz_tiles[1] (8 tile
- *       rows without a map)
- *   >0  that many tile rows (rounded up to a power of two of workgroups)
- *   <0  one contiguous range per XCD
- * QGTC_OPT_LAYER_PATH: 0 = qgtc_layer uses its fused kernel whenever it applies
- * (default), 1 = always aggregate and update as two kernels.
- * QGTC_OPT_LAYER_KSPLIT: waves of a workgroup of the fused kernel that split one
- * tile list: 0 = automatic (more when the grid is small), 1, 2 or 4.
+ * The selector: which tile width, which kernels and which launch shape the library
+ * takes for one layer (the paper leaves such a heuristic as future work, end of its
+ * Section 6.3).  A pure host function over the shape, the bit widths and the tile
+ * statistics; qgtc_update and qgtc_layer make their automatic choices through it, so
+ * the rules exist once.  Every rule is a measured crossover on MI355X.
+ *   in:  rows (nodes), in_cols (D), out_cols (H), s, t,
+ *        nnz_tiles[3] from qgtc_tile_stats (all zero: unknown, 128-bit tiles assumed,
+ *        every tile of a row counted), n_tile_rows, a_cols (columns of A as stored)
+ *   out: tile_kbits     32, 64 or 128: least executed work, tiles x width x cost per bit
+ *                       (a narrower tile must win by 2 %)
+ *        fused          1: qgtc_layer runs as one kernel (s, t <= 8, D <= 1024, H <= 256)
+ *        update_path    1 popcount, 2 int8 matrix cores: the stand-alone update's kernel
+ *        ksplit         waves of a fused workgroup that split a tile list (1, 2, 4)
+ *        est_us_aggregate_first, est_us_update_first
+ *                       rough times of (A.X).W and A.(X.W) from the measured rates; the two
+ *                       orders are different quantized networks (the requantization sits
+ *                       elsewhere), so the order stays the caller's choice
  * ------------------------------------------------------------------------- */
-enum {
-  QGTC_OPT_UPDATE_PATH = 0,
-  QGTC_OPT_AGG_XCD_RUN = 1,
-  QGTC_OPT_LAYER_PATH = 2,
-  QGTC_OPT_LAYER_KSPLIT = 3
-};
-qgtc_status qgtc_set_option(int32_t option, int32_t value);
+typedef struct qgtc_plan_in {
+  int32_t rows, in_cols, out_cols;
+  int32_t s, t;
+  int32_t n_tile_rows;
+  int32_t a_cols;
+  int32_t reserved;
+  int64_t nnz_tiles[3];
+} qgtc_plan_in;
 
-/* Measurement aid: runs the AND + popcount inner block of the aggregation
- * (16 rows x 8 planes = 256 vector instructions = 64 lanes x 32 x 128 one-bit
- * multiply-accumulates per wave and call) 4 * iters times per wave on registers
- * only, in `workgroups` workgroups of `waves_per_workgroup` (1..4) waves.  Timing
- * the launch gives the attainable AND + popcount rate of the device as it is
- * clocked at that moment.  sink: one device word, practically never written. */
-qgtc_status qgtc_probe_popcount(int32_t workgroups, int32_t waves_per_workgroup,
-                                int32_t iters, uint32_t* sink, void* stream);
+typedef struct qgtc_plan_out {
+  int32_t tile_kbits;
+  int32_t fused;
+  int32_t update_path;
+  int32_t ksplit;
+  double est_us_aggregate_first;
+  double est_us_update_first;
+} qgtc_plan_out;
+
+qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* out);
+
+/* ---------------------------------------------------------------------------
+ * Host-side scalar algebra around a stack of layers, so that a caller sets up the
+ * epilogues without redoing it.  Pure functions; no GPU.
+ * ------------------------------------------------------------------------- */
+
+/* fp32(2^nbits / (hi - lo)), formed in double and rounded once: the inverse step of
+ * Eq. (2) as qgtc_pack_bits forms it, and rq_inv_scale for a range [lo, hi).
+ * 0 when the range is empty or nbits is outside [1, 32]. */
+float qgtc_quant_inv_scale(double lo, double hi, int32_t nbits);
+
+/* One layer of a stack.  Activations between layers are low-bit codes (Section 4.5);
+ * the codes a hidden layer emits are read as pure scales, value = x_scale * code, the
+ * input features of the first layer as x_lo + x_scale * code (Eq. (2)).
+ *   order          0: aggregate, requantize, update (Algorithm 1); 1: update first,
+ *                  A.(X.W) (Section 6.1)
+ *   last           1: this layer emits fp32, 0: ReLU + requantization to s bits
+ *   batchnorm      1: col_scale / col_shift of the output epilogue hold a folded batch
+ *                  normalization (qgtc_fold_batchnorm); out_hi is then in units of the
+ *                  normalized real value
+ *   agg_hi         requantization range [0, agg_hi) of the first product's result, in
+ *                  accumulator units ("empirical bounds ... determined by users", Eq. (2))
+ *   out_hi         hidden layers: range [0, out_hi) of the second product's result */
+typedef struct qgtc_layer_spec {
+  int32_t s, t;
+  int32_t in_cols;
+  int32_t order;
+  int32_t self_term;
+  int32_t last;
+  int32_t batchnorm;
+  int32_t reserved;
+  double x_lo, x_scale;
+  double w_lo, w_hi;
+  double agg_hi;
+  double out_hi;
+} qgtc_layer_spec;
+
+/* Fills the scalar fields of the two epilogues of the layer (the pointer fields - row_l =
+ * degrees, col_i = column sums of W, col_scale / col_shift, tuning - stay the caller's):
+ *   first_ep   epilogue of the first product: QGTC_OUT_BITS to s bits over [0, agg_hi)
+ *              (agg_ep of qgtc_layer / qgtc_aggregate; with order 1: of qgtc_update)
+ *   second_ep  epilogue of the second product: hidden layer QGTC_OUT_BITS with ReLU over
+ *              [0, out_hi); last layer QGTC_OUT_F32 with cc, rs, l0a, l0b, ck, cs set for the
+ *              exact real product of the dequantized operands (order 0) or cc alone (order 1)
+ *   z_scale    real value of one unit of the second product's accumulator under the
+ *              pure-scale reading (what a batch normalization is folded with)
+ *   next_x_scale   x_scale of the next layer's codes (0 for the last layer) */
+qgtc_status qgtc_layer_epilogues(const qgtc_layer_spec* spec, qgtc_epilogue* first_ep,
+                                 qgtc_epilogue* second_ep, double* z_scale,
+                                 double* next_x_scale);
+
+/* Batch normalization folded into a per-column affine map (Section 4.5):
+ * a_j = gamma_j / sqrt(var_j + eps); col_scale_j = fp32(a_j * value_scale),
+ * col_shift_j = fp32(beta_j - a_j * mean_j).  Host arrays of n entries. */
+qgtc_status qgtc_fold_batchnorm(const double* gamma, const double* beta, const double* mean,
+                                const double* var, double eps, double value_scale, int32_t n,
+                                float* col_scale, float* col_shift);
 
 /* Library version, major*10000 + minor*100 + patch. */
 int32_t qgtc_version(void);

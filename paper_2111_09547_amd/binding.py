@@ -47,13 +47,39 @@ class _TileMapC(C.Structure):
                 ("nnz_tiles", C.c_void_p), ("deg", C.c_void_p)]
 
 
+class _TuningC(C.Structure):
+    _fields_ = [("update_path", C.c_int32), ("agg_xcd_run", C.c_int32),
+                ("layer_path", C.c_int32), ("layer_ksplit", C.c_int32)]
+
+
 class _EpilogueC(C.Structure):
     _fields_ = [("mode", C.c_int32), ("relu", C.c_int32), ("self_term", C.c_int32),
                 ("rq_nbits", C.c_int32), ("rq_lo", C.c_int32), ("rq_inv_scale", C.c_float),
                 ("cc", C.c_double), ("rs", C.c_double), ("l0a", C.c_double),
                 ("l0b", C.c_double), ("ck", C.c_double), ("cs", C.c_double),
                 ("row_i", C.c_void_p), ("row_l", C.c_void_p), ("col_i", C.c_void_p),
-                ("col_scale", C.c_void_p), ("col_shift", C.c_void_p)]
+                ("col_scale", C.c_void_p), ("col_shift", C.c_void_p),
+                ("tuning", C.POINTER(_TuningC))]
+
+
+class _PlanInC(C.Structure):
+    _fields_ = [("rows", C.c_int32), ("in_cols", C.c_int32), ("out_cols", C.c_int32),
+                ("s", C.c_int32), ("t", C.c_int32), ("n_tile_rows", C.c_int32),
+                ("a_cols", C.c_int32), ("reserved", C.c_int32), ("nnz_tiles", C.c_int64 * 3)]
+
+
+class _PlanOutC(C.Structure):
+    _fields_ = [("tile_kbits", C.c_int32), ("fused", C.c_int32), ("update_path", C.c_int32),
+                ("ksplit", C.c_int32), ("est_us_aggregate_first", C.c_double),
+                ("est_us_update_first", C.c_double)]
+
+
+class _LayerSpecC(C.Structure):
+    _fields_ = [("s", C.c_int32), ("t", C.c_int32), ("in_cols", C.c_int32), ("order", C.c_int32),
+                ("self_term", C.c_int32), ("last", C.c_int32), ("batchnorm", C.c_int32),
+                ("reserved", C.c_int32), ("x_lo", C.c_double), ("x_scale", C.c_double),
+                ("w_lo", C.c_double), ("w_hi", C.c_double), ("agg_hi", C.c_double),
+                ("out_hi", C.c_double)]
 
 
 _lib = None
@@ -95,7 +121,13 @@ def lib():
                                  P(_EpilogueC), vp, sz, vp, i64, vp]),
         "qgtc_layer_static": (C.c_int, [P(_BitsC), P(_TileMapC), P(_BitsC), P(_BitsC), P(_EpilogueC),
                                         P(_EpilogueC), vp, i64, vp]),
-        "qgtc_set_option": (C.c_int, [i32, i32]),
+        "qgtc_tile_stats": (C.c_int, [P(_BitsC), vp, vp]),
+        "qgtc_plan_layer": (C.c_int, [P(_PlanInC), P(_PlanOutC)]),
+        "qgtc_quant_inv_scale": (C.c_float, [C.c_double, C.c_double, i32]),
+        "qgtc_layer_epilogues": (C.c_int, [P(_LayerSpecC), P(_EpilogueC), P(_EpilogueC),
+                                          P(C.c_double), P(C.c_double)]),
+        "qgtc_fold_batchnorm": (C.c_int, [P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double),
+                                         C.c_double, C.c_double, i32, P(C.c_float), P(C.c_float)]),
         "qgtc_probe_popcount": (C.c_int, [i32, i32, i32, C.c_void_p, C.c_void_p]),
         "qgtc_prof_enable": (C.c_int, [i32]),
         "qgtc_prof_reset": (C.c_int, []),
@@ -159,6 +191,15 @@ class TileMap:
 
 
 @dataclass
+class Tuning:
+    """Per-call choices that only affect speed (qgtc_tuning); zeros leave them to the library."""
+    update_path: int = 0      # UPDATE_AUTO / UPDATE_POPCOUNT / UPDATE_MATRIX_CORES
+    agg_xcd_run: int = 0
+    layer_path: int = 0       # LAYER_FUSED / LAYER_TWO_KERNELS
+    layer_ksplit: int = 0
+
+
+@dataclass
 class Epilogue:
     mode: int = OUT_I32
     relu: bool = False
@@ -177,7 +218,7 @@ class Epilogue:
     col_i: torch.Tensor | None = None
     col_scale: torch.Tensor | None = None      # fp32 [cols]: per-column affine (folded batch norm)
     col_shift: torch.Tensor | None = None
-    _keep: list = field(default_factory=list, repr=False)
+    tuning: Tuning | None = None
 
     def to_c(self) -> _EpilogueC:
         def ptr(t):
@@ -190,10 +231,22 @@ class Epilogue:
                 return None
             assert t.dtype == torch.float32 and t.is_contiguous() and t.is_cuda
             return t.data_ptr()
+        tn = None
+        if self.tuning is not None:
+            t = self.tuning
+            tn = C.pointer(_TuningC(t.update_path, t.agg_xcd_run, t.layer_path, t.layer_ksplit))
+        # (the structure keeps the pointed-to tuning alive)
         return _EpilogueC(self.mode, int(self.relu), int(self.self_term), self.rq_nbits,
                           self.rq_lo, self.rq_inv_scale, self.cc, self.rs, self.l0a,
                           self.l0b, self.ck, self.cs, ptr(self.row_i), ptr(self.row_l),
-                          ptr(self.col_i), fptr(self.col_scale), fptr(self.col_shift))
+                          ptr(self.col_i), fptr(self.col_scale), fptr(self.col_shift), tn)
+
+    @staticmethod
+    def from_c(c: "_EpilogueC") -> "Epilogue":
+        """The scalar fields of a C epilogue (pointer fields stay unset)."""
+        return Epilogue(mode=c.mode, relu=bool(c.relu), self_term=bool(c.self_term), rq_nbits=c.rq_nbits,
+                        rq_lo=c.rq_lo, rq_inv_scale=c.rq_inv_scale, cc=c.cc, rs=c.rs, l0a=c.l0a, l0b=c.l0b,
+                        ck=c.ck, cs=c.cs)
 
 
 def describe(rows: int, cols: int, nbits: int, layout: int, block_rows: int = 0):
@@ -337,16 +390,59 @@ def qgtc_layer_static(A: Bits, tmap: TileMap | None, X: Bits, W: Bits, agg_ep: E
     return res
 
 
-OPT_UPDATE_PATH = 0
-OPT_AGG_XCD_RUN = 1
-OPT_LAYER_PATH = 2
-OPT_LAYER_KSPLIT = 3
 LAYER_FUSED, LAYER_TWO_KERNELS = 0, 1
 UPDATE_AUTO, UPDATE_POPCOUNT, UPDATE_MATRIX_CORES = 0, 1, 2
 
 
-def qgtc_set_option(option: int, value: int):
-    _check(lib().qgtc_set_option(option, value), "qgtc_set_option")
+def qgtc_tile_stats(A: Bits, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Device int32[4]: non-zero tiles of A at 16 x 32, 16 x 64, 16 x 128, and its rows of tiles."""
+    if out is None:
+        out = torch.empty(4, dtype=torch.int32, device=A.words.device)
+    assert out.dtype == torch.int32 and out.is_contiguous() and out.numel() >= 4
+    _check(lib().qgtc_tile_stats(C.byref(A.c), C.c_void_p(out.data_ptr()), _stream()), "qgtc_tile_stats")
+    return out
+
+
+def qgtc_plan_layer(rows: int, in_cols: int, out_cols: int, s: int, t: int, n_tile_rows: int = 0,
+                    a_cols: int = 0, nnz_tiles=(0, 0, 0)) -> dict:
+    """The library's selector for one layer (host-only); nnz_tiles: the first three numbers
+    of qgtc_tile_stats."""
+    pin = _PlanInC(rows, in_cols, out_cols, s, t, n_tile_rows, a_cols, 0, (C.c_int64 * 3)(*[int(v) for v in nnz_tiles]))
+    pout = _PlanOutC()
+    _check(lib().qgtc_plan_layer(C.byref(pin), C.byref(pout)), "qgtc_plan_layer")
+    return {k: getattr(pout, k) for k, _ in _PlanOutC._fields_}
+
+
+def qgtc_quant_inv_scale(lo: float, hi: float, nbits: int) -> float:
+    """fp32(2^nbits / (hi - lo)) as the library forms it for Eq. (2)."""
+    return float(lib().qgtc_quant_inv_scale(float(lo), float(hi), int(nbits)))
+
+
+def qgtc_layer_epilogues(s: int, t: int, in_cols: int, x_lo: float, x_scale: float, w_range, agg_hi: float,
+                         out_hi: float | None, self_term: bool = False, last: bool = False,
+                         batchnorm: bool = False, update_first: bool = False):
+    """(first_ep, second_ep, z_scale, next_x_scale) of one layer of a stack: the scalar
+    fields of the two epilogues as the library's helper sets them; the caller adds the
+    device vectors (row_l, col_i, col_scale, col_shift)."""
+    spec = _LayerSpecC(s, t, in_cols, int(update_first), int(self_term), int(last), int(batchnorm), 0,
+                       float(x_lo), float(x_scale), float(w_range[0]), float(w_range[1]), float(agg_hi),
+                       float(out_hi) if out_hi is not None else 0.0)
+    e1, e2 = _EpilogueC(), _EpilogueC()
+    zs, nx = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().qgtc_layer_epilogues(C.byref(spec), C.byref(e1), C.byref(e2), C.byref(zs), C.byref(nx)),
+           "qgtc_layer_epilogues")
+    return Epilogue.from_c(e1), Epilogue.from_c(e2), zs.value, nx.value
+
+
+def qgtc_fold_batchnorm(gamma, beta, mean, var, eps: float, value_scale: float):
+    """(col_scale, col_shift) as host float32 tensors: a batch normalization folded into a
+    per-column affine map acting on value_scale * accumulator."""
+    n = len(gamma)
+    arr = lambda v: (C.c_double * n)(*[float(x) for x in v])
+    cs, ch = (C.c_float * n)(), (C.c_float * n)()
+    _check(lib().qgtc_fold_batchnorm(arr(gamma), arr(beta), arr(mean), arr(var), float(eps), float(value_scale),
+                                     n, cs, ch), "qgtc_fold_batchnorm")
+    return torch.tensor(list(cs), dtype=torch.float32), torch.tensor(list(ch), dtype=torch.float32)
 
 
 def qgtc_probe_popcount(workgroups: int, waves_per_workgroup: int, iters: int, sink: torch.Tensor):

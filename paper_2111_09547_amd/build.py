@@ -13,7 +13,7 @@ LIB_DIR = os.path.join(PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libqgtc.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["api.hip", "pack.hip", "host_pack.hip", "tilemap.hip", "aggregate.hip", "layer.hip", "update.hip", "update_mfma.hip", "probe.hip"]
+SOURCES = ["api.hip", "plan.hip", "pack.hip", "host_pack.hip", "tilemap.hip", "aggregate.hip", "layer.hip", "update.hip", "update_mfma.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",

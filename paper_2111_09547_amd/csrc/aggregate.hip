@@ -290,20 +290,24 @@ extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* m
   const bool square = A->block_rows > 0 || A->rows == A->cols;
   st = make_epilogue(ep, out, ld_out, A->rows, X->cols, QGTC_LEFT, square, &p.ep);
   if (st != QGTC_OK) return st;
+  st = check_tuning(ep->tuning);
+  if (st != QGTC_OK) return st;
   if (A->rows == 0 || X->cols == 0) return QGTC_OK;
 
   p.kslices = agg_kslices(X->cols, p.tile_words);
   p.n_cg = cdiv(X->cols, 64);
   p.nblocks = (uint32_t)p.n_cg * (uint32_t)p.n_tile_rows;
   // few waves: let the four waves of a workgroup split each tile list
-  p.ksplit = p.nblocks >= 3072u ? 1 : 4;
+  // (fewer than the wave slots of the device: CUs x 4 SIMDs x waves per SIMD)
+  const unsigned slots = (unsigned)(device_compute_units() * 4 * agg_waves_per_simd(X->nbits > 8 ? 8 : X->nbits));
+  p.ksplit = p.nblocks >= slots ? 1 : 4;
   // Each XCD takes runs of `chunk` consecutive workgroups, run k going to XCD
   // k % 8.  A run covers all column groups of a few neighbouring tile rows, which
   // read the same word rows of X from the XCD's L2 (with few tiles per row these
   // are the diagonal tiles); dealing short runs round-robin spreads the rows of
   // one subgraph over all XCDs, so a subgraph that holds far more tiles than the
   // others (the hubs of a power-law graph) does not leave seven XCDs idle.
-  agg_set_dealing(&p, p.n_cg);
+  agg_set_dealing(&p, p.n_cg, ep->tuning ? ep->tuning->agg_xcd_run : 0);
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_AGGREGATE, s);

@@ -126,17 +126,15 @@ int device_compute_units() {
   return g_device_cus[dev];
 }
 
-// ---- library options ---------------------------------------------------------------
-namespace {
-int g_update_path = 0;
-int g_agg_chunk = 0;
-int g_layer_path = 0;
-int g_layer_ksplit = 0;
+qgtc_status check_tuning(const qgtc_tuning* t) {
+  if (!t) return QGTC_OK;
+  if (t->update_path < 0 || t->update_path > 2) return QGTC_ERR_UNSUPPORTED;
+  if (t->layer_path < 0 || t->layer_path > 1) return QGTC_ERR_UNSUPPORTED;
+  if (t->layer_ksplit != 0 && t->layer_ksplit != 1 && t->layer_ksplit != 2 && t->layer_ksplit != 4)
+    return QGTC_ERR_UNSUPPORTED;
+  if (t->agg_xcd_run > 4096) return QGTC_ERR_UNSUPPORTED;
+  return QGTC_OK;
 }
-int update_path_option() { return g_update_path; }
-int agg_chunk_option() { return g_agg_chunk; }
-int layer_path_option() { return g_layer_path; }
-int layer_ksplit_option() { return g_layer_ksplit; }
 
 // ---- event-based kernel timing ------------------------------------------------
 namespace {
@@ -196,31 +194,7 @@ extern "C" const char* qgtc_status_string(qgtc_status s) {
   return "unknown status";
 }
 
-extern "C" int32_t qgtc_version(void) { return 101; }
-
-extern "C" qgtc_status qgtc_set_option(int32_t option, int32_t value) {
-  if (option == QGTC_OPT_UPDATE_PATH) {
-    if (value < 0 || value > 2) return QGTC_ERR_UNSUPPORTED;
-    g_update_path = value;
-    return QGTC_OK;
-  }
-  if (option == QGTC_OPT_LAYER_PATH) {
-    if (value < 0 || value > 1) return QGTC_ERR_UNSUPPORTED;
-    g_layer_path = value;
-    return QGTC_OK;
-  }
-  if (option == QGTC_OPT_LAYER_KSPLIT) {
-    if (value != 0 && value != 1 && value != 2 && value != 4) return QGTC_ERR_UNSUPPORTED;
-    g_layer_ksplit = value;
-    return QGTC_OK;
-  }
-  if (option == QGTC_OPT_AGG_XCD_RUN) {
-    if (value > 4096) return QGTC_ERR_UNSUPPORTED;
-    g_agg_chunk = value;
-    return QGTC_OK;
-  }
-  return QGTC_ERR_UNSUPPORTED;
-}
+extern "C" int32_t qgtc_version(void) { return 200; }
 
 extern "C" size_t qgtc_describe(qgtc_bits* d, int32_t rows, int32_t cols, int32_t nbits, int32_t layout,
                                 int32_t block_rows) {
@@ -301,6 +275,8 @@ extern "C" qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map, 
   st = check_bits(W, W->layout == QGTC_RIGHT_BYTES ? QGTC_RIGHT_BYTES : QGTC_RIGHT);
   if (st != QGTC_OK) return st;
   if (W->rows != X->cols) return QGTC_ERR_SHAPE;
+  st = check_tuning(upd_ep->tuning);
+  if (st != QGTC_OK) return st;
   EpiParams probe;
   st = make_epilogue(upd_ep, out, ld_out, A->rows, W->cols, QGTC_RIGHT, false, &probe);
   if (st != QGTC_OK) return st;
@@ -311,7 +287,9 @@ extern "C" qgtc_status qgtc_layer(const qgtc_bits* A, const qgtc_tile_map* map, 
   if (st != QGTC_OK || done) return st;
   if (W->layout == QGTC_RIGHT_BYTES) return QGTC_ERR_UNSUPPORTED;   // only the fused kernel reads bytes
 
-  st = qgtc_aggregate(A, map, X, agg_ep, &Y, 0, stream);
+  qgtc_epilogue agg = *agg_ep;                       // the call's tuning is upd_ep's
+  agg.tuning = upd_ep->tuning;
+  st = qgtc_aggregate(A, map, X, &agg, &Y, 0, stream);
   if (st != QGTC_OK) return st;
   qgtc_epilogue upd = *upd_ep;
   if (upd.mode == QGTC_OUT_F32 && upd.row_i == nullptr && upd.rs != 0.0) {

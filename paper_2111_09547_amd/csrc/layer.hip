@@ -414,12 +414,13 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
                         void* workspace, size_t workspace_bytes, void* out, int64_t ld_out,
                         hipStream_t stream, bool* done) {
   *done = false;
-  if (layer_path_option() == 1 && W && W->layout != QGTC_RIGHT_BYTES) return QGTC_OK;
   if (!A || !X || !W || !agg_ep || !upd_ep || !workspace || !out) return QGTC_OK;
+  const qgtc_tuning* tn = upd_ep->tuning;
+  if (tn && tn->layer_path == 1 && W->layout != QGTC_RIGHT_BYTES) return QGTC_OK;
   // what the kernel covers; everything else takes the two-kernel path
-  if (X->nbits > 8 || W->nbits > 8 || agg_ep->rq_nbits < 1 || agg_ep->rq_nbits > 8) return QGTC_OK;
+  if (!plan_fused_applies(X->cols, W->cols, X->nbits, W->nbits)) return QGTC_OK;
+  if (agg_ep->rq_nbits < 1 || agg_ep->rq_nbits > 8) return QGTC_OK;
   if (upd_ep->mode == QGTC_OUT_BITS && upd_ep->rq_nbits > 8) return QGTC_OK;
-  if (X->cols < 1 || X->cols > 1024 || W->cols < 1 || W->cols > 256) return QGTC_OK;
   if (A->rows < 1) return QGTC_OK;
   const bool w_bytes = W->layout == QGTC_RIGHT_BYTES;
   if (!w_bytes && workspace_bytes < layer_fused_workspace_bytes(X->cols, W->cols)) return QGTC_OK;
@@ -446,22 +447,18 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   a.kslices = agg_kslices(X->cols, a.tile_words);
   a.n_cg = cdiv(X->cols, 64);
   a.nblocks = (uint32_t)a.n_tile_rows;
-  p.cgw = a.n_cg <= 4 ? a.n_cg : (a.n_cg % 3 == 0 ? 3 : 4);
+  // waves side by side over the column groups, and waves that split each tile list
+  int cgw = 1, ksplit = 1;
+  plan_layer_shape(a.n_tile_rows, X->cols, X->nbits, &cgw, &ksplit);
+  p.cgw = cgw;
   p.n_pass = cdiv(a.n_cg, p.cgw);
-  // Waves that split each tile list: as many as it takes to put ~3000 waves on the
-  // chip when there are few tile rows; with two column groups, workgroups of four
-  // waves measured faster than pairs, so the lists are split in two there as well.
-  a.ksplit = 1;
-  const int opt_k = layer_ksplit_option();
-  if (opt_k > 0) {
-    a.ksplit = opt_k;
+  a.ksplit = ksplit;
+  if (tn && tn->layer_ksplit > 0) {
+    a.ksplit = tn->layer_ksplit;
     while (p.cgw * a.ksplit > 4 && a.ksplit > 1) a.ksplit >>= 1;
-  } else {
-    while ((int64_t)a.n_tile_rows * p.cgw * a.ksplit < 3072 && p.cgw * a.ksplit * 2 <= 4) a.ksplit *= 2;
-    if (p.cgw == 2 && a.ksplit == 1) a.ksplit = 2;
   }
   const unsigned nw = (unsigned)(p.cgw * a.ksplit);
-  agg_set_dealing(&a, 1);
+  agg_set_dealing(&a, 1, tn ? tn->agg_xcd_run : 0);
 
   p.h = W->cols;
   p.n_nt_w = cdiv(W->cols, 16);

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "qgtc.h"
+#include "qgtc_bench.h"
 
 namespace qgtc {
 
@@ -94,19 +95,16 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
                         void* workspace, size_t workspace_bytes, void* out, int64_t ld_out,
                         hipStream_t stream, bool* done);
 size_t layer_fused_workspace_bytes(int32_t in_cols, int32_t out_cols);
-// 0 = fused kernel whenever it applies, 1 = always aggregate and update separately
-int layer_path_option();
-// 0 = automatic, 1 / 2 / 4 = waves that split a tile list in the fused layer kernel
-int layer_ksplit_option();
+// The selector's rules (plan.hip), shared by qgtc_plan_layer and the entry points.
+bool plan_fused_applies(int in_cols, int out_cols, int s, int t);
+int plan_update_path(int s, int t);                 // 1 popcount, 2 matrix cores
+void plan_layer_shape(int n_tile_rows, int in_cols, int s, int* cgw, int* ksplit);
+// Range check of a caller's tuning (NULL is fine).
+qgtc_status check_tuning(const qgtc_tuning* t);
 
 // int8 matrix-core variant of the update for s, t <= 8 (update_mfma.hip).
 bool update_mfma_eligible(const UpdParams& p);
 qgtc_status update_mfma_launch(const UpdParams& p, hipStream_t stream);
-// 0 = choose by measured crossover, 1 = popcount only, 2 = matrix cores whenever eligible
-int update_path_option();
-// tile rows per run of workgroups dealt to one XCD by the aggregation; 0 = default,
-// < 0 = one contiguous range per XCD
-int agg_chunk_option();
 
 // ---- device side -------------------------------------------------------------
 #if defined(__HIPCC__)

@@ -174,6 +174,50 @@ __global__ __launch_bounds__(256) void degree_kernel(const MapParams p) {
   if (lane == 0) p.deg[r] = cnt;
 }
 
+// Non-zero tiles at 16 x 32, 16 x 64 and 16 x 128 in one pass: one wave per row of tiles,
+// lane <-> (row = lane % 16, one of four consecutive 128-bit groups = lane / 16).  A ballot
+// per word of the group tells, for each of the four groups, whether any of the 16 rows has
+// a bit there; the three counts follow from the four answers.
+__global__ __launch_bounds__(256) void tile_stats_kernel(const MapParams p, int32_t* counts) {
+  const int lane = threadIdx.x & 63;
+  const int tr = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tr >= p.n_tile_rows) return;               // whole wave
+  const int r = tr * 16 + (lane & 15);
+  const int g = lane >> 4;
+  const bool r_ok = r < p.rows;
+  const uint32_t* row = p.A + (int64_t)(r_ok ? r : 0) * p.lda;
+  const int n128 = (p.n_words + 3) >> 2;          // rows are padded to 128 bits with zeros
+  int c32 = 0, c64 = 0, c128 = 0;
+  for (int t0 = 0; t0 < n128; t0 += 4) {
+    const int tc = t0 + g;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (r_ok && tc < n128) v = *reinterpret_cast<const uint4*>(row + 4 * tc);
+    const unsigned long long mx = __builtin_amdgcn_ballot_w64(v.x != 0u);
+    const unsigned long long my = __builtin_amdgcn_ballot_w64(v.y != 0u);
+    const unsigned long long mz = __builtin_amdgcn_ballot_w64(v.z != 0u);
+    const unsigned long long mw = __builtin_amdgcn_ballot_w64(v.w != 0u);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {                 // wave-uniform arithmetic
+      const int bx = ((mx >> (16 * k)) & 0xffffull) != 0ull, by = ((my >> (16 * k)) & 0xffffull) != 0ull;
+      const int bz = ((mz >> (16 * k)) & 0xffffull) != 0ull, bw = ((mw >> (16 * k)) & 0xffffull) != 0ull;
+      c32 += bx + by + bz + bw;
+      c64 += (bx | by) + (bz | bw);
+      c128 += bx | by | bz | bw;
+    }
+  }
+  if (lane == 0) {
+    atomicAdd(&counts[0], c32);
+    atomicAdd(&counts[1], c64);
+    atomicAdd(&counts[2], c128);
+  }
+}
+
+// Start values of the four counters (a kernel, so that the call can be recorded into a HIP graph).
+__global__ void tile_stats_init_kernel(int32_t* counts, int32_t n_tile_rows) {
+  if (threadIdx.x < 3) counts[threadIdx.x] = 0;
+  if (threadIdx.x == 3) counts[3] = n_tile_rows;
+}
+
 bool tile_shape_ok(int tile_rows, int tile_kbits) {
   const bool r = tile_rows == 8 || tile_rows == 16 || tile_rows == 32 || tile_rows == 64;
   const bool k = tile_kbits == 32 || tile_kbits == 64 || tile_kbits == 128 || tile_kbits == 256 ||
@@ -253,6 +297,28 @@ extern "C" qgtc_status qgtc_build_tile_map(const qgtc_bits* A, const qgtc_tile_m
   if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
   if (p.rows > 0 && !(fused && p.n_tile_rows > 0 && p.n_tile_cols > 0)) {
     hipLaunchKernelGGL(degree_kernel, dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p);
+    if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
+  }
+  return QGTC_OK;
+}
+
+extern "C" qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void* stream) {
+  if (!A || !counts) return QGTC_ERR_NULL;
+  qgtc_status st = check_adjacency(A);
+  if (st != QGTC_OK) return st;
+  if (((uintptr_t)counts & 3u) != 0) return QGTC_ERR_ALIGN;
+  MapParams p{};
+  p.A = A->data;
+  p.lda = A->ld_words;
+  p.rows = A->rows;
+  p.n_words = cdiv(A->cols, 32);
+  p.n_tile_rows = cdiv(A->rows, 16);
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  ProfScope prof(QGTC_KERNEL_TILE_MAP, s);
+  hipLaunchKernelGGL(tile_stats_init_kernel, dim3(1), dim3(64), 0, s, counts, p.n_tile_rows);
+  if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
+  if (p.n_tile_rows > 0) {
+    hipLaunchKernelGGL(tile_stats_kernel, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p, counts);
     if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
   }
   return QGTC_OK;

@@ -211,6 +211,8 @@ extern "C" qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W, const
   if (Y->rows == 0 || W->cols == 0) return QGTC_OK;
   st = make_epilogue(ep, out, ld_out, Y->rows, W->cols, QGTC_RIGHT, false, &p.ep);
   if (st != QGTC_OK) return st;
+  st = check_tuning(ep->tuning);
+  if (st != QGTC_OK) return st;
 
   p.n_row_waves = cdiv(Y->rows, 64);
   // enough waves to fill 256 CUs x 4 SIMDs a few times over
@@ -226,12 +228,11 @@ extern "C" qgtc_status qgtc_update(const qgtc_bits* Y, const qgtc_bits* W, const
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_UPDATE, s);
-  // int8 matrix cores when the operands fit in bytes.  Measured on MI355X, they
-  // win from 2 x 2 bits upwards; 1-bit x 1-bit stays on the popcount kernel.
-  const int path = update_path_option();
+  // popcount kernel or int8 matrix cores: the caller's choice, else the selector's rule
+  int path = ep->tuning ? ep->tuning->update_path : 0;
+  if (path == 0) path = plan_update_path(Y->nbits, W->nbits);
   if (y_bytes) return update_mfma_eligible(p) ? update_mfma_launch(p, s) : QGTC_ERR_UNSUPPORTED;
-  if (path != 1 && update_mfma_eligible(p) && (path == 2 || Y->nbits * W->nbits >= 4))
-    return update_mfma_launch(p, s);
+  if (path == 2 && update_mfma_eligible(p)) return update_mfma_launch(p, s);
   const int b = Y->nbits > W->nbits ? Y->nbits : W->nbits;
   switch (b) {
     case 1: return dispatch_k<1>(p, hsplit, s);

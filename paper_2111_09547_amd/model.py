@@ -14,8 +14,7 @@ from . import binding as B
 
 def inv_scale(lo: float, hi: float, nbits: int) -> float:
     """fp32(2^nbits / (hi - lo)) as the library forms it for Eq. (2)."""
-    return float(torch.tensor(float(2 ** nbits) / (float(hi) - float(lo)),
-                              dtype=torch.float64).to(torch.float32))
+    return B.qgtc_quant_inv_scale(lo, hi, nbits)
 
 
 @dataclass
@@ -36,31 +35,20 @@ class BatchNorm:
     eps: float = 1e-5
 
 
-# Relative cost of one adjacency bit column by tile width (measured on configs 4 and 5: 64-bit
-# tiles cost what 128-bit tiles cost per bit, 32-bit tiles 1.0-1.4 times as much)
-TILE_COST = {128: 1.0, 64: 1.0, 32: 1.3}
-
-
-def choose_tile_kbits(A: "B.Bits") -> int:
-    """Tile width for the zero-tile map of a packed adjacency: the one with the least
-    executed work, non-zero tiles x tile width x TILE_COST; within 2 % the wider tile wins.
-    Narrow tiles skip more zeros (the paper's second kind of zero tiles, gaps inside a
-    subgraph, Section 6.3) but cost more per bit.  Builds the three maps and reads their
-    tile counts back (synchronizes)."""
-    cost = {}
-    for kb in (128, 64, 32):
-        m = B.qgtc_build_tile_map(A, 16, kb)
-        cost[kb] = int(m.nnz_tiles[0].item()) * kb * TILE_COST[kb]
-    best = 128
-    for kb in (64, 32):
-        if cost[kb] < 0.98 * cost[best]:
-            best = kb
-    return best
+def choose_tile_kbits(A: "B.Bits", d: int = 64, h: int = 64, s: int = 8, t: int = 8) -> int:
+    """Tile width for the zero-tile map of a packed adjacency, by the library's selector:
+    one pass over A counts its non-zero tiles at the three widths (qgtc_tile_stats), the
+    host reads the four numbers back once (this synchronizes) and qgtc_plan_layer picks the
+    width with the least executed work.  Narrow tiles skip more zeros (the paper's second
+    kind of zero tiles, gaps inside a subgraph, Section 6.3) but cost more per bit."""
+    counts = [int(v) for v in B.qgtc_tile_stats(A).cpu()]
+    plan = B.qgtc_plan_layer(A.rows, d, h, s, t, n_tile_rows=counts[3], a_cols=A.cols, nnz_tiles=counts[:3])
+    return plan["tile_kbits"]
 
 
 def fused_layer_applies(d: int, h: int, s: int, t: int) -> bool:
-    """The shapes and bit widths qgtc_layer runs as one kernel (see qgtc.h)."""
-    return 1 <= d <= 1024 and 1 <= h <= 256 and s <= 8 and t <= 8
+    """The shapes and bit widths qgtc_layer runs as one kernel (the selector's rule)."""
+    return bool(B.qgtc_plan_layer(16, d, h, s, t)["fused"])
 
 
 class QuantGNN:
@@ -74,8 +62,10 @@ class QuantGNN:
 
     def __init__(self, A_src, Ws, s: int, t: int, self_term: bool,
                  tile_kbits: int | str = 128, use_map: bool = True, block_rows: int = 0,
-                 weights_as_bytes: bool = True, update_first: bool = False, batchnorm=None):
+                 weights_as_bytes: bool = True, update_first: bool = False, batchnorm=None,
+                 tuning: "B.Tuning | None" = None):
         self.s, self.t = s, t
+        self.tuning = tuning           # per-call speed choices handed to qgtc_layer (None: the library's)
         # batchnorm: per layer None or a BatchNorm; it is folded into the layer's output
         # epilogue as a per-column affine map (no kernel of its own)
         self.batchnorm = list(batchnorm) if batchnorm is not None else [None] * len(Ws)
@@ -102,7 +92,7 @@ class QuantGNN:
         if tile_kbits == "auto":            # needs the packed adjacency: pack it now, choose once
             if self.A_src is not None:
                 B.qgtc_pack_bits(self.A_src, 1, B.LEFT, out=self.A)
-            self.tile_kbits = choose_tile_kbits(self.A)
+            self.tile_kbits = choose_tile_kbits(self.A, self.dims[0][0], self.dims[0][1], s, t)
         # Weights are cached in the form their layer's kernel reads: bytes in
         # matrix-core operand order where the fused layer kernel applies, bit planes
         # for the two-kernel path.
@@ -222,6 +212,13 @@ class QuantGNN:
                           rq_inv_scale=inv_scale(0.0, float(agg_hi), self.s),
                           self_term=self.self_term)
 
+    def _layer_eps(self, l: int, x_lo: float, x_scale: float, agg_hi, out_hi, last: bool):
+        """The two epilogues of layer l and the scales around it, from the library's helper."""
+        return B.qgtc_layer_epilogues(self.s, self.t, self.dims[l][0], x_lo, x_scale, self.w_ranges[l],
+                                      agg_hi, out_hi, self_term=self.self_term, last=last,
+                                      batchnorm=self.batchnorm[l] is not None and not last,
+                                      update_first=self.update_first)
+
     # -- update first ---------------------------------------------------------------------
     def _xl_view(self, which: int, cols: int) -> B.Bits:
         buf = self.xl_bufs[which]
@@ -245,7 +242,7 @@ class QuantGNN:
         else:
             xl = B.qgtc_pack_bits(X, self.s, B.LEFT, quant=x_range, out=self._xl_view(0, X.shape[1]))
         n_layers = len(self.W)
-        scale = (float(x_range[1]) - float(x_range[0])) / float(2 ** self.s)
+        x_scale = (float(x_range[1]) - float(x_range[0])) / float(2 ** self.s)
         for l, W in enumerate(self.W):
             d, h = self.dims[l]
             last = l == n_layers - 1
@@ -254,12 +251,9 @@ class QuantGNN:
                 p_hi = max(1, int(p32.max()))
             else:
                 p_hi = ranges[l].agg_hi
-            inv_p = inv_scale(0.0, float(p_hi), self.s)
-            pb = B.qgtc_update(xl, W, B.Epilogue(mode=B.OUT_BITS, rq_nbits=self.s, rq_lo=0,
-                                                 rq_inv_scale=inv_p),
-                               out=self._x_view(l & 1, h))
-            lo_w, hi_w = self.w_ranges[l]
-            scale = scale * ((hi_w - lo_w) / float(2 ** self.t)) / inv_p
+            # epilogue of X.W (requantize to s bits) - only its range is known while calibrating
+            upd_ep, _, _, _ = self._layer_eps(l, 0.0, x_scale, p_hi, 1.0, last=False)
+            pb = B.qgtc_update(xl, W, upd_ep, out=self._x_view(l & 1, h))
             out_hi = None
             if calibrating or (last and want_int):
                 z32 = B.qgtc_aggregate(self.A, self.map, pb,
@@ -275,38 +269,23 @@ class QuantGNN:
                 if calibrating:
                     return found
                 if not want_int:
-                    # codes read as pure scales (no zero points): out = scale * (A.Pq)
-                    B.qgtc_aggregate(self.A, self.map, pb,
-                                     B.Epilogue(mode=B.OUT_F32, cc=scale, self_term=self.self_term), out=out)
+                    # codes read as pure scales (no zero points): out = z_scale * (A.Pq)
+                    _, agg_ep, _, _ = self._layer_eps(l, 0.0, x_scale, p_hi, None, last=True)
+                    B.qgtc_aggregate(self.A, self.map, pb, agg_ep, out=out)
                 return out
-            inv_z = inv_scale(0.0, float(out_hi), self.s)
-            xl = B.qgtc_aggregate(self.A, self.map, pb,
-                                  B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0,
-                                             rq_inv_scale=inv_z, self_term=self.self_term),
-                                  out=self._xl_view((l + 1) & 1, h))
-            scale = scale / inv_z
+            _, agg_ep, _, x_scale = self._layer_eps(l, 0.0, x_scale, p_hi, out_hi, last=False)
+            xl = B.qgtc_aggregate(self.A, self.map, pb, agg_ep, out=self._xl_view((l + 1) & 1, h))
 
     def _bn_fold(self, l: int, value_scale: float):
-        """(col_scale, col_shift) of layer l's batch normalization acting on value_scale * C:
-        a_j = gamma_j / sqrt(var_j + eps), col_scale = a_j * value_scale, col_shift =
-        beta_j - a_j * mean_j, formed in fp64 and rounded once to fp32.  Cached per scale so
-        that a recorded pass allocates nothing."""
+        """(col_scale, col_shift) of layer l's batch normalization acting on value_scale * C
+        (qgtc_fold_batchnorm).  Cached per scale so that a recorded pass allocates nothing."""
         key = (l, float(value_scale))
         if key not in self._bn_cache:
-            import numpy as np
             bn = self.batchnorm[l]
-            g = np.asarray(bn.gamma, dtype=np.float64) / np.sqrt(np.asarray(bn.var, dtype=np.float64) + float(bn.eps))
-            a = (g * float(value_scale)).astype(np.float32)
-            b = (np.asarray(bn.beta, dtype=np.float64) - g * np.asarray(bn.mean, dtype=np.float64)).astype(np.float32)
+            a, b = B.qgtc_fold_batchnorm(bn.gamma, bn.beta, bn.mean, bn.var, bn.eps, value_scale)
             dv = self.A.words.device
-            self._bn_cache[key] = (torch.from_numpy(a).to(dv), torch.from_numpy(b).to(dv))
+            self._bn_cache[key] = (a.to(dv), b.to(dv))
         return self._bn_cache[key]
-
-    def _z_scale(self, l: int, x_scale: float, agg_hi) -> float:
-        """Real value of one unit of layer l's update accumulator (codes read as pure scales)."""
-        lo_w, hi_w = self.w_ranges[l]
-        sw = (hi_w - lo_w) / float(2 ** self.t)
-        return (x_scale / inv_scale(0.0, float(agg_hi), self.s)) * sw
 
     # -- calibration: integer maxima per layer, from int32 outputs ---------------------
     def calibrate(self, X: torch.Tensor, x_range):
@@ -330,36 +309,22 @@ class QuantGNN:
             if last:
                 ranges.append(LayerRanges(agg_hi, None))
                 break
-            ep = B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0)
+            _, _, z_scale, _ = self._layer_eps(l, 0.0, x_scale, agg_hi, 1.0, last=False)
+            ca = cb = None
             if self.batchnorm[l] is not None:
                 # range of the normalized value, [0, max(a_j * z + b_j)]
-                ca, cb = self._bn_fold(l, self._z_scale(l, x_scale, agg_hi))
+                ca, cb = self._bn_fold(l, z_scale)
                 v = z32.to(torch.float64) * ca.to(torch.float64)[None, :] + cb.to(torch.float64)[None, :]
                 out_hi = max(1e-6, float(v.max()))
-                ep.col_scale, ep.col_shift = ca, cb
-                x_scale = 1.0 / inv_scale(0.0, out_hi, self.s)
             else:
                 out_hi = max(1, int(z32.max()))
-                x_scale = self._z_scale(l, x_scale, agg_hi) / inv_scale(0.0, float(out_hi), self.s)
             ranges.append(LayerRanges(agg_hi, out_hi))
-            ep.rq_inv_scale = inv_scale(0.0, float(out_hi), self.s)
+            _, ep, _, x_scale = self._layer_eps(l, 0.0, x_scale, agg_hi, out_hi, last=False)
+            ep.col_scale, ep.col_shift = ca, cb
             xb = B.qgtc_update(yb, W, ep, out=self._x_view((l + 1) & 1, self.dims[l][1]))
         return ranges
 
     # -- forward ---------------------------------------------------------------------
-    def last_layer_dequant(self, l: int, x_lo: float, x_scale: float, agg_hi: int,
-                           yq_rowsum: torch.Tensor) -> B.Epilogue:
-        """Epilogue that turns the last update's accumulators into the real
-        product of the dequantized operands: Y^ = l0[v] + sl*Yq, W^ = lo_w + sw*Wq."""
-        d = self.dims[l][0]
-        lo_w, hi_w = self.w_ranges[l]
-        sw = (hi_w - lo_w) / float(2 ** self.t)
-        inv = inv_scale(0.0, float(agg_hi), self.s)
-        sl = x_scale / inv
-        return B.Epilogue(mode=B.OUT_F32, cc=sl * sw, rs=sl * lo_w, row_i=yq_rowsum,
-                          l0a=(x_lo if self.self_term else 0.0), l0b=x_lo, row_l=self.deg,
-                          ck=lo_w * d, cs=sw, col_i=self.w_colsum[l])
-
     def forward(self, X: torch.Tensor, x_range, ranges, out: torch.Tensor | None = None,
                 want_int: bool = False, streams: int = 1, x_packed: bool = False,
                 x_bits: B.Bits | None = None):
@@ -436,30 +401,27 @@ class QuantGNN:
     def _run_layers(self, r0, r1, A, tmap, deg, xb, x_range, ranges, out, want_int, workspace):
         """All layers on rows [r0, r1) (whole subgraphs), on the current stream."""
         n_layers = len(self.W)
+        # the first layer's codes stand for x_lo + x_scale * code; behind a hidden layer the
+        # codes are read as pure scales (x_lo = 0)
         x_lo = float(x_range[0])
         x_scale = (float(x_range[1]) - float(x_range[0])) / float(2 ** self.s)
         for l, W in enumerate(self.W):
             r = ranges[l]
-            agg_ep = self._agg_ep(r.agg_hi)
-            if l < n_layers - 1:
-                ep = B.Epilogue(mode=B.OUT_BITS, relu=True, rq_nbits=self.s, rq_lo=0,
-                                rq_inv_scale=inv_scale(0.0, float(r.out_hi), self.s))
-                # hidden activations are read as pure scales: x^ = Xq * step
-                z_scale = self._z_scale(l, x_scale, r.agg_hi)
+            last = l == n_layers - 1
+            agg_ep, ep, z_scale, x_next = self._layer_eps(l, x_lo, x_scale, r.agg_hi, r.out_hi, last)
+            ep.tuning = self.tuning
+            if not last:
                 if self.batchnorm[l] is not None:
                     ep.col_scale, ep.col_shift = self._bn_fold(l, z_scale)
-                    x_scale = 1.0 / inv_scale(0.0, float(r.out_hi), self.s)
-                else:
-                    x_scale = z_scale / inv_scale(0.0, float(r.out_hi), self.s)
                 xb = B.qgtc_layer(A, tmap, xb, W, agg_ep, ep, workspace,
                                   out=self._x_rows((l + 1) & 1, self.dims[l][1], r0, r1))
-                x_lo = 0.0
+                x_lo, x_scale = 0.0, x_next
             elif want_int:
-                B.qgtc_layer(A, tmap, xb, W, agg_ep, B.Epilogue(mode=B.OUT_I32), workspace, out=out)
+                B.qgtc_layer(A, tmap, xb, W, agg_ep, B.Epilogue(mode=B.OUT_I32, tuning=self.tuning), workspace,
+                             out=out)
             else:
                 # row_i = None: the layer takes the row sums of its own requantized Y
-                ep = self.last_layer_dequant(l, x_lo, x_scale, r.agg_hi, None)
-                ep.row_l = deg
+                ep.row_l, ep.col_i = deg, self.w_colsum[l]
                 if self.batchnorm[l] is not None:      # acts on the real output value
                     ep.col_scale, ep.col_shift = self._bn_fold(l, 1.0)
                 B.qgtc_layer(A, tmap, xb, W, agg_ep, ep, workspace, out=out)

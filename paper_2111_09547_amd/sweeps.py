@@ -15,8 +15,14 @@
   transfer host -> device cost of a batch (Section 4.6): dense fp32 adjacency + fp32
            features in two copies against the low-bit compound buffer packed on the host
            and copied once (configs 4 and 5; pinned memory on both sides)
+  gate     the stand-alone update Y.W as s*t one-bit products (AND + popcount, Algorithm 1's
+           second loop) against the same product on the int8 matrix cores, s = t = 1..8, at
+           the update shapes of configs 4 and 5, int32 and low-bit outputs: the measurement
+           behind the selector's rule for the update (qgtc_plan_layer)
+  tiles    cost of an adjacency bit by tile width (16 x 32 / 64 / 128) on configs 4 and 5:
+           the measurement behind the selector's tile-width rule
 
-Run:  python -m paper_2111_09547_amd.sweeps [table3|config3|config5|sizes|reuse|transfer ...]
+Run:  python -m paper_2111_09547_amd.sweeps [table3|config3|config5|sizes|reuse|transfer|gate|tiles ...]
 Prints one JSON line per measurement and a markdown table per sweep."""
 from __future__ import annotations
 
@@ -252,12 +258,104 @@ def transfer():
               f"{r['host_pack_us_16_threads']} us |")
 
 
+def _kernel_us(fn, kind, n=10, warm=3):
+    """Mean GPU time per launch, from the library's events around each launch."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    q.qgtc_prof_enable(True)
+    q.qgtc_prof_reset()
+    for _ in range(n):
+        fn()
+    torch.cuda.synchronize()
+    ms, launches = q.qgtc_prof_read(kind)
+    q.qgtc_prof_enable(False)
+    q.qgtc_prof_reset()
+    return ms * 1e3 / max(launches, 1)
+
+
+GATE_SHAPES = ((65536, 64, 64), (65536, 128, 64), (262144, 512, 16))
+
+
+def gate():
+    """Each case: 3 warm-up and 10 timed launches of one kernel, in the order printed."""
+    gen = torch.Generator(device="cuda").manual_seed(12)
+    rows = []
+    for (n, d, h) in GATE_SHAPES:
+        for s in range(1, 9):
+            yq = torch.randint(0, 2 ** s, (n, d), device="cuda", dtype=torch.int32, generator=gen)
+            wq = torch.randint(0, 2 ** s, (d, h), device="cuda", dtype=torch.int32, generator=gen)
+            yb = q.qgtc_pack_bits(yq, s, q.LEFT, out=q.alloc_bits(n, d, s, q.LEFT, ld_words=-(-d // 32)))
+            wb = q.qgtc_pack_bits(wq, s, q.RIGHT)
+            out_i = torch.empty((n, h), dtype=torch.int32, device="cuda")
+            out_b = q.alloc_bits(n, h, s, q.RIGHT)
+            rec = {"sweep": "gate", "N": n, "D": d, "H": h, "bits": s}
+            for path, name in ((q.UPDATE_POPCOUNT, "popcount"), (q.UPDATE_MATRIX_CORES, "mfma")):
+                tn = q.Tuning(update_path=path)
+                ep_i = q.Epilogue(mode=q.OUT_I32, tuning=tn)
+                ep_b = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=s, rq_lo=0, rq_inv_scale=1e-3, tuning=tn)
+                t_i = _kernel_us(lambda: q.qgtc_update(yb, wb, ep_i, out=out_i), q.KERNEL_UPDATE)
+                t_b = _kernel_us(lambda: q.qgtc_update(yb, wb, ep_b, out=out_b), q.KERNEL_UPDATE)
+                rec[f"us_{name}_int32"] = round(t_i, 1)
+                rec[f"us_{name}_bits"] = round(t_b, 1)
+                # bytes: the planes of Y once, W, and the output
+                rec[f"gbps_{name}_int32"] = round((n * d * s / 8 + d * h * s / 8 + n * h * 4) / t_i / 1e3, 1)
+                rec[f"gbps_{name}_bits"] = round((n * d * s / 8 + d * h * s / 8 + n * h * s / 8) / t_b / 1e3, 1)
+            print(json.dumps(rec), flush=True)
+            rows.append(rec)
+            del yq, yb, out_i, out_b
+        torch.cuda.empty_cache()
+    print("\nupdate Y.W, s = t, popcount kernel against int8 matrix cores; us per launch (achieved GB/s of "
+          "algorithmic bytes):")
+    print("\n| N x D -> H | bits | popcount, int32 out | matrix cores, int32 out | popcount, low-bit out | "
+          "matrix cores, low-bit out |")
+    print("|---|---|---|---|---|---|")
+    for r in rows:
+        print(f"| {r['N']} x {r['D']} -> {r['H']} | {r['bits']} | "
+              f"{r['us_popcount_int32']} ({r['gbps_popcount_int32']}) | {r['us_mfma_int32']} ({r['gbps_mfma_int32']}) | "
+              f"{r['us_popcount_bits']} ({r['gbps_popcount_bits']}) | {r['us_mfma_bits']} ({r['gbps_mfma_bits']}) |")
+
+
+def tiles():
+    """One fused layer (8 bits, first layer's shape) per tile width: time per visited adjacency bit."""
+    from workloads import make_workload
+    rows = []
+    for cfg in (4, 5):
+        w = make_workload(cfg)
+        g = w.graph
+        a_src = torch.from_numpy(g.dense_compact()).cuda()
+        ws = [torch.from_numpy(W).cuda() for W in w.W]
+        x = torch.from_numpy(w.X).cuda()
+        xr = (float(w.X.min()), float(w.X.max()))
+        base = None
+        for kb in (128, 64, 32):
+            net = QuantGNN(a_src, ws, w.s, w.t, w.model == "gin", tile_kbits=kb, block_rows=g.block)
+            ranges = net.calibrate(x, xr)
+            out = torch.empty((g.n_nodes, net.dims[-1][1]), dtype=torch.float32, device="cuda")
+            t = _kernel_us(lambda: net.forward(x, xr, ranges, out=out), q.KERNEL_LAYER, n=5, warm=2) * len(net.dims)
+            nnz = int(net.map.nnz_tiles.cpu()[0])
+            per_bit = t / (nnz * 16.0 * kb)
+            base = base or per_bit
+            rec = {"sweep": "tiles", "config": cfg, "tile_kbits": kb, "nonzero_tiles": nnz,
+                   "us_layers": round(t, 1), "ps_per_adjacency_bit": round(per_bit * 1e6, 3),
+                   "cost_relative_to_128": round(per_bit / base, 2)}
+            print(json.dumps(rec), flush=True)
+            rows.append(rec)
+            del net, out
+        del a_src, x
+        torch.cuda.empty_cache()
+    print("\n| config | tile | non-zero tiles | all layers us | cost per visited adjacency bit, relative to 16 x 128 |")
+    print("|---|---|---|---|---|")
+    for r in rows:
+        print(f"| {r['config']} | 16 x {r['tile_kbits']} | {r['nonzero_tiles']} | {r['us_layers']} | {r['cost_relative_to_128']} |")
+
+
 def main():
     torch.cuda.set_device(0)
-    which = sys.argv[1:] or ["table3", "config3", "config5", "sizes", "reuse", "transfer"]
+    which = sys.argv[1:] or ["table3", "config3", "config5", "sizes", "reuse", "transfer", "gate", "tiles"]
     for name in which:
         {"table3": table3, "config3": config3, "config5": config5, "sizes": sizes, "reuse": reuse,
-         "transfer": transfer}[name]()
+         "transfer": transfer, "gate": gate, "tiles": tiles}[name]()
 
 
 if __name__ == "__main__":

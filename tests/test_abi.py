@@ -15,9 +15,13 @@ pytestmark = pytest.mark.skipif(not os.path.exists(LIB),
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "qgtc.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(qgtc_[a-z0-9_]+)\s*\(", text)))
+    """Every function declared in include/*.h (comments stripped)."""
+    import glob
+    names = set()
+    for path in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+        names |= set(re.findall(r"\b(qgtc_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported():
@@ -155,15 +159,79 @@ def test_probe_arguments_are_checked():
     assert l.qgtc_probe_popcount(1, 5, 1, C.c_void_p(0x1000), None) == 2
 
 
-def test_options_are_range_checked():
+def test_tuning_is_range_checked_before_any_launch():
+    """qgtc_tuning comes with the call; values outside its ranges are refused on the host."""
     import paper_2111_09547_amd.binding as b
     l = b.lib()
-    assert l.qgtc_set_option(b.OPT_UPDATE_PATH, 3) == 7
-    assert l.qgtc_set_option(b.OPT_UPDATE_PATH, 0) == 0
-    assert l.qgtc_set_option(b.OPT_AGG_XCD_RUN, 5000) == 7
-    assert l.qgtc_set_option(b.OPT_AGG_XCD_RUN, -1) == 0
-    assert l.qgtc_set_option(b.OPT_AGG_XCD_RUN, 0) == 0
-    assert l.qgtc_set_option(99, 0) == 7
+    Y = _fake_bits(b, 64, 64, 4, b.LEFT)
+    W = _fake_bits(b, 64, 16, 4, b.RIGHT)
+    for bad in (b._TuningC(3, 0, 0, 0), b._TuningC(0, 5000, 0, 0), b._TuningC(0, 0, 2, 0), b._TuningC(0, 0, 0, 3),
+                b._TuningC(-1, 0, 0, 0)):
+        ep = b.Epilogue(mode=b.OUT_I32).to_c()
+        ep.tuning = C.pointer(bad)
+        assert l.qgtc_update(C.byref(Y), C.byref(W), C.byref(ep), C.c_void_p(0x20000), 16, None) == 7
+
+
+def test_layer_static_refuses_oversized_layers_on_the_host():
+    """The layer without a workspace argument checks its size limit before any GPU call."""
+    import paper_2111_09547_amd.binding as b
+    l = b.lib()
+    n, d = 70000, 2048
+    assert l.qgtc_layer_workspace_bytes(n, d, 16, 16) > b.LAYER_STATIC_MAX_BYTES
+    A = _fake_bits(b, n, 128, 1, b.LEFT, block_rows=128)
+    X = _fake_bits(b, n, d, 16, b.RIGHT)
+    W = _fake_bits(b, d, 16, 16, b.RIGHT)
+    agg = b.Epilogue(mode=b.OUT_BITS, rq_nbits=16, rq_inv_scale=1.0).to_c()
+    upd = b.Epilogue(mode=b.OUT_I32).to_c()
+    st = l.qgtc_layer_static(C.byref(A), None, C.byref(X), C.byref(W), C.byref(agg), C.byref(upd),
+                             C.c_void_p(0x30000), 16, None)
+    assert st == 6                                       # QGTC_ERR_WORKSPACE
+    assert l.qgtc_layer_static(None, None, C.byref(X), C.byref(W), C.byref(agg), C.byref(upd),
+                               C.c_void_p(0x30000), 16, None) == 1
+
+
+def test_selector_and_scalar_helpers_on_the_host():
+    """qgtc_plan_layer, qgtc_quant_inv_scale, qgtc_layer_epilogues and qgtc_fold_batchnorm
+    are pure host functions: rules and values checked without a GPU."""
+    import numpy as np
+    import paper_2111_09547_amd.binding as b
+    from oracle import qgnn
+    # Eq. (2)'s inverse step, rounded once to fp32, as the oracle forms it
+    for lo, hi, bits in ((0.0, 8.0, 2), (-1.7, 3.9, 8), (0.0, 12345.0, 5), (-4.0, 4.0, 32)):
+        assert b.qgtc_quant_inv_scale(lo, hi, bits) == float(qgnn.inv_scale(lo, hi, bits))
+    assert b.qgtc_quant_inv_scale(1.0, 1.0, 4) == 0.0 and b.qgtc_quant_inv_scale(0.0, 1.0, 33) == 0.0
+    # selector: narrow tiles only when they skip enough; fused kernel up to 8 bits, 1024 x 256
+    plan = b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024, nnz_tiles=(131072, 65536, 32768))
+    assert plan["tile_kbits"] == 128 and plan["fused"] == 1 and plan["update_path"] == 2
+    plan = b.qgtc_plan_layer(262144, 512, 16, 8, 8, n_tile_rows=16384, a_cols=2048, nnz_tiles=(60000, 40000, 30000))
+    assert plan["tile_kbits"] == 32                      # 60000*32*1.3 < 40000*64 < 30000*128
+    assert plan["est_us_update_first"] < plan["est_us_aggregate_first"]      # 512 -> 16 columns
+    plan = b.qgtc_plan_layer(8192, 64, 64, 16, 16, n_tile_rows=512, a_cols=8192)
+    assert plan["fused"] == 0 and plan["update_path"] == 1 and plan["tile_kbits"] == 128
+    assert b.qgtc_plan_layer(8192, 2000, 64, 8, 8)["fused"] == 0
+    assert b.qgtc_plan_layer(100, 64, 64, 8, 8, n_tile_rows=7)["ksplit"] == 4         # few tile rows: split the lists
+    with pytest.raises(b.QgtcError):
+        b.qgtc_plan_layer(10, 0, 4, 8, 8)
+    # the scalars of a layer: the hand-worked 2-layer network of tests/golden
+    e1, e2, zs, nx = b.qgtc_layer_epilogues(2, 2, 2, -2.0, 1.0, (-1.0, 1.0), 8, 8)
+    assert (e1.mode, e1.rq_nbits, e1.rq_inv_scale, e1.relu) == (b.OUT_BITS, 2, 0.5, False)
+    assert (e2.mode, e2.rq_nbits, e2.rq_inv_scale, e2.relu) == (b.OUT_BITS, 2, 0.5, True)
+    assert zs == 1.0 and nx == 2.0
+    e1, e2, zs, nx = b.qgtc_layer_epilogues(2, 2, 2, 0.0, 2.0, (-1.0, 1.0), 8, None, last=True)
+    assert e2.mode == b.OUT_F32 and (e2.cc, e2.rs, e2.l0a, e2.l0b, e2.ck, e2.cs) == (2.0, -4.0, 0.0, 0.0, -2.0, 0.5)
+    assert nx == 0.0
+    # one-layer GIN: the zero point of the features enters through l0a / l0b
+    e1, e2, _, _ = b.qgtc_layer_epilogues(8, 8, 64, -3.5, 0.03, (-0.1, 0.1), 900, None, self_term=True, last=True)
+    assert e1.self_term and not e2.self_term and e2.l0a == -3.5 and e2.l0b == -3.5
+    # update first: every code a pure scale
+    e1, e2, zs, nx = b.qgtc_layer_epilogues(2, 2, 2, 0.0, 1.0, (-1.0, 1.0), 16, 4, self_term=True, update_first=True)
+    assert not e1.self_term and e2.self_term and zs == 2.0 and nx == 2.0
+    # batch normalization fold against the oracle's
+    rng = np.random.default_rng(3)
+    g, be, mu, var = rng.uniform(0.5, 2, 7), rng.uniform(-1, 1, 7), rng.uniform(-1, 1, 7), rng.uniform(0.1, 3, 7)
+    a, sh = b.qgtc_fold_batchnorm(g, be, mu, var, 1e-5, 3.1e-4)
+    ra, rb = qgnn.fold_batchnorm(g, be, mu, var, 1e-5, 3.1e-4)
+    assert (a.numpy() == ra).all() and (sh.numpy() == rb).all()
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

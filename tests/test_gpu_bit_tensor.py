@@ -9,7 +9,8 @@ from oracle import qgnn, bitplane as bp
 pytestmark = pytest.mark.gpu
 
 q = pytest.importorskip("paper_2111_09547_amd")
-from paper_2111_09547_amd.bit_tensor import to_bit, to_val, bitMM2Int, bitMM2Bit  # noqa: E402
+from paper_2111_09547_amd.bit_tensor import (BitTensor, to_bit, to_val, bitMM2Int, bitMM2Bit,  # noqa: E402
+                                             calibrate_inv_scale, enable_tensor_methods)
 from gpu_util import dev, as_u32, words_np  # noqa: E402
 
 
@@ -40,7 +41,53 @@ def test_bit_products(sa, sb):
     inv = qgnn.inv_scale(0.0, float(max(1, qgnn.as_signed(C).max())), bit_c)
     want = qgnn.requantize(C, 0, inv, bit_c)
     layout = bp.LEFT if sa == 1 else bp.RIGHT        # next left operand after an aggregation, next X after an update
-    for got in (bitMM2Bit(Lb, Rb, bit_c, inv_scale=float(inv)), bitMM2Bit(Lb, Rb, bit_c)):
-        assert got.nbits == bit_c
-        assert (words_np(got) == bp.pack(want, bit_c, layout)).all()
-        assert (to_val(got).cpu().numpy().view(np.uint32) == want).all()
+    assert calibrate_inv_scale(Lb, Rb, bit_c) == float(inv)          # the range found from the data
+    got = bitMM2Bit(Lb, Rb, bit_c, inv_scale=float(inv))
+    assert isinstance(got, BitTensor) and got.nbits == bit_c and got.shape == (m, n)
+    assert got.side == ("left" if sa == 1 else "right") and got.storage.dtype == torch.int32
+    assert (words_np(got.bits) == bp.pack(want, bit_c, layout)).all()
+    assert (got.to_val().cpu().numpy().view(np.uint32) == want).all()
+
+
+def test_tensor_methods_as_the_paper_writes_them():
+    """Section 5: Tensor.to_bit(nbits) gives a bit-Tensor, .to_val() decodes it."""
+    enable_tensor_methods()
+    rng = np.random.default_rng(73)
+    x = rng.normal(size=(50, 20)).astype(np.float32)
+    xb = dev(x).to_bit(3)
+    assert isinstance(xb, BitTensor) and xb.nbits == 3 and xb.side == "right"
+    assert (xb.to_val().cpu().numpy().view(np.uint32) == qgnn.quantize(x, float(x.min()), float(x.max()), 3)).all()
+    a = (rng.random((50, 50)) < 0.1).astype(np.uint8)
+    ab = dev(a).to_bit(1, side="left")
+    assert ab.is_adjacency()
+    assert (as_u32(bitMM2Int(ab, xb)) == qgnn.aggregate(a, qgnn.quantize(x, float(x.min()), float(x.max()), 3))).all()
+
+
+@pytest.mark.parametrize("d", [64, 100, 128])
+def test_one_bit_layer_chained_through_the_products(d):
+    """Aggregate, requantize to ONE bit, update: the 1-bit result of bitMM2Bit is a left
+    operand without the 128-bit row padding of an adjacency (d = 64: two words per row), so
+    the second product must run as an update, not as an aggregation."""
+    rng = np.random.default_rng([74, d])
+    n, h, t = 130, 24, 3
+    A = (rng.random((n, n)) < 0.08).astype(np.uint8)
+    Xq = rng.integers(0, 2, size=(n, d)).astype(np.uint32)
+    Wq = rng.integers(0, 2 ** t, size=(d, h)).astype(np.uint32)
+    Y = qgnn.aggregate(A, Xq)
+    inv = qgnn.inv_scale(0.0, float(max(1, Y.max())), 1)
+    Yq = qgnn.requantize(Y, 0, inv, 1)
+    Z = qgnn.update(Yq, Wq)
+    Ab = to_bit(dev(A), 1, side="left")
+    Xb = to_bit(dev(Xq.view(np.int32)), 1, side="right")
+    Wb = to_bit(dev(Wq.view(np.int32)), t, side="right")
+    Yb = bitMM2Bit(Ab, Xb, 1, inv_scale=float(inv))
+    assert Yb.nbits == 1 and Yb.side == "left" and (Yb.to_val().cpu().numpy().view(np.uint32) == Yq).all()
+    assert Yb.is_adjacency() == (Yb.bits.c.ld_words % 4 == 0 and Yb.bits.c.data % 16 == 0)
+    assert (as_u32(bitMM2Int(Yb, Wb)) == Z).all()
+    # the same 1-bit result written into a padded destination is a valid adjacency operand
+    dst = q.alloc_bits(n, d, 1, q.LEFT)
+    dst.words.fill_(-1)
+    q.qgtc_aggregate(Ab.bits, None, Xb.bits, q.Epilogue(mode=q.OUT_BITS, rq_nbits=1, rq_inv_scale=float(inv)), out=dst)
+    padded = BitTensor(dst)
+    assert padded.is_adjacency()
+    assert (as_u32(bitMM2Int(padded, Wb)) == Z).all()

@@ -207,14 +207,13 @@ def test_aggregate_does_not_depend_on_xcd_run(d):
     A = rand_graph(rng, n, n, 0.01)
     X = rng.integers(0, 2 ** s, size=(n, d)).astype(np.uint32)
     want = qgnn.aggregate(A, X)
-    try:
-        for run in (-1, 0, 1, 3, 64, 4096):
-            q.qgtc_set_option(q.OPT_AGG_XCD_RUN, run)
-            for ep in (q.Epilogue(mode=q.OUT_I32), ):
-                got, _ = run_aggregate(A, X, s, 128, ep=ep)
-                assert (as_u32(got) == want).all(), run
-    finally:
-        q.qgtc_set_option(q.OPT_AGG_XCD_RUN, 0)
+    for run in (-1, 0, 1, 3, 64, 4096):
+        ep = q.Epilogue(mode=q.OUT_I32, tuning=q.Tuning(agg_xcd_run=run))
+        got, _ = run_aggregate(A, X, s, 128, ep=ep)
+        assert (as_u32(got) == want).all(), run
+    with pytest.raises(q.QgtcError) as e:                  # out of range: refused, nothing launched
+        run_aggregate(A, X, s, 128, ep=q.Epilogue(mode=q.OUT_I32, tuning=q.Tuning(agg_xcd_run=5000)))
+    assert e.value.status == 7
 
 
 @pytest.mark.parametrize("d", [16, 32, 64, 200])
@@ -493,38 +492,33 @@ def test_fused_layer_all_outputs(shape, st):
             seg = A[r, b0:b0 + block]
             compact[r, :seg.size] = seg
         storages.append((q.qgtc_pack_bits(dev(compact), 1, q.LEFT, block_rows=block), 32))
-    try:
-        for Ab, kb in storages:
-            m = q.qgtc_build_tile_map(Ab, 16, kb) if kb else None
-            for path, ksplit in ((q.LAYER_FUSED, 0), (q.LAYER_FUSED, 1), (q.LAYER_FUSED, 2),
-                                 (q.LAYER_FUSED, 4), (q.LAYER_TWO_KERNELS, 0)):
-                q.qgtc_set_option(q.OPT_LAYER_PATH, path)
-                q.qgtc_set_option(q.OPT_LAYER_KSPLIT, ksplit)
-                tag = (kb, path, ksplit)
-                q.qgtc_prof_enable(True)
-                q.qgtc_prof_reset()
-                got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32))
-                fused_launches = q.qgtc_prof_read(q.KERNEL_LAYER)[1]
-                q.qgtc_prof_enable(False)
-                q.qgtc_prof_reset()
-                assert fused_launches == (1 if path == q.LAYER_FUSED else 0), tag
-                assert (as_u32(got) == Z).all(), tag
-                # weights cached as bytes in operand order: always the fused kernel
-                got = q.qgtc_layer(Ab, m, Xb, Wbytes, agg_ep, q.Epilogue(mode=q.OUT_I32))
-                assert (as_u32(got) == Z).all(), tag
-                ep = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=out_bits, rq_lo=3,
-                                rq_inv_scale=float(z_inv))
-                # poison the destination: every word, padding included, must be written
-                dst = q.alloc_bits(n, h, out_bits, q.RIGHT)
-                dst.words.fill_(-1)
-                got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep, out=dst)
-                assert (words_np(got) == want_bits).all(), tag
-                ep = q.Epilogue(mode=q.OUT_F32, row_i=None, row_l=dev(rl), col_i=dev(cs), **kw)
-                got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep).cpu().numpy()
-                assert_fp32_close(got, want_f32, str(tag))
-    finally:
-        q.qgtc_set_option(q.OPT_LAYER_PATH, q.LAYER_FUSED)
-        q.qgtc_set_option(q.OPT_LAYER_KSPLIT, 0)
+    for Ab, kb in storages:
+        m = q.qgtc_build_tile_map(Ab, 16, kb) if kb else None
+        for path, ksplit in ((q.LAYER_FUSED, 0), (q.LAYER_FUSED, 1), (q.LAYER_FUSED, 2),
+                             (q.LAYER_FUSED, 4), (q.LAYER_TWO_KERNELS, 0)):
+            tn = q.Tuning(layer_path=path, layer_ksplit=ksplit)
+            tag = (kb, path, ksplit)
+            q.qgtc_prof_enable(True)
+            q.qgtc_prof_reset()
+            got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32, tuning=tn))
+            fused_launches = q.qgtc_prof_read(q.KERNEL_LAYER)[1]
+            q.qgtc_prof_enable(False)
+            q.qgtc_prof_reset()
+            assert fused_launches == (1 if path == q.LAYER_FUSED else 0), tag
+            assert (as_u32(got) == Z).all(), tag
+            # weights cached as bytes in operand order: always the fused kernel
+            got = q.qgtc_layer(Ab, m, Xb, Wbytes, agg_ep, q.Epilogue(mode=q.OUT_I32, tuning=tn))
+            assert (as_u32(got) == Z).all(), tag
+            ep = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=out_bits, rq_lo=3,
+                            rq_inv_scale=float(z_inv), tuning=tn)
+            # poison the destination: every word, padding included, must be written
+            dst = q.alloc_bits(n, h, out_bits, q.RIGHT)
+            dst.words.fill_(-1)
+            got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep, out=dst)
+            assert (words_np(got) == want_bits).all(), tag
+            ep = q.Epilogue(mode=q.OUT_F32, row_i=None, row_l=dev(rl), col_i=dev(cs), tuning=tn, **kw)
+            got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep).cpu().numpy()
+            assert_fp32_close(got, want_f32, str(tag))
 
 
 # ------------------------------------------------- folded batch normalization
@@ -586,30 +580,25 @@ def test_column_affine_epilogue(shape, st):
                             col_scale=dev(a))
     Yb = q.qgtc_pack_bits(dev(Yq.view(np.int32)), rq_bits, q.LEFT)
     Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
-    try:
-        for path in (q.UPDATE_POPCOUNT, q.UPDATE_MATRIX_CORES):
-            q.qgtc_set_option(q.OPT_UPDATE_PATH, path)
-            assert (words_np(q.qgtc_update(Yb, Wb, ep_bits)) == want_bits).all(), path
-            assert (words_np(q.qgtc_update(Yb, Wb, ep_noshift)) == want_noshift).all(), path
-            ep = q.Epilogue(mode=q.OUT_F32, row_i=dev(rs.astype(np.int32)), relu=True,
-                            col_scale=dev(a1), col_shift=dev(b1), **kw)
-            got = q.qgtc_update(Yb, Wb, ep).cpu().numpy()
-            assert_fp32_close(got, want_f32, str(path))
-    finally:
-        q.qgtc_set_option(q.OPT_UPDATE_PATH, q.UPDATE_AUTO)
+    for path in (q.UPDATE_POPCOUNT, q.UPDATE_MATRIX_CORES):
+        ep_bits.tuning = ep_noshift.tuning = q.Tuning(update_path=path)
+        assert (words_np(q.qgtc_update(Yb, Wb, ep_bits)) == want_bits).all(), path
+        assert (words_np(q.qgtc_update(Yb, Wb, ep_noshift)) == want_noshift).all(), path
+        ep = q.Epilogue(mode=q.OUT_F32, row_i=dev(rs.astype(np.int32)), relu=True,
+                        col_scale=dev(a1), col_shift=dev(b1), tuning=q.Tuning(update_path=path), **kw)
+        got = q.qgtc_update(Yb, Wb, ep).cpu().numpy()
+        assert_fp32_close(got, want_f32, str(path))
     agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=rq_bits, rq_lo=0, rq_inv_scale=float(y_inv))
-    try:
-        for path in (q.LAYER_FUSED, q.LAYER_TWO_KERNELS):
-            q.qgtc_set_option(q.OPT_LAYER_PATH, path)
-            dst = q.alloc_bits(n, h, out_bits, q.RIGHT)
-            dst.words.fill_(-1)
-            assert (words_np(q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep_bits, out=dst)) == want_bits).all(), path
-            assert (words_np(q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep_noshift)) == want_noshift).all(), path
-            ep = q.Epilogue(mode=q.OUT_F32, row_i=None, relu=True, col_scale=dev(a1), col_shift=dev(b1), **kw)
-            got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep).cpu().numpy()
-            assert_fp32_close(got, want_f32, str(path))
-    finally:
-        q.qgtc_set_option(q.OPT_LAYER_PATH, q.LAYER_FUSED)
+    for path in (q.LAYER_FUSED, q.LAYER_TWO_KERNELS):
+        ep_bits.tuning = ep_noshift.tuning = q.Tuning(layer_path=path)
+        dst = q.alloc_bits(n, h, out_bits, q.RIGHT)
+        dst.words.fill_(-1)
+        assert (words_np(q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep_bits, out=dst)) == want_bits).all(), path
+        assert (words_np(q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep_noshift)) == want_noshift).all(), path
+        ep = q.Epilogue(mode=q.OUT_F32, row_i=None, relu=True, col_scale=dev(a1), col_shift=dev(b1),
+                        tuning=q.Tuning(layer_path=path), **kw)
+        got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, ep).cpu().numpy()
+        assert_fp32_close(got, want_f32, str(path))
 
 
 @pytest.mark.parametrize("st", [(1, 1), (2, 3), (4, 4), (7, 7), (8, 8), (8, 2), (3, 8), (8, 7)])
@@ -631,17 +620,14 @@ def test_update_matrix_core_path_equals_popcount_and_oracle(st, shape):
     cs = Wq.sum(axis=0).astype(np.int32)
     kw = dict(cc=1.7e-3, rs=-0.031, l0a=0.4, l0b=-0.9, ck=-6.4, cs=0.0125)
     outs = {}
-    try:
-        for path in (q.UPDATE_POPCOUNT, q.UPDATE_MATRIX_CORES):
-            q.qgtc_set_option(q.OPT_UPDATE_PATH, path)
-            z = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_I32))
-            bits = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=5, rq_lo=0,
-                                                    rq_inv_scale=float(inv)))
-            f = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_F32, row_i=dev(rs), row_l=dev(rs),
-                                                 col_i=dev(cs), **kw))
-            outs[path] = (as_u32(z), words_np(bits), f.cpu().numpy())
-    finally:
-        q.qgtc_set_option(q.OPT_UPDATE_PATH, q.UPDATE_AUTO)
+    for path in (q.UPDATE_POPCOUNT, q.UPDATE_MATRIX_CORES):
+        tn = q.Tuning(update_path=path)
+        z = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_I32, tuning=tn))
+        bits = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=5, rq_lo=0,
+                                                rq_inv_scale=float(inv), tuning=tn))
+        f = q.qgtc_update(Yb, Wb, q.Epilogue(mode=q.OUT_F32, row_i=dev(rs), row_l=dev(rs),
+                                             col_i=dev(cs), tuning=tn, **kw))
+        outs[path] = (as_u32(z), words_np(bits), f.cpu().numpy())
     for path, (z, bits, f) in outs.items():
         assert (z == Z).all(), path
         assert (bits == bp.pack(qgnn.requantize(Z, 0, inv, 5, relu=True), 5, bp.RIGHT)).all(), path
