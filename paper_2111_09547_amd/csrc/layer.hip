@@ -222,10 +222,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
       const float rq_inv = k2->a.ep.rq_inv_scale;
       const float qmaxf = (float)((1u << k2->a.ep.rq_nbits) - 1u);   // at most 8 bits here
       const int ys = k2->ys;
+      // with the usual range [0, hi) the integer part of the rule is max(c, 0), with or without ReLU
+      const bool from_zero = rq_lo == 0;                              // wave-uniform
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         if ((j & km2) != kpart2) continue;
-        uint32_t q = requantize_code_small(y[j], relu_floor, rq_lo, rq_inv, qmaxf);
+        uint32_t q = from_zero ? requantize_code_relu0(y[j], rq_inv, qmaxf)
+                               : requantize_code_small(y[j], relu_floor, rq_lo, rq_inv, qmaxf);
         q = (c_ok && j < rows_left) ? q : 0u;
         if (cg_ok) yb[j * ys + cg * 64 + lane] = (uint8_t)q;   // zeros from the lanes past the last column
       }
@@ -245,44 +248,60 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
     const uint8_t* wb = k3->wb;
     const int64_t wb_part = k3->wb_part;
     const int n_units = n_nt * k3->n_kc;
-    for (int u = wave; u < n_units; u += nw) {
+    // The wave's (unit, K step) pairs one after the other; the weights of the next pair are
+    // requested before the matrix instructions of the current one.
+    auto load_b = [&](int u, int ks, v4u& b7, v4u& bb) {
       const int nt = u % n_nt;
-      const int kc = u / n_nt;
-      const int ks0 = kc * ks_per;
-      const int ks1 = min(ks0 + ks_per, n_ks);
-      const bool ones = nt >= n_nt_w;                // the tile whose column 0 sums the rows of Y
-      v4i acc1 = {0, 0, 0, 0}, acc7 = {0, 0, 0, 0}, acc14 = {0, 0, 0, 0};
-      for (int ks = ks0; ks < ks1; ++ks) {
-        const v4u av = *reinterpret_cast<const v4u*>(yb + ln * ys + ks * 64 + g * 16);
-        v4u a7 = av, ab = {0u, 0u, 0u, 0u};
-        if (split_y) {
-          a7 = av & 0x7f7f7f7fu;
-          ab = (av >> 7) & 0x01010101u;
-        }
-        v4u b7 = {0u, 0u, 0u, 0u}, bb = {0u, 0u, 0u, 0u};
-        if (ones) {
-          if (ln == 0) b7 = (v4u){0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
-        } else if (u == wave && ks == 0) {
-          b7 = b7_first;                             // u == wave < n_nt: chunk 0, so ks0 == 0
-          bb = bb_first;
-        } else {
-          const uint8_t* src = wb + ((int64_t)(nt * n_ks + ks) * 64 + lane) * 16;
-          b7 = *reinterpret_cast<const v4u*>(src);
-          if (split_w) bb = *reinterpret_cast<const v4u*>(src + wb_part);
-        }
-        acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)b7, acc1, 0, 0, 0);
-        if (split_y) acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)b7, acc7, 0, 0, 0);
-        if (split_w && !ones) {
-          acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)bb, acc7, 0, 0, 0);
-          if (split_y) acc14 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)bb, acc14, 0, 0, 0);
-        }
+      b7 = (v4u){0u, 0u, 0u, 0u};
+      bb = (v4u){0u, 0u, 0u, 0u};
+      if (nt >= n_nt_w) {                            // the tile whose column 0 sums the rows of Y
+        if (ln == 0) b7 = (v4u){0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
+      } else {
+        const uint8_t* src = wb + ((int64_t)(nt * n_ks + ks) * 64 + lane) * 16;
+        b7 = *reinterpret_cast<const v4u*>(src);
+        if (split_w) bb = *reinterpret_cast<const v4u*>(src + wb_part);
       }
-      // element r of the result: row 4 g + r, column ln of the tile
+    };
+    int u = wave;
+    int ks = (u / n_nt) * ks_per;
+    v4u b7 = b7_first, bb = bb_first;                // fetched early for unit `wave` when it is a tile of W, step 0
+    if (u < n_units && !(u < n_nt_w && ks == 0)) load_b(u, ks, b7, bb);
+    v4i acc1 = {0, 0, 0, 0}, acc7 = {0, 0, 0, 0}, acc14 = {0, 0, 0, 0};
+    while (u < n_units) {
+      const int nt = u % n_nt;
+      const int ks1 = min((u / n_nt) * ks_per + ks_per, n_ks);
+      const bool ones = nt >= n_nt_w;
+      int nu = u, nks = ks + 1;
+      if (nks >= ks1) { nu = u + nw; nks = (nu / n_nt) * ks_per; }
+      v4u nb7 = {0u, 0u, 0u, 0u}, nbb = {0u, 0u, 0u, 0u};
+      if (nu < n_units) load_b(nu, nks, nb7, nbb);
+      const v4u av = *reinterpret_cast<const v4u*>(yb + ln * ys + ks * 64 + g * 16);
+      v4u a7 = av, ab = {0u, 0u, 0u, 0u};
+      if (split_y) {
+        a7 = av & 0x7f7f7f7fu;
+        ab = (av >> 7) & 0x01010101u;
+      }
+      acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)b7, acc1, 0, 0, 0);
+      if (split_y) acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)b7, acc7, 0, 0, 0);
+      if (split_w && !ones) {
+        acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)bb, acc7, 0, 0, 0);
+        if (split_y) acc14 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)bb, acc14, 0, 0, 0);
+      }
+      if (nu != u) {
+        // the unit is complete; element r of the result: row 4 g + r, column ln of the tile
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const uint32_t v = (uint32_t)acc1[r] + ((uint32_t)acc7[r] << 7) + ((uint32_t)acc14[r] << 14);
-        atomicAdd(&z[(4 * g + r) * zs + nt * 16 + ln], v);
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t v = (uint32_t)acc1[r] + ((uint32_t)acc7[r] << 7) + ((uint32_t)acc14[r] << 14);
+          atomicAdd(&z[(4 * g + r) * zs + nt * 16 + ln], v);
+        }
+        acc1 = (v4i){0, 0, 0, 0};
+        acc7 = (v4i){0, 0, 0, 0};
+        acc14 = (v4i){0, 0, 0, 0};
       }
+      b7 = nb7;
+      bb = nbb;
+      u = nu;
+      ks = nks;
     }
   }
   __syncthreads();
@@ -350,6 +369,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
           uint32_t q = requantize_affine(zz[j], ca, cb, relu, rq_lo, rq_inv, qmax, qmaxf);
+          q = (h_ok && j < valid_rows) ? q : 0u;
+          b[j >> 2] |= q << (8 * (j & 3));
+        }
+      } else if (rq_lo == 0) {                       // wave-uniform; max(c, 0) with or without ReLU
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          uint32_t q = requantize_code_relu0(zz[j], rq_inv, qmaxf);
           q = (h_ok && j < valid_rows) ? q : 0u;
           b[j >> 2] |= q << (8 * (j & 3));
         }

@@ -142,15 +142,21 @@ __device__ __forceinline__ uint32_t requantize_code(uint32_t c_u32, int relu, in
   return (uint32_t)t;
 }
 
-// requantize_code for codes of at most 24 bits, in seven instructions: relu_floor is 0
-// with ReLU, INT32_MIN without; 2^bits - 1 is exact in fp32, so the clamp can be taken on
-// the float (t is never negative or NaN: the difference is >= 0, the scale finite and > 0).
+// requantize_code for codes of at most 24 bits: relu_floor is 0 with ReLU, INT32_MIN
+// without; 2^bits - 1 is exact in fp32, so the clamp can be taken on the float (t is never
+// negative or NaN: the difference is >= 0, the scale finite and > 0), and the conversion to
+// an integer truncates, which is the floor of a non-negative value.
 __device__ __forceinline__ uint32_t requantize_code_small(uint32_t c_u32, int32_t relu_floor, int32_t rq_lo,
                                                           float rq_inv_scale, float qmaxf) {
   const int32_t c = max((int32_t)c_u32, relu_floor);
   const uint32_t du = (uint32_t)max(c, rq_lo) - (uint32_t)rq_lo;
-  const float t = floorf((float)du * rq_inv_scale);
-  return (uint32_t)fminf(t, qmaxf);
+  return (uint32_t)fminf((float)du * rq_inv_scale, qmaxf);
+}
+
+// The same for a range that starts at 0, [0, hi): max(c, 0) is the whole integer part,
+// with or without ReLU.
+__device__ __forceinline__ uint32_t requantize_code_relu0(uint32_t c_u32, float rq_inv_scale, float qmaxf) {
+  return (uint32_t)fminf((float)(uint32_t)max((int32_t)c_u32, 0) * rq_inv_scale, qmaxf);
 }
 
 // The same behind a per-column affine map (a folded batch normalization); see

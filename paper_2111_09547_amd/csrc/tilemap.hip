@@ -67,30 +67,51 @@ __global__ __launch_bounds__(256) void tile_list16_kernel(const MapParams p) {
   int32_t* list = p.col_idx + (int64_t)tr * p.n_tile_cols;
   int count = 0;
   int deg = 0;
-  for (int tc0 = 0; tc0 < p.n_tile_cols; tc0 += 4) {
-    const int tc = tc0 + g;
-    uint32_t any = 0u;
-    if (r_ok && tc < p.n_tile_cols) {
-      const int w0 = tc * p.tile_words;
-      if (p.tile_words == 4) {                   // rows are padded to 128 bits
-        const uint4 v = *reinterpret_cast<const uint4*>(row + w0);
-        any = v.x | v.y | v.z | v.w;
-        deg += __builtin_popcount(v.x) + __builtin_popcount(v.y) + __builtin_popcount(v.z) +
-               __builtin_popcount(v.w);
-      } else {
+  if (p.tile_words == 4) {
+    // rows are padded to 128 bits: one 16-byte load per tile; the loads of four iterations
+    // (16 tiles of a row) are issued before the first ballot
+    for (int tc0 = 0; tc0 < p.n_tile_cols; tc0 += 16) {
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int tc = tc0 + 4 * u + g;
+        v[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (r_ok && tc < p.n_tile_cols) v[u] = *reinterpret_cast<const uint4*>(row + 4 * tc);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t any = v[u].x | v[u].y | v[u].z | v[u].w;
+        deg += __builtin_popcount(v[u].x) + __builtin_popcount(v[u].y) + __builtin_popcount(v[u].z) +
+               __builtin_popcount(v[u].w);
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(any != 0u);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          if (((m >> (16 * k)) & 0xffffull) != 0ull) {   // wave-uniform
+            if (lane == 0) list[count] = tc0 + 4 * u + k;
+            ++count;
+          }
+        }
+      }
+    }
+  } else {
+    for (int tc0 = 0; tc0 < p.n_tile_cols; tc0 += 4) {
+      const int tc = tc0 + g;
+      uint32_t any = 0u;
+      if (r_ok && tc < p.n_tile_cols) {
+        const int w0 = tc * p.tile_words;
         for (int w = w0; w < w0 + p.tile_words; ++w) {
           const uint32_t v = row[w];
           any |= v;
           deg += __builtin_popcount(v);
         }
       }
-    }
-    const unsigned long long m = __builtin_amdgcn_ballot_w64(any != 0u);
+      const unsigned long long m = __builtin_amdgcn_ballot_w64(any != 0u);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if (((m >> (16 * k)) & 0xffffull) != 0ull) {   // wave-uniform
-        if (lane == 0) list[count] = tc0 + k;
-        ++count;
+      for (int k = 0; k < 4; ++k) {
+        if (((m >> (16 * k)) & 0xffffull) != 0ull) {   // wave-uniform
+          if (lane == 0) list[count] = tc0 + k;
+          ++count;
+        }
       }
     }
   }
@@ -174,42 +195,56 @@ __global__ __launch_bounds__(256) void degree_kernel(const MapParams p) {
   if (lane == 0) p.deg[r] = cnt;
 }
 
-// Non-zero tiles at 16 x 32, 16 x 64 and 16 x 128 in one pass: one wave per row of tiles,
+// Non-zero tiles at 16 x 32, 16 x 64 and 16 x 128 in one pass: a wave per row of tiles,
 // lane <-> (row = lane % 16, one of four consecutive 128-bit groups = lane / 16).  A ballot
 // per word of the group tells, for each of the four groups, whether any of the 16 rows has
 // a bit there; the three counts follow from the four answers.
 __global__ __launch_bounds__(256) void tile_stats_kernel(const MapParams p, int32_t* counts) {
+  __shared__ int part[3];
   const int lane = threadIdx.x & 63;
-  const int tr = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (tr >= p.n_tile_rows) return;               // whole wave
-  const int r = tr * 16 + (lane & 15);
-  const int g = lane >> 4;
-  const bool r_ok = r < p.rows;
-  const uint32_t* row = p.A + (int64_t)(r_ok ? r : 0) * p.lda;
+  if (threadIdx.x < 3) part[threadIdx.x] = 0;
+  __syncthreads();
   const int n128 = (p.n_words + 3) >> 2;          // rows are padded to 128 bits with zeros
+  const int g = lane >> 4;
   int c32 = 0, c64 = 0, c128 = 0;
-  for (int t0 = 0; t0 < n128; t0 += 4) {
-    const int tc = t0 + g;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (r_ok && tc < n128) v = *reinterpret_cast<const uint4*>(row + 4 * tc);
-    const unsigned long long mx = __builtin_amdgcn_ballot_w64(v.x != 0u);
-    const unsigned long long my = __builtin_amdgcn_ballot_w64(v.y != 0u);
-    const unsigned long long mz = __builtin_amdgcn_ballot_w64(v.z != 0u);
-    const unsigned long long mw = __builtin_amdgcn_ballot_w64(v.w != 0u);
+  // a wave walks over rows of tiles with the stride of the grid: few, long-lived waves, and
+  // three atomic additions per workgroup at the end
+  for (int tr = blockIdx.x * 4 + (threadIdx.x >> 6); tr < p.n_tile_rows; tr += (int)gridDim.x * 4) {
+    const int r = tr * 16 + (lane & 15);
+    const bool r_ok = r < p.rows;
+    const uint32_t* row = p.A + (int64_t)(r_ok ? r : 0) * p.lda;
+    for (int t0 = 0; t0 < n128; t0 += 16) {
+      uint4 v[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {                 // wave-uniform arithmetic
-      const int bx = ((mx >> (16 * k)) & 0xffffull) != 0ull, by = ((my >> (16 * k)) & 0xffffull) != 0ull;
-      const int bz = ((mz >> (16 * k)) & 0xffffull) != 0ull, bw = ((mw >> (16 * k)) & 0xffffull) != 0ull;
-      c32 += bx + by + bz + bw;
-      c64 += (bx | by) + (bz | bw);
-      c128 += bx | by | bz | bw;
+      for (int u = 0; u < 4; ++u) {               // 16 groups of a row in flight together
+        const int tc = t0 + 4 * u + g;
+        v[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (r_ok && tc < n128) v[u] = *reinterpret_cast<const uint4*>(row + 4 * tc);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const unsigned long long mx = __builtin_amdgcn_ballot_w64(v[u].x != 0u);
+        const unsigned long long my = __builtin_amdgcn_ballot_w64(v[u].y != 0u);
+        const unsigned long long mz = __builtin_amdgcn_ballot_w64(v[u].z != 0u);
+        const unsigned long long mw = __builtin_amdgcn_ballot_w64(v[u].w != 0u);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {             // wave-uniform arithmetic
+          const int bx = ((mx >> (16 * k)) & 0xffffull) != 0ull, by = ((my >> (16 * k)) & 0xffffull) != 0ull;
+          const int bz = ((mz >> (16 * k)) & 0xffffull) != 0ull, bw = ((mw >> (16 * k)) & 0xffffull) != 0ull;
+          c32 += bx + by + bz + bw;
+          c64 += (bx | by) + (bz | bw);
+          c128 += bx | by | bz | bw;
+        }
+      }
     }
   }
   if (lane == 0) {
-    atomicAdd(&counts[0], c32);
-    atomicAdd(&counts[1], c64);
-    atomicAdd(&counts[2], c128);
+    atomicAdd(&part[0], c32);
+    atomicAdd(&part[1], c64);
+    atomicAdd(&part[2], c128);
   }
+  __syncthreads();
+  if (threadIdx.x < 3 && part[threadIdx.x] != 0) atomicAdd(&counts[threadIdx.x], part[threadIdx.x]);
 }
 
 // Start values of the four counters (a kernel, so that the call can be recorded into a HIP graph).
@@ -318,7 +353,9 @@ extern "C" qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void
   hipLaunchKernelGGL(tile_stats_init_kernel, dim3(1), dim3(64), 0, s, counts, p.n_tile_rows);
   if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
   if (p.n_tile_rows > 0) {
-    hipLaunchKernelGGL(tile_stats_kernel, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p, counts);
+    const int blocks = cdiv(p.n_tile_rows, 4);
+    const int cap = device_compute_units() * 8;
+    hipLaunchKernelGGL(tile_stats_kernel, dim3((unsigned)(blocks < cap ? blocks : cap)), dim3(256), 0, s, p, counts);
     if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;
   }
   return QGTC_OK;

@@ -9,10 +9,13 @@
 // integer modulo 2^32, bit for bit; inputs (packed planes) and outputs (int32,
 // fp32 or packed planes) are exactly those of the popcount kernel.
 //
-// The instruction is signed, codes of 8 bits are not: an 8-bit code c is split
-// into c7 = c & 127 and its top bit b7, and
-//   y.w = y7.w7 + 128 (b7y.w7 + y7.b7w) + 16384 b7y.b7w
-// is taken with up to four instructions into three accumulators.
+// The instruction is signed, codes of 8 bits are not: an 8-bit code c is taken as
+// c' = c - 128 (one XOR with 0x80 per byte), and with K' the staged length of K
+//   sum_k y_k w_k = sum_k y'_k w'_k + 128 sum_k y'_k + 128 sum_k w'_k + 16384 K'
+//                 = sum_k y'_k w'_k + 128 (sum_k y'_k + sum_k w_k)
+// (only Y with 8 bits: sum_k y'_k w_k + 128 sum_k w_k; only W: sum_k y_k w'_k + 128 sum_k y_k).
+// The column sums of W are taken once per workgroup while W is staged, the row sums of
+// Y by one more matrix instruction against an all-ones operand.  All of it modulo 2^32.
 //
 // Work split: a workgroup of four waves puts the byte form of its slice of W (up to
 // 64 output columns) into LDS once; each wave then walks over groups of 32 rows (two
@@ -74,7 +77,7 @@ __device__ __forceinline__ void planes_word_to_codes(uint32_t (&a)[8]) {
   for (int p = 0; p < 8; p += 2) swap_bits<1, 0x55555555u>(a[p], a[p + 1]);
 }
 
-// SPLIT_Y / SPLIT_W: the operand has 8 planes and is split into 7 bits + top bit;
+// SPLIT_Y / SPLIT_W: the operand has 8 planes and is taken as code - 128 (see the top);
 // NTC: 16-column tiles per workgroup (1 or 4); LW: see above (1, 2 or 8).
 template <bool SPLIT_Y, bool SPLIT_W, int NTC, int LW>
 __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
@@ -93,10 +96,14 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
   const int n_ss = (p.kwords + SSW - 1) / SSW;
   const int kpad = n_ss * SSW * 32;                 // K positions per column in LDS, one byte each
   const int wstride = kpad + kPad;
-  const int part_bytes = CC * wstride;
+  int32_t* colsum = reinterpret_cast<int32_t*>(wl + CC * wstride);   // [CC], sum of the codes of a column
 
   // ---- stage W[.][c0 .. c0+CC) in LDS as bytes ------------------------------------
   // one thread turns one word (32 K positions) of one column, all planes, into 32 bytes
+  if (SPLIT_Y) {
+    for (int i = threadIdx.x; i < CC; i += 256) colsum[i] = 0;
+    __syncthreads();
+  }
   for (int idx = threadIdx.x; idx < CC * (kpad >> 5); idx += 256) {
     const int cl = idx % CC;
     const int kw = idx / CC;
@@ -121,14 +128,17 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
 #pragma unroll
       for (int q = 0; q < 8; ++q) d[q] = wv[q];
     }
+    if (SPLIT_Y) {
+      uint32_t sum = 0u;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) sum = __builtin_amdgcn_sad_u8(d[q], 0u, sum);
+      if (sum != 0u) atomicAdd(&colsum[cl], (int32_t)sum);
+    }
     uint8_t* dst = wl + cl * wstride + kw * 32;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       v4u lo = {d[4 * h], d[4 * h + 1], d[4 * h + 2], d[4 * h + 3]};
-      if (SPLIT_W) {
-        *reinterpret_cast<v4u*>(dst + part_bytes + 16 * h) = (lo >> 7) & 0x01010101u;
-        lo = lo & 0x7f7f7f7fu;
-      }
+      if (SPLIT_W) lo = lo ^ 0x80808080u;           // codes - 128, padding included
       *reinterpret_cast<v4u*>(dst + 16 * h) = lo;
     }
   }
@@ -176,7 +186,7 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
     }
   };
 
-  v4i acc1[2][NTC], acc7[2][NTC], acc14[2][NTC];
+  v4i acc[2][NTC], rsum[2];                          // products; row sums of Y (8-bit W only)
 
   // LW steps on the matrix cores for one tile: two per loaded word (one for LW = 1).  A
   // step's 16 bytes of W sit at kb in its column's LDS row, for both forms of Y.
@@ -184,12 +194,10 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
     constexpr int mt = decltype(mt_c)::value;
 #pragma unroll
     for (int k = 0; k < WPL; ++k) {
-      uint32_t codes[8], top = 0u;                  // the word's 32 codes; its plane 7
+      uint32_t codes[8];                            // the word's 32 codes
       if (!p.y_bytes) {
 #pragma unroll
         for (int pl = 0; pl < 8; ++pl) codes[pl] = raw[pl * WPL + k];
-        top = codes[7];
-        if (SPLIT_Y) codes[7] = 0u;                 // seven low planes -> bytes below 128
         planes_word_to_codes(codes);
       }
 #pragma unroll
@@ -197,42 +205,30 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
         const int j = 2 * k + h;
         const int kb = p.y_bytes ? (ss * LW + j) * 64 + g * 16
                                  : (LW == 1 ? ss * 64 + g * 16 : ss * SSW * 32 + g * 16 * LW + j * 16);
-        v4i a7, ab = {0, 0, 0, 0};
+        uint32_t d[4];
         if (p.y_bytes) {
-          const uint32_t d0 = raw[4 * j], d1 = raw[4 * j + 1], d2 = raw[4 * j + 2], d3 = raw[4 * j + 3];
-          if (SPLIT_Y) {
-            a7 = (v4i){(int)(d0 & 0x7f7f7f7fu), (int)(d1 & 0x7f7f7f7fu), (int)(d2 & 0x7f7f7f7fu), (int)(d3 & 0x7f7f7f7fu)};
-            ab = (v4i){(int)((d0 >> 7) & 0x01010101u), (int)((d1 >> 7) & 0x01010101u),
-                       (int)((d2 >> 7) & 0x01010101u), (int)((d3 >> 7) & 0x01010101u)};
-          } else {
-            a7 = (v4i){(int)d0, (int)d1, (int)d2, (int)d3};
-          }
+          d[0] = raw[4 * j]; d[1] = raw[4 * j + 1]; d[2] = raw[4 * j + 2]; d[3] = raw[4 * j + 3];
         } else {
           // words 0..3 or 4..7 of the codes; LW = 1: the half of the word this lane owns
           // (chosen with a lane mask: a select between two array elements would become an
           // indexed access to an array in scratch memory)
           const uint32_t hi = LW == 1 ? 0u - (uint32_t)(g & 1) : (h != 0 ? 0xffffffffu : 0u);
-          uint32_t d[4], t[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            d[i] = (codes[4 + i] & hi) | (codes[i] & ~hi);
-            // bit 0 of byte b of word r: plane 7 at K position 8 b + r
-            t[i] = (top >> (i + (int)(hi & 4u))) & 0x01010101u;
-          }
-          a7 = (v4i){(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
-          if (SPLIT_Y) ab = (v4i){(int)t[0], (int)t[1], (int)t[2], (int)t[3]};
+          for (int i = 0; i < 4; ++i) d[i] = (codes[4 + i] & hi) | (codes[i] & ~hi);
+        }
+        if (SPLIT_Y) {                              // codes - 128
+#pragma unroll
+          for (int i = 0; i < 4; ++i) d[i] ^= 0x80808080u;
+        }
+        const v4i av = {(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
+        if (SPLIT_W) {
+          const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+          rsum[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, ones, rsum[mt], 0, 0, 0);
         }
 #pragma unroll
         for (int nt = 0; nt < NTC; ++nt) {
-          const uint8_t* src = wl + (nt * 16 + ln) * wstride + kb;
-          const v4i b7 = *reinterpret_cast<const v4i*>(src);
-          v4i bb = {0, 0, 0, 0};
-          if (SPLIT_W) bb = *reinterpret_cast<const v4i*>(src + part_bytes);
-          acc1[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a7, b7, acc1[mt][nt], 0, 0, 0);
-          if (SPLIT_Y) acc7[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab, b7, acc7[mt][nt], 0, 0, 0);
-          if (SPLIT_W) acc7[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a7, bb, acc7[mt][nt], 0, 0, 0);
-          if (SPLIT_Y && SPLIT_W)
-            acc14[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab, bb, acc14[mt][nt], 0, 0, 0);
+          const v4i bv = *reinterpret_cast<const v4i*>(wl + (nt * 16 + ln) * wstride + kb);
+          acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv, acc[mt][nt], 0, 0, 0);
         }
       }
     }
@@ -250,13 +246,11 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
     const int row0 = rg * kRowsPerGroup;
     if (ss == 0) {
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+      for (int mt = 0; mt < 2; ++mt) {
+        rsum[mt] = (v4i){0, 0, 0, 0};
 #pragma unroll
-        for (int nt = 0; nt < NTC; ++nt) {
-          acc1[mt][nt] = (v4i){0, 0, 0, 0};
-          acc7[mt][nt] = (v4i){0, 0, 0, 0};
-          acc14[mt][nt] = (v4i){0, 0, 0, 0};
-        }
+        for (int nt = 0; nt < NTC; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
+      }
     }
     compute_tile(buf0, ss, std::integral_constant<int, 0>{});
     int nrg = rg, nss = ss + 1;
@@ -276,10 +270,10 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(const UpdParams p) {
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          uint32_t v = (uint32_t)acc1[mt][nt][r];
-          if (SPLIT_Y || SPLIT_W) v += (uint32_t)acc7[mt][nt][r] << 7;
-          if (SPLIT_Y && SPLIT_W) v += (uint32_t)acc14[mt][nt][r] << 14;
-          z[mt][r] = v;
+          uint32_t corr = 0u;                       // see the top of the file
+          if (SPLIT_W) corr += (uint32_t)rsum[mt][r];
+          if (SPLIT_Y) corr += (uint32_t)colsum[nt * 16 + ln];
+          z[mt][r] = (uint32_t)acc[mt][nt][r] + (corr << 7);
         }
       if (e.mode == QGTC_OUT_I32) {
 #pragma unroll
@@ -349,7 +343,7 @@ int pick_lw(const UpdParams& p) {
 size_t lds_bytes(const UpdParams& p, int ntc, int lw) {
   const int ssw = 2 * lw;
   const int kpad = cdiv(p.kwords, ssw) * ssw * 32;
-  return (size_t)(p.t == 8 ? 2 : 1) * 16 * ntc * (size_t)(kpad + kPad);
+  return (size_t)16 * ntc * (size_t)(kpad + kPad) + (size_t)16 * ntc * sizeof(int32_t);
 }
 
 int pick_ntc(const UpdParams& p) {
@@ -375,7 +369,7 @@ qgtc_status launch(const UpdParams& p, hipStream_t stream) {
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, update_mfma_kernel<SY, SW, NTC, LW>, 256, 0) != hipSuccess ||
         n < 1)
       n = 1;
-    by_regs = n > 2 ? 2 : n;
+    by_regs = n > 3 ? 3 : n;
   }
   int per_cu = by_regs;
   const int by_lds = (int)((size_t)(160 * 1024) / (lds + 256));

@@ -19,10 +19,13 @@
            second loop) against the same product on the int8 matrix cores, s = t = 1..8, at
            the update shapes of configs 4 and 5, int32 and low-bit outputs: the measurement
            behind the selector's rule for the update (qgtc_plan_layer)
+  streaming the HBM-bound kernels one at a time at the shapes of configs 4 and 5: packing the
+           adjacency and the features, the zero-tile map and statistics, the update on the
+           matrix cores from planes and from bytes; achieved TB/s of algorithmic bytes
   tiles    cost of an adjacency bit by tile width (16 x 32 / 64 / 128) on configs 4 and 5:
            the measurement behind the selector's tile-width rule
 
-Run:  python -m paper_2111_09547_amd.sweeps [table3|config3|config5|sizes|reuse|transfer|gate|tiles ...]
+Run:  python -m paper_2111_09547_amd.sweeps [table3|config3|config5|sizes|reuse|transfer|gate|streaming|tiles ...]
 Prints one JSON line per measurement and a markdown table per sweep."""
 from __future__ import annotations
 
@@ -316,6 +319,66 @@ def gate():
               f"{r['us_popcount_bits']} ({r['gbps_popcount_bits']}) | {r['us_mfma_bits']} ({r['gbps_mfma_bits']}) |")
 
 
+def streaming():
+    """Each kernel alone on the device (in a forward pass the packing of A and of X overlap on
+    two streams and share the bandwidth)."""
+    gen = torch.Generator(device="cuda").manual_seed(14)
+    rows = []
+
+    def case(name, fn, nbytes, kind):
+        t = _kernel_us(fn, kind, n=10, warm=3)
+        rec = {"sweep": "streaming", "kernel": name, "us": round(t, 1), "MiB": round(nbytes / 2 ** 20, 1),
+               "TBps": round(nbytes / t / 1e6, 2), "frac_of_8TBps": round(nbytes / t / 8e6, 2)}
+        print(json.dumps(rec), flush=True)
+        rows.append(rec)
+
+    for (cfg, n, blk, d, h) in ((4, 65536, 1024, 128, 64), (5, 262144, 2048, 512, 16)):
+        a8 = (torch.rand((n, blk), device="cuda", generator=gen) < 0.006).to(torch.uint8)
+        ab = q.alloc_bits(n, blk, 1, q.LEFT, blk)
+        case(f"config {cfg}: pack A, uint8 {n} x {blk} -> 1 bit", lambda: q.qgtc_pack_bits(a8, 1, q.LEFT, out=ab),
+             n * blk * (1 + 1 / 8), q.KERNEL_PACK)
+        del a8
+        for kb in (128, 32):
+            m = q.qgtc_build_tile_map(ab, 16, kb)
+            case(f"config {cfg}: zero-tile map 16 x {kb} (list, total and run length, degrees)",
+                 lambda: q.qgtc_build_tile_map(ab, 16, kb, out=m), n * blk / 8, q.KERNEL_TILE_MAP)
+        cnt = q.qgtc_tile_stats(ab)
+        case(f"config {cfg}: tile statistics at three widths", lambda: q.qgtc_tile_stats(ab, out=cnt), n * blk / 8,
+             q.KERNEL_TILE_MAP)
+        x = torch.randn((n, d), device="cuda", generator=gen)
+        xr = (float(x.min()), float(x.max()))
+        for s in (8, 4, 1):
+            xb = q.alloc_bits(n, d, s, q.RIGHT)
+            case(f"config {cfg}: pack X, fp32 {n} x {d} -> {s} planes", lambda: q.qgtc_pack_bits(x, s, q.RIGHT, quant=xr, out=xb),
+                 n * d * (4 + s / 8), q.KERNEL_PACK)
+        xl = q.alloc_bits(n, d, 8, q.LEFT_BYTES)
+        case(f"config {cfg}: pack X, fp32 {n} x {d} -> bytes", lambda: q.qgtc_pack_bits(x, 8, q.LEFT_BYTES, quant=xr, out=xl),
+             n * d * 5, q.KERNEL_PACK)
+        del x
+        for s in (8, 7, 4):
+            yq = torch.randint(0, 2 ** s, (n, d), device="cuda", dtype=torch.int32, generator=gen)
+            wq = torch.randint(0, 2 ** s, (d, h), device="cuda", dtype=torch.int32, generator=gen)
+            yb = q.qgtc_pack_bits(yq, s, q.LEFT, out=q.alloc_bits(n, d, s, q.LEFT, ld_words=-(-d // 32)))
+            yl = q.qgtc_pack_bits(yq, s, q.LEFT_BYTES)
+            wb = q.qgtc_pack_bits(wq, s, q.RIGHT)
+            ob = q.alloc_bits(n, h, s, q.RIGHT)
+            oi = torch.empty((n, h), dtype=torch.int32, device="cuda")
+            ep_b = q.Epilogue(mode=q.OUT_BITS, relu=True, rq_nbits=s, rq_lo=0, rq_inv_scale=1e-3)
+            case(f"config {cfg}: update {n} x {d} -> {h}, {s}-bit planes, int32 out",
+                 lambda: q.qgtc_update(yb, wb, q.Epilogue(mode=q.OUT_I32), out=oi), n * d * s / 8 + n * h * 4, q.KERNEL_UPDATE)
+            case(f"config {cfg}: update {n} x {d} -> {h}, {s}-bit planes, low-bit out",
+                 lambda: q.qgtc_update(yb, wb, ep_b, out=ob), n * d * s / 8 + n * h * s / 8, q.KERNEL_UPDATE)
+            case(f"config {cfg}: update {n} x {d} -> {h}, {s}-bit codes as bytes, low-bit out",
+                 lambda: q.qgtc_update(yl, wb, ep_b, out=ob), n * d + n * h * s / 8, q.KERNEL_UPDATE)
+            del yq, yb, yl, ob, oi
+        del ab
+        torch.cuda.empty_cache()
+    print("\n| kernel (alone on the device) | us | algorithmic MiB | TB/s | fraction of 8 TB/s |")
+    print("|---|---|---|---|---|")
+    for r in rows:
+        print(f"| {r['kernel']} | {r['us']} | {r['MiB']} | {r['TBps']} | {r['frac_of_8TBps']} |")
+
+
 def tiles():
     """One fused layer (8 bits, first layer's shape) per tile width: time per visited adjacency bit."""
     from workloads import make_workload
@@ -352,10 +415,10 @@ def tiles():
 
 def main():
     torch.cuda.set_device(0)
-    which = sys.argv[1:] or ["table3", "config3", "config5", "sizes", "reuse", "transfer", "gate", "tiles"]
+    which = sys.argv[1:] or ["table3", "config3", "config5", "sizes", "reuse", "transfer", "gate", "streaming", "tiles"]
     for name in which:
         {"table3": table3, "config3": config3, "config5": config5, "sizes": sizes, "reuse": reuse,
-         "transfer": transfer, "gate": gate, "tiles": tiles}[name]()
+         "transfer": transfer, "gate": gate, "streaming": streaming, "tiles": tiles}[name]()
 
 
 if __name__ == "__main__":

@@ -116,6 +116,37 @@ def test_tile_map_matches_brute_force(tile):
     assert (m.deg.cpu().numpy() == deg).all()
 
 
+@pytest.mark.parametrize("shape", [(1, 1), (100, 300), (257, 257), (1000, 2100), (4100, 640)])
+def test_tile_stats_match_the_oracle_at_three_widths(shape):
+    """qgtc_tile_stats: non-zero tiles at 16 x 32 / 64 / 128 in one pass, against the brute-force
+    tile map of the oracle and against the three maps built one by one."""
+    n, k = shape
+    rng = np.random.default_rng([5, n, k])
+    A = rand_graph(rng, n, k, 0.004)
+    if n > 64:
+        A[40:90, :] = 0                             # rows of tiles without any edge
+    Ab = pack_adjacency(A)
+    got = q.qgtc_tile_stats(Ab).cpu().numpy().tolist()
+    want = [sum(len(l) for l in qgnn.tile_map(A, 16, kb)[0]) for kb in (32, 64, 128)]
+    assert got == want + [-(-n // 16)]
+    for i, kb in enumerate((32, 64, 128)):
+        assert int(q.qgtc_build_tile_map(Ab, 16, kb).nnz_tiles.cpu()[0]) == want[i]
+    # a second call into the same buffer starts from zero again
+    buf = q.qgtc_tile_stats(Ab)
+    assert q.qgtc_tile_stats(Ab, out=buf).cpu().numpy().tolist() == got
+
+
+def test_tile_stats_on_block_diagonal_storage():
+    w = make_workload(5, n_blocks=2)
+    g = w.graph
+    Ab = pack_adjacency(g, "compact")
+    got = q.qgtc_tile_stats(Ab).cpu().numpy().tolist()
+    compact = g.dense_compact()
+    want = [sum(len(l) for l in qgnn.tile_map(compact, 16, kb)[0]) for kb in (32, 64, 128)]
+    assert got == want + [g.n_nodes // 16]
+    assert want[0] > want[1] > want[2]
+
+
 def expected_run_log2(cnt):
     """The rule stated for nnz_tiles[1] in qgtc.h, on the host."""
     w = np.asarray(cnt, dtype=np.int64) + 1
