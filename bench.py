@@ -144,11 +144,11 @@ def side_config(cfg, bits, steps, warmup, w=None):
 
 
 # ---------------------------------------------------------------- HBM traffic (rocprofv3)
-def traffic_child(cfg, bits):
+def traffic_child(cfg, bits, tile_kbits="auto"):
     """What the counter runs execute: a device-to-device copy of known size (the reference
     the counters are scaled by), then a few forward passes."""
     import torch
-    w, net, A_src, Ws, X, xr, ranges, out = make_net(cfg, bits, 128)
+    w, net, A_src, Ws, X, xr, ranges, out = make_net(cfg, bits, tile_kbits)
     src = torch.ones(1 << 26, dtype=torch.int32, device="cuda")      # 256 MiB
     dst = torch.empty_like(src)
     torch.cuda.synchronize()
@@ -161,7 +161,7 @@ def traffic_child(cfg, bits):
     print(json.dumps({"copy_kib": src.numel() * 4 // 1024}))
 
 
-def measure_traffic(cfg, bits, kernel_substr="layer_kernel", timeout=150):
+def measure_traffic(cfg, bits, kernel_substr="layer_kernel", timeout=150, tile_kbits="auto"):
     """HBM bytes per launch of the dominant kernel (read + written), from two rocprofv3
     counter runs of this script (FETCH_SIZE, then WRITE_SIZE, KiB-like units per dispatch),
     each scaled by what the same counter reads for a plain copy of known size.  None when
@@ -174,7 +174,7 @@ def measure_traffic(cfg, bits, kernel_substr="layer_kernel", timeout=150):
         with tempfile.TemporaryDirectory(dir="/tmp") as tmp:
             cmd = [rocprof, "--pmc", counter, "--kernel-trace", "--output-format", "csv", "-d", tmp, "--",
                    sys.executable, os.path.abspath(__file__), "--traffic-child", "--config", str(cfg),
-                   "--bits", str(bits)]
+                   "--bits", str(bits), "--tile-kbits", str(tile_kbits)]
             env = dict(os.environ, TMPDIR="/tmp")
             try:
                 proc = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE,
@@ -267,7 +267,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="workload of the headline line (3, 4 or 5)")
     ap.add_argument("--bits", type=int, default=8)
-    ap.add_argument("--tile-kbits", type=int, default=128)
+    ap.add_argument("--tile-kbits", default="auto",
+                    help="width of the zero-tile map's tiles: 32, 64, 128 or auto (the library's selector, "
+                         "decided once per adjacency)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--no-traffic", action="store_true", help="skip the two rocprofv3 counter runs")
@@ -276,6 +278,8 @@ def main():
                     help="only run a 1 GiB device-to-device copy 5 times (reference point for "
                          "the FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
+    if args.tile_kbits != "auto":
+        args.tile_kbits = int(args.tile_kbits)
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path "
               "(subgraph batches would be sharded with no collective); run with --gpus 1",
@@ -287,7 +291,7 @@ def main():
     traffic, traffic_note = (None, "skipped")
     dom_guess = "layer_kernel" if args.bits <= 8 else "aggregate_kernel"
     if not (args.no_traffic or args.traffic_child or args.copy_calibration):
-        traffic, traffic_note = measure_traffic(args.config, args.bits, dom_guess)
+        traffic, traffic_note = measure_traffic(args.config, args.bits, dom_guess, tile_kbits=args.tile_kbits)
 
     import torch
     import paper_2111_09547_amd as q
@@ -295,7 +299,7 @@ def main():
 
     torch.cuda.set_device(0)
     if args.traffic_child:
-        traffic_child(args.config, args.bits)
+        traffic_child(args.config, args.bits, args.tile_kbits)
         return
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")      # 1 GiB
@@ -345,7 +349,7 @@ def main():
 
     # the same forward pass as separate aggregation and update kernels (what the fused
     # layer kernel replaces)
-    planes = QuantGNN(A_src, Ws, w.s, w.t, self_term, tile_kbits=args.tile_kbits,
+    planes = QuantGNN(A_src, Ws, w.s, w.t, self_term, tile_kbits=net.map.c.tile_kbits,
                       block_rows=block_rows, weights_as_bytes=False,
                       tuning=q.Tuning(layer_path=q.LAYER_TWO_KERNELS))
     for _ in range(3):

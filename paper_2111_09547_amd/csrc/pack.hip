@@ -130,41 +130,54 @@ __device__ __forceinline__ uint32_t squeeze4(uint32_t d) {
   return t & 0xfu;
 }
 
-// A unit is 1024 columns of one row (64 lanes x 16 bytes); a wave takes kU8Units units
-// at a time, all of their loads in flight together, and walks over the matrix with the
-// stride of the grid, so that a launch is a few thousand long-lived waves rather than
-// one short wave per row.
-constexpr int kU8Units = 8;
+// A unit is 1024 columns of one row (64 lanes x 16 bytes); a wave takes UNITS units, all
+// of their loads in flight together.  Measured on 64 MiB to 1 GiB of input with 1, 2, 4
+// and 8 units per wave and grids capped at 2048 to 8192 workgroups or not at all: two units
+// and one wave per pair of units is the fastest or level everywhere (5.0 - 5.7 TB/s of
+// read + written bytes from 128 MiB on).
+constexpr int kU8Units = 2;
 
+template <int UNITS>
 __global__ __launch_bounds__(256) void pack_left_u8_kernel(const PackParams p) {
   const int lane = threadIdx.x & 63;
   const int n_words = (int)p.ld;
   const int n_pass = (n_words + 31) >> 5;          // units per row
   const int64_t n_units = (int64_t)p.rows * n_pass;
-  const int64_t wave_id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int64_t n_waves = (int64_t)gridDim.x * 4;
+  const int64_t wave_id = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t step = (int64_t)gridDim.x * 4 * UNITS;
+  // (row, unit within the row) of the wave's first unit and of the stride: one division
+  // each per wave, then additions only
+  int64_t r0 = wave_id * UNITS / n_pass;
+  int q0 = (int)(wave_id * UNITS % n_pass);
+  const int64_t step_r = step / n_pass;
+  const int step_q = (int)(step % n_pass);
   const uint8_t* src = reinterpret_cast<const uint8_t*>(p.src);
-  for (int64_t u0 = wave_id * kU8Units; u0 < n_units; u0 += n_waves * kU8Units) {
-    uint4 v[kU8Units];
+  for (int64_t u0 = wave_id * UNITS; u0 < n_units; u0 += step) {
+    uint4 v[UNITS];
+    int64_t r = r0;
+    int q = q0;
 #pragma unroll
-    for (int k = 0; k < kU8Units; ++k) {
-      const int64_t u = u0 + k;
-      const int64_t r = u / n_pass;
-      const int c = (int)(u % n_pass) * 1024 + lane * 16;
+    for (int k = 0; k < UNITS; ++k) {
+      const int c = q * 1024 + lane * 16;
       v[k] = make_uint4(0u, 0u, 0u, 0u);
-      if (u < n_units && c < p.cols) v[k] = *reinterpret_cast<const uint4*>(src + r * p.ld_src + c);
+      if (r < p.rows && c < p.cols) v[k] = *reinterpret_cast<const uint4*>(src + r * p.ld_src + c);
+      if (++q == n_pass) { q = 0; ++r; }
     }
+    r = r0;
+    q = q0;
 #pragma unroll
-    for (int k = 0; k < kU8Units; ++k) {
-      const int64_t u = u0 + k;
-      const int64_t r = u / n_pass;
-      const int w = (int)(u % n_pass) * 32 + (lane >> 1);
+    for (int k = 0; k < UNITS; ++k) {
+      const int w = q * 32 + (lane >> 1);
       const uint32_t h = squeeze4(v[k].x) | (squeeze4(v[k].y) << 4) | (squeeze4(v[k].z) << 8) |
                          (squeeze4(v[k].w) << 12);
       // odd lane's half moves down to the even lane (wave shift left by one lane)
       const uint32_t up = (uint32_t)__shfl_down((int)h, 1, 64);
-      if ((lane & 1) == 0 && u < n_units && w < n_words) p.dst[r * p.ld + w] = h | (up << 16);
+      if ((lane & 1) == 0 && r < p.rows && w < n_words) p.dst[r * p.ld + w] = h | (up << 16);
+      if (++q == n_pass) { q = 0; ++r; }
     }
+    r0 += step_r;
+    q0 += step_q;
+    if (q0 >= n_pass) { q0 -= n_pass; ++r0; }
   }
 }
 
@@ -352,8 +365,9 @@ qgtc_status launch_pack(const PackParams& p, int layout, hipStream_t s) {
   } else if (SRC == QGTC_SRC_U8 && p.nbits == 1 && (p.cols & 15) == 0 && (p.ld_src & 15) == 0 &&
              ((uintptr_t)p.src & 15u) == 0) {
     const int64_t units = (int64_t)p.rows * cdiv(p.ld, 32);
-    const int64_t blocks = cdiv(units, 4 * kU8Units);
-    hipLaunchKernelGGL(pack_left_u8_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, p);
+    const int64_t blocks = cdiv(units, 4 * kU8Units);        // beyond 2^24 workgroups the waves loop
+    hipLaunchKernelGGL(pack_left_u8_kernel<kU8Units>, dim3((unsigned)(blocks < (1 << 24) ? blocks : (1 << 24))),
+                       dim3(256), 0, s, p);
   } else {
     hipLaunchKernelGGL((pack_left_kernel<SRC>), dim3((unsigned)cdiv(p.rows, 4)), dim3(256), 0, s, p);
   }
