@@ -470,6 +470,25 @@ qgtc_status qgtc_fold_batchnorm(const double* gamma, const double* beta, const d
                                 const double* var, double eps, double value_scale, int32_t n,
                                 float* col_scale, float* col_shift);
 
+/* What the library found on the current device, against what its kernels are written
+ * for: code objects for gfx950 only, workgroups dealt over 8 XCDs of 32 compute units
+ * each (Section 4.3's tile rows are spread so that a subgraph's rows share an XCD's L2),
+ * launch shapes sized by the compute-unit count read from the device.
+ *   compute_units   of the current device (multiprocessor count)
+ *   xcds            compute_units / 32
+ *   is_gfx950       1 when the device's architecture name starts with "gfx950"
+ *   xcds_assumed    8
+ * QGTC_OK when the device is gfx950 (a partition with fewer XCDs runs correctly: the
+ * dealing is a permutation of workgroup ids whatever the hardware), QGTC_ERR_UNSUPPORTED
+ * otherwise, QGTC_ERR_HIP when no device can be queried.  Host call, no launch. */
+typedef struct qgtc_device {
+  int32_t compute_units;
+  int32_t xcds;
+  int32_t is_gfx950;
+  int32_t xcds_assumed;
+} qgtc_device;
+qgtc_status qgtc_device_info(qgtc_device* out);
+
 /* Library version, major*10000 + minor*100 + patch. */
 int32_t qgtc_version(void);
 

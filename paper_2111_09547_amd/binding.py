@@ -82,6 +82,11 @@ class _LayerSpecC(C.Structure):
                 ("out_hi", C.c_double)]
 
 
+class _DeviceC(C.Structure):
+    _fields_ = [("compute_units", C.c_int32), ("xcds", C.c_int32), ("is_gfx950", C.c_int32),
+                ("xcds_assumed", C.c_int32)]
+
+
 _lib = None
 
 
@@ -128,6 +133,7 @@ def lib():
                                           P(C.c_double), P(C.c_double)]),
         "qgtc_fold_batchnorm": (C.c_int, [P(C.c_double), P(C.c_double), P(C.c_double), P(C.c_double),
                                          C.c_double, C.c_double, i32, P(C.c_float), P(C.c_float)]),
+        "qgtc_device_info": (C.c_int, [P(_DeviceC)]),
         "qgtc_probe_popcount": (C.c_int, [i32, i32, i32, C.c_void_p, C.c_void_p]),
         "qgtc_prof_enable": (C.c_int, [i32]),
         "qgtc_prof_reset": (C.c_int, []),
@@ -443,6 +449,15 @@ def qgtc_fold_batchnorm(gamma, beta, mean, var, eps: float, value_scale: float):
     _check(lib().qgtc_fold_batchnorm(arr(gamma), arr(beta), arr(mean), arr(var), float(eps), float(value_scale),
                                      n, cs, ch), "qgtc_fold_batchnorm")
     return torch.tensor(list(cs), dtype=torch.float32), torch.tensor(list(ch), dtype=torch.float32)
+
+
+def qgtc_device_info() -> dict:
+    """Compute units and XCDs of the current device, and whether it is the gfx950 part the
+    kernels are written for (raises QgtcError when it is not)."""
+    d = _DeviceC()
+    _check(lib().qgtc_device_info(C.byref(d)), "qgtc_device_info")
+    return {"compute_units": d.compute_units, "xcds": d.xcds, "is_gfx950": bool(d.is_gfx950),
+            "xcds_assumed": d.xcds_assumed}
 
 
 def qgtc_probe_popcount(workgroups: int, waves_per_workgroup: int, iters: int, sink: torch.Tensor):

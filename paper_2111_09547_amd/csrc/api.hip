@@ -1,5 +1,6 @@
 // Host-side parts of the C ABI: argument checks, descriptors, the one-layer
 // driver and the optional event-based kernel timing.
+#include <cstring>
 #include <mutex>
 #include <vector>
 
@@ -125,6 +126,25 @@ int device_compute_units() {
   }
   return g_device_cus[dev];
 }
+
+}  // namespace qgtc
+
+extern "C" qgtc_status qgtc_device_info(qgtc_device* out) {
+  if (!out) return QGTC_ERR_NULL;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return QGTC_ERR_HIP;
+  }
+  out->compute_units = prop.multiProcessorCount;
+  out->xcds = prop.multiProcessorCount / 32;
+  out->is_gfx950 = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 0;
+  out->xcds_assumed = 8;
+  return out->is_gfx950 ? QGTC_OK : QGTC_ERR_UNSUPPORTED;
+}
+
+namespace qgtc {
 
 qgtc_status check_tuning(const qgtc_tuning* t) {
   if (!t) return QGTC_OK;

@@ -53,10 +53,14 @@ __global__ __launch_bounds__(256) void tile_list_kernel(const MapParams p) {
 }
 
 // The shape the aggregation kernel uses (16 rows x 32/64/128 bits): one wave per
-// tile row, lane <-> (row = lane % 16, one of four consecutive tile columns =
-// lane / 16), each row read once, 4..16 bytes per load.  A ballot over the wave
-// tells which of the four tiles hold a bit; the same pass counts the degrees.
+// tile row, lane <-> (row = lane % 16, one of four consecutive 128-bit columns =
+// lane / 16).  Rows are padded to 128 bits, so every row is read once with 16-byte
+// loads whatever the tile width, the loads of four iterations (16 columns of a row)
+// issued before the first ballot; a 128-bit column holds 4 / TW tiles, and a ballot per
+// tile over the wave tells which of them hold a bit.  The same pass counts the degrees.
+template <int TW>
 __global__ __launch_bounds__(256) void tile_list16_kernel(const MapParams p) {
+  constexpr int SUB = 4 / TW;                    // tiles per 128-bit column
   const int lane = threadIdx.x & 63;
   const int tr = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (tr >= p.n_tile_rows) return;               // whole wave
@@ -65,52 +69,44 @@ __global__ __launch_bounds__(256) void tile_list16_kernel(const MapParams p) {
   const bool r_ok = r < p.rows;
   const uint32_t* row = p.A + (int64_t)(r_ok ? r : 0) * p.lda;
   int32_t* list = p.col_idx + (int64_t)tr * p.n_tile_cols;
+  const int n128 = (p.n_words + 3) >> 2;
   int count = 0;
   int deg = 0;
-  if (p.tile_words == 4) {
-    // rows are padded to 128 bits: one 16-byte load per tile; the loads of four iterations
-    // (16 tiles of a row) are issued before the first ballot
-    for (int tc0 = 0; tc0 < p.n_tile_cols; tc0 += 16) {
-      uint4 v[4];
+  for (int tc0 = 0; tc0 < n128; tc0 += 16) {
+    uint4 v[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int tc = tc0 + 4 * u + g;
-        v[u] = make_uint4(0u, 0u, 0u, 0u);
-        if (r_ok && tc < p.n_tile_cols) v[u] = *reinterpret_cast<const uint4*>(row + 4 * tc);
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const uint32_t any = v[u].x | v[u].y | v[u].z | v[u].w;
-        deg += __builtin_popcount(v[u].x) + __builtin_popcount(v[u].y) + __builtin_popcount(v[u].z) +
-               __builtin_popcount(v[u].w);
-        const unsigned long long m = __builtin_amdgcn_ballot_w64(any != 0u);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          if (((m >> (16 * k)) & 0xffffull) != 0ull) {   // wave-uniform
-            if (lane == 0) list[count] = tc0 + 4 * u + k;
-            ++count;
-          }
-        }
-      }
+    for (int u = 0; u < 4; ++u) {
+      const int tc = tc0 + 4 * u + g;
+      v[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (r_ok && tc < n128) v[u] = *reinterpret_cast<const uint4*>(row + 4 * tc);
     }
-  } else {
-    for (int tc0 = 0; tc0 < p.n_tile_cols; tc0 += 4) {
-      const int tc = tc0 + g;
-      uint32_t any = 0u;
-      if (r_ok && tc < p.n_tile_cols) {
-        const int w0 = tc * p.tile_words;
-        for (int w = w0; w < w0 + p.tile_words; ++w) {
-          const uint32_t v = row[w];
-          any |= v;
-          deg += __builtin_popcount(v);
-        }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      deg += __builtin_popcount(v[u].x) + __builtin_popcount(v[u].y) + __builtin_popcount(v[u].z) +
+             __builtin_popcount(v[u].w);
+      uint32_t any[SUB];
+      if constexpr (TW == 4) {
+        any[0] = v[u].x | v[u].y | v[u].z | v[u].w;
+      } else if constexpr (TW == 2) {
+        any[0] = v[u].x | v[u].y;
+        any[1] = v[u].z | v[u].w;
+      } else {
+        any[0] = v[u].x; any[1] = v[u].y; any[2] = v[u].z; any[3] = v[u].w;
       }
-      const unsigned long long m = __builtin_amdgcn_ballot_w64(any != 0u);
+      unsigned long long m[SUB];
+#pragma unroll
+      for (int c = 0; c < SUB; ++c) m[c] = __builtin_amdgcn_ballot_w64(any[c] != 0u);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        if (((m >> (16 * k)) & 0xffffull) != 0ull) {   // wave-uniform
-          if (lane == 0) list[count] = tc0 + k;
-          ++count;
+#pragma unroll
+        for (int c = 0; c < SUB; ++c) {
+          const int tile = (tc0 + 4 * u + k) * SUB + c;
+          // wave-uniform; the bound keeps a destination whose row padding was not
+          // zeroed (a contract violation) from writing past the list
+          if (((m[c] >> (16 * k)) & 0xffffull) != 0ull && tile < p.n_tile_cols) {
+            if (lane == 0) list[count] = tile;
+            ++count;
+          }
         }
       }
     }
@@ -322,8 +318,12 @@ extern "C" qgtc_status qgtc_build_tile_map(const qgtc_bits* A, const qgtc_tile_m
   ProfScope prof(QGTC_KERNEL_TILE_MAP, s);
   const bool fused = p.tile_rows == 16 && p.tile_words <= 4;
   if (p.n_tile_rows > 0 && p.n_tile_cols > 0) {
-    if (fused)
-      hipLaunchKernelGGL(tile_list16_kernel, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p);
+    if (fused && p.tile_words == 4)
+      hipLaunchKernelGGL(tile_list16_kernel<4>, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p);
+    else if (fused && p.tile_words == 2)
+      hipLaunchKernelGGL(tile_list16_kernel<2>, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p);
+    else if (fused)
+      hipLaunchKernelGGL(tile_list16_kernel<1>, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p);
     else
       hipLaunchKernelGGL(tile_list_kernel, dim3((unsigned)cdiv(p.n_tile_rows, 4)), dim3(256), 0, s, p);
     if (launch_status() != QGTC_OK) return QGTC_ERR_HIP;

@@ -234,6 +234,16 @@ def test_selector_and_scalar_helpers_on_the_host():
     assert (a.numpy() == ra).all() and (sh.numpy() == rb).all()
 
 
+def test_device_info_rejects_null_and_reports_no_device_without_a_gpu():
+    import torch
+    import paper_2111_09547_amd.binding as b
+    l = b.lib()
+    assert l.qgtc_device_info(None) == 1                      # QGTC_ERR_NULL
+    if not torch.cuda.is_available():
+        d = b._DeviceC()
+        assert l.qgtc_device_info(C.byref(d)) != 0        # no device to query: an error, not a crash
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     import paper_2111_09547_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)

@@ -116,6 +116,16 @@ def test_tile_map_matches_brute_force(tile):
     assert (m.deg.cpu().numpy() == deg).all()
 
 
+
+def test_device_is_what_the_kernels_are_written_for():
+    """The launch shapes read the compute-unit count from the device; the workgroup dealing
+    is written for 8 XCDs of 32 compute units: check both on the device the tests run on."""
+    d = q.qgtc_device_info()
+    assert d["is_gfx950"]
+    assert d["compute_units"] == torch.cuda.get_device_properties(0).multi_processor_count
+    assert d["xcds"] == d["xcds_assumed"] == 8 and d["compute_units"] == 256
+
+
 @pytest.mark.parametrize("shape", [(1, 1), (100, 300), (257, 257), (1000, 2100), (4100, 640)])
 def test_tile_stats_match_the_oracle_at_three_widths(shape):
     """qgtc_tile_stats: non-zero tiles at 16 x 32 / 64 / 128 in one pass, against the brute-force
