@@ -80,6 +80,19 @@ def timed(fn, n):
     return (time.perf_counter() - t0) * 1e3 / n
 
 
+def timed_in_flight(graphs, n):
+    """n graph replays in all, dealt round-robin to one stream per graph: ms per replay."""
+    import torch
+    streams = [torch.cuda.Stream() for _ in graphs]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n):
+        with torch.cuda.stream(streams[i % len(graphs)]):
+            graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / n
+
+
 def kernel_events(fn, steps):
     """Runs fn `steps` times with the library's HIP events around every kernel launch
     (recorded on the launch stream): {kind: (total ms, launches)}."""
@@ -273,6 +286,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--no-traffic", action="store_true", help="skip the two rocprofv3 counter runs")
+    ap.add_argument("--no-in-flight", action="store_true",
+                    help="skip the throughput runs with two and three batches in flight")
     ap.add_argument("--traffic-child", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device-to-device copy 5 times (reference point for "
@@ -344,6 +359,23 @@ def main():
         step()
     ms_step_eager = timed(step, min(args.steps, 50))
 
+    # Throughput with several independent batches in flight: every batch has its own buffers
+    # and its own graph (the same step), replayed round-robin on one stream per batch, so the
+    # drain of one batch's launches overlaps the start of another's.  The headline fields stay
+    # one batch at a time.
+    in_flight = []
+    if not args.no_in_flight:
+        more = [make_net(args.config, args.bits, net.map.c.tile_kbits, w) for _ in range(2)]
+        g_steps = [graph_step] + [m[1].capture(m[4], m[5], m[6], m[7], with_static=True) for m in more]
+        g_layers = [graph_layers] + [m[1].capture(m[4], m[5], m[6], m[7]) for m in more]
+        for k in (2, 3):
+            timed_in_flight(g_steps[:k], 2 * k)
+            in_flight.append({"batches": k, "ms_per_step": timed_in_flight(g_steps[:k], args.steps),
+                              "ms_layers_only": timed_in_flight(g_layers[:k], args.steps)})
+        for m in more:
+            assert torch.equal(m[7], out)               # every batch computed the same output
+        del g_steps, g_layers, more
+
     # the same steps again with HIP events around every kernel launch
     prof = kernel_events(step, args.steps)
 
@@ -411,6 +443,9 @@ def main():
         "tops_equiv_dense": dense_macs / (ms_layers * 1e-3) / 1e12,
         "nominal_tbitops": nominal_ops / (ms_layers * 1e-3) / 1e12,
         "ms_layers_two_kernels": ms_two_kernels,
+        "batches_in_flight": [dict(r, value=total_ops / (r["ms_per_step"] * 1e-3) / 1e12,
+                                   aggregation_frac_of_peak=sum(agg_ops) / (r["ms_layers_only"] * 1e-3) / PEAK_BITOPS)
+                              for r in in_flight],
         "roofline": {"bound": "alu", "kernel": dom_name,
                      "achieved": agg_rate / 1e12, "peak": PEAK_BITOPS / 1e12,
                      "unit": "Tbit-op/s", "frac": agg_rate / PEAK_BITOPS,
