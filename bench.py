@@ -135,7 +135,7 @@ def side_config(cfg, bits, steps, warmup, w=None):
     import torch
     w, net, A_src, Ws, X, xr, ranges, out = make_net(cfg, bits, "auto", w)
     g = w.graph
-    graph = net.capture(X, xr, ranges, out)
+    graph = net.capture(X, xr, ranges, out, streams=net.auto_runs())
     for _ in range(warmup):
         graph.replay()
     ms = timed(graph.replay, steps)
@@ -286,6 +286,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--no-traffic", action="store_true", help="skip the two rocprofv3 counter runs")
+    ap.add_argument("--runs", type=int, default=-1,
+                    help="independent runs of subgraphs (streams) per forward pass; default: what the "
+                         "library's selector says (QuantGNN.auto_runs)")
     ap.add_argument("--no-in-flight", action="store_true",
                     help="skip the throughput runs with two and three batches in flight")
     ap.add_argument("--traffic-child", action="store_true", help=argparse.SUPPRESS)
@@ -337,8 +340,9 @@ def main():
 
     # The step as one HIP graph: the same launches, recorded once, so that the host's
     # per-launch cost (Python + ctypes, ~25 us each) does not limit a step of ~20 launches.
-    graph_step = net.capture(X, xr, ranges, out, with_static=True)
-    graph_layers = net.capture(X, xr, ranges, out)
+    n_runs = net.auto_runs() if args.runs < 0 else args.runs
+    graph_step = net.capture(X, xr, ranges, out, with_static=True, streams=n_runs)
+    graph_layers = net.capture(X, xr, ranges, out, streams=n_runs)
     for _ in range(args.warmup):
         graph_step.replay()
     ms_step = timed(graph_step.replay, args.steps)
@@ -354,6 +358,12 @@ def main():
     ms_step_median = per_step[len(per_step) // 2]
     # features-to-output only (adjacency, map and weights cached, as the paper does)
     ms_layers = timed(graph_layers.replay, args.steps)
+    if n_runs > 1:
+        g1 = net.capture(X, xr, ranges, out)
+        ms_layers_one_run = timed(g1.replay, args.steps)
+        del g1
+    else:
+        ms_layers_one_run = ms_layers
     # the same, launched eagerly from Python
     for _ in range(3):
         step()
@@ -366,8 +376,8 @@ def main():
     in_flight = []
     if not args.no_in_flight:
         more = [make_net(args.config, args.bits, net.map.c.tile_kbits, w) for _ in range(2)]
-        g_steps = [graph_step] + [m[1].capture(m[4], m[5], m[6], m[7], with_static=True) for m in more]
-        g_layers = [graph_layers] + [m[1].capture(m[4], m[5], m[6], m[7]) for m in more]
+        g_steps = [graph_step] + [m[1].capture(m[4], m[5], m[6], m[7], with_static=True, streams=n_runs) for m in more]
+        g_layers = [graph_layers] + [m[1].capture(m[4], m[5], m[6], m[7], streams=n_runs) for m in more]
         for k in (2, 3):
             timed_in_flight(g_steps[:k], 2 * k)
             in_flight.append({"batches": k, "ms_per_step": timed_in_flight(g_steps[:k], args.steps),
@@ -437,7 +447,9 @@ def main():
         "value_update_nominal": sum(upd_ops) / (ms_step * 1e-3) / 1e12,
         "ms_per_step_median": ms_step_median,
         "ms_per_step_eager": ms_step_eager,
-        "launch": "one HIP graph per step (the same kernel launches, recorded once)",
+        "launch": "one HIP graph per step (the same kernel launches, recorded once); the layers of a batch "
+                  f"run as {n_runs} independent run(s) of subgraphs on as many streams inside the graph",
+        "ms_layers_only_one_run": ms_layers_one_run,
         "ms_per_layer": ms_layers / n_layers,
         "ms_layers_only": ms_layers,
         "tops_equiv_dense": dense_macs / (ms_layers * 1e-3) / 1e12,
@@ -451,7 +463,9 @@ def main():
                      "unit": "Tbit-op/s", "frac": agg_rate / PEAK_BITOPS,
                      "avg_launch_ms": dom_avg_ms, "launches": dom_n,
                      "counted": "executed AND+popcount bit-ops of the aggregation only; the update "
-                                "inside the same kernel runs on the matrix cores and is not counted",
+                                "inside the same kernel runs on the matrix cores and is not counted; launch "
+                                "durations are taken with the launches one after the other on one stream",
+                     "frac_in_step": sum(agg_ops) / (ms_layers * 1e-3) / PEAK_BITOPS,
                      "measured_peak": measured_peak / 1e12,
                      "frac_of_measured_peak": agg_rate / measured_peak,
                      "traffic": traffic, "traffic_source": traffic_note},

@@ -382,12 +382,20 @@ qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void* stream);
  * the rules exist once.  Every rule is a measured crossover on MI355X.
  *   in:  rows (nodes), in_cols (D), out_cols (H), s, t,
  *        nnz_tiles[3] from qgtc_tile_stats (all zero: unknown, 128-bit tiles assumed,
- *        every tile of a row counted), n_tile_rows, a_cols (columns of A as stored)
+ *        every tile of a row counted), n_tile_rows, a_cols (columns of A as stored),
+ *        subgraphs (diagonal blocks of a batched adjacency, Section 4.1; 0: unknown or one)
  *   out: tile_kbits     32, 64 or 128: least executed work, tiles x width x cost per bit
  *                       (a narrower tile must win by 2 %)
  *        fused          1: qgtc_layer runs as one kernel (s, t <= 8, D <= 1024, H <= 256)
  *        update_path    1 popcount, 2 int8 matrix cores: the stand-alone update's kernel
  *        ksplit         waves of a fused workgroup that split a tile list (1, 2, 4)
+ *        runs           independent runs of whole subgraphs to issue the layer as, one stream
+ *                       each (1 or 2): subgraphs share no edge, so a batch can be cut between
+ *                       them; 2 when the fused launch is short (at most two rounds of the
+ *                       device's wave slots), where the drain of one run's launch then
+ *                       overlaps the other run's work (measured on config 4: 434 against
+ *                       464 us for five layers).  A run is then launched with the K split of
+ *                       the whole batch (qgtc_tuning.layer_ksplit = ksplit)
  *        est_us_aggregate_first, est_us_update_first
  *                       rough times of (A.X).W and A.(X.W) from the measured rates; the two
  *                       orders are different quantized networks (the requantization sits
@@ -398,7 +406,7 @@ typedef struct qgtc_plan_in {
   int32_t s, t;
   int32_t n_tile_rows;
   int32_t a_cols;
-  int32_t reserved;
+  int32_t subgraphs;
   int64_t nnz_tiles[3];
 } qgtc_plan_in;
 
@@ -409,6 +417,8 @@ typedef struct qgtc_plan_out {
   int32_t ksplit;
   double est_us_aggregate_first;
   double est_us_update_first;
+  int32_t runs;
+  int32_t reserved;
 } qgtc_plan_out;
 
 qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* out);

@@ -65,13 +65,13 @@ class _EpilogueC(C.Structure):
 class _PlanInC(C.Structure):
     _fields_ = [("rows", C.c_int32), ("in_cols", C.c_int32), ("out_cols", C.c_int32),
                 ("s", C.c_int32), ("t", C.c_int32), ("n_tile_rows", C.c_int32),
-                ("a_cols", C.c_int32), ("reserved", C.c_int32), ("nnz_tiles", C.c_int64 * 3)]
+                ("a_cols", C.c_int32), ("subgraphs", C.c_int32), ("nnz_tiles", C.c_int64 * 3)]
 
 
 class _PlanOutC(C.Structure):
     _fields_ = [("tile_kbits", C.c_int32), ("fused", C.c_int32), ("update_path", C.c_int32),
                 ("ksplit", C.c_int32), ("est_us_aggregate_first", C.c_double),
-                ("est_us_update_first", C.c_double)]
+                ("est_us_update_first", C.c_double), ("runs", C.c_int32), ("reserved", C.c_int32)]
 
 
 class _LayerSpecC(C.Structure):
@@ -410,10 +410,11 @@ def qgtc_tile_stats(A: Bits, out: torch.Tensor | None = None) -> torch.Tensor:
 
 
 def qgtc_plan_layer(rows: int, in_cols: int, out_cols: int, s: int, t: int, n_tile_rows: int = 0,
-                    a_cols: int = 0, nnz_tiles=(0, 0, 0)) -> dict:
+                    a_cols: int = 0, nnz_tiles=(0, 0, 0), subgraphs: int = 0) -> dict:
     """The library's selector for one layer (host-only); nnz_tiles: the first three numbers
     of qgtc_tile_stats."""
-    pin = _PlanInC(rows, in_cols, out_cols, s, t, n_tile_rows, a_cols, 0, (C.c_int64 * 3)(*[int(v) for v in nnz_tiles]))
+    pin = _PlanInC(rows, in_cols, out_cols, s, t, n_tile_rows, a_cols, int(subgraphs),
+                   (C.c_int64 * 3)(*[int(v) for v in nnz_tiles]))
     pout = _PlanOutC()
     _check(lib().qgtc_plan_layer(C.byref(pin), C.byref(pout)), "qgtc_plan_layer")
     return {k: getattr(pout, k) for k, _ in _PlanOutC._fields_}

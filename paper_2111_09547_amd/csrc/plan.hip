@@ -55,7 +55,8 @@ using namespace qgtc;
 
 extern "C" qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* out) {
   if (!in || !out) return QGTC_ERR_NULL;
-  if (in->rows < 0 || in->in_cols < 1 || in->out_cols < 1 || in->n_tile_rows < 0 || in->a_cols < 0)
+  if (in->rows < 0 || in->in_cols < 1 || in->out_cols < 1 || in->n_tile_rows < 0 || in->a_cols < 0 ||
+      in->subgraphs < 0)
     return QGTC_ERR_SHAPE;
   if (in->s < 1 || in->s > 32 || in->t < 1 || in->t > 32) return QGTC_ERR_BITWIDTH;
   for (int k = 0; k < 3; ++k)
@@ -78,6 +79,18 @@ extern "C" qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* ou
   int cgw = 1, ksplit = 1;
   plan_layer_shape(in->n_tile_rows, in->in_cols, in->s, &cgw, &ksplit);
   out->ksplit = ksplit;
+  // Independent runs: a short fused launch (at most two rounds of the wave slots) leaves
+  // the device part empty while it drains; two runs of whole subgraphs on two streams
+  // overlap one run's drain with the other's work.  Runs of at least eight subgraphs, so
+  // that the XCD dealing inside a run still has one subgraph per XCD.
+  out->runs = 1;
+  out->reserved = 0;
+  if (out->fused && in->subgraphs >= 16 && in->subgraphs % 2 == 0) {
+    const int planes = in->s > 8 ? 8 : in->s;
+    const int per_simd = planes >= 5 ? 3 : (planes >= 3 ? 4 : 5);
+    const int64_t slots = (int64_t)device_compute_units() * 4 * per_simd;
+    if ((int64_t)in->n_tile_rows * cgw * ksplit <= 2 * slots) out->runs = 2;
+  }
 
   // rough times of the two orders of the products
   const double bits = 16.0 * kTileBits[best] * kTileCost[best] * tiles;   // adjacency bits visited, weighted

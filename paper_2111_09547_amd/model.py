@@ -333,11 +333,14 @@ class QuantGNN:
         streams > 1 (block-diagonal storage): the subgraphs are cut into that many
         independent runs, each issued on a stream of its own, so that the start and the
         drain of one run's kernels overlap with the other runs' work.  A list gives the
-        number of subgraphs of each run instead ([48, 16]: the first 48, then 16).
+        number of subgraphs of each run instead ([48, 16]: the first 48, then 16); "auto"
+        takes auto_runs() (resolve it before recording a graph: it reads the tile map back).
         x_packed: the features are already packed (pack_static(X, x_range)).
         x_bits: the features as packed planes that live elsewhere (a SubgraphPacket's,
         packed on the host with the same x_range); X is then not read (single run only)."""
         n = self.A.rows
+        if streams == "auto":
+            streams = self.auto_runs()
         if out is None:
             out = torch.empty((n, self.dims[-1][1]), dtype=torch.int32 if want_int else torch.float32,
                               device=self.A.words.device)
@@ -379,6 +382,9 @@ class QuantGNN:
         library's launches are plain kernel launches on the current stream (no memset, no
         synchronization), the runs on side streams fork from and join the capturing stream
         through events, so the whole pass is one graph launch for the host."""
+        if streams == "auto":
+            streams = self.auto_runs()
+
         def run():
             if with_static:
                 self.pack_static(X, x_range)
@@ -398,9 +404,47 @@ class QuantGNN:
             run()
         return graph
 
+    def auto_runs(self) -> int:
+        """Independent runs of subgraphs to issue a forward pass as (the selector's `runs`,
+        the largest over the layers), 1 unless the adjacency is stored block-diagonally and
+        the two halves of the batch hold the same work within 15 % (the tile counts are read
+        back once: this synchronizes; call it at set-up)."""
+        if getattr(self, "_auto_runs", None) is not None:
+            return self._auto_runs
+        runs = 1
+        br = self.A.c.block_rows
+        if br > 0 and br % 32 == 0 and self.map is not None and not self.update_first:
+            n_blocks = -(-self.A.rows // br)
+            n_tr = -(-self.A.rows // 16)
+            runs = max(B.qgtc_plan_layer(self.A.rows, d, h, self.s, self.t, n_tile_rows=n_tr, a_cols=self.A.cols,
+                                         subgraphs=n_blocks)["runs"] for d, h in self.dims)
+            if runs > 1:
+                cnt = self.map.row_cnt.cpu().to(torch.int64) + 1       # a tile row: its tiles plus a fixed part
+                half = (n_blocks // 2) * br // 16
+                a, b = int(cnt[:half].sum()), int(cnt[half:].sum())
+                if max(a, b) > 1.15 * min(a, b):
+                    runs = 1
+        self._auto_runs = runs
+        return runs
+
+    def _run_tuning(self, l: int, whole_batch: bool):
+        """Tuning of layer l.  A run that covers part of the batch shares the device with the
+        other runs: it takes the K split the whole batch would get from the selector, not the
+        one its own (smaller) number of tile rows suggests - that one would split the tile
+        lists to fill a device the other runs are already filling."""
+        if whole_batch or (self.tuning is not None and self.tuning.layer_ksplit):
+            return self.tuning
+        d, h = self.dims[l]
+        k = B.qgtc_plan_layer(self.A.rows, d, h, self.s, self.t, n_tile_rows=-(-self.A.rows // 16),
+                              a_cols=self.A.cols)["ksplit"]
+        base = self.tuning or B.Tuning()
+        return B.Tuning(update_path=base.update_path, agg_xcd_run=base.agg_xcd_run, layer_path=base.layer_path,
+                        layer_ksplit=k)
+
     def _run_layers(self, r0, r1, A, tmap, deg, xb, x_range, ranges, out, want_int, workspace):
         """All layers on rows [r0, r1) (whole subgraphs), on the current stream."""
         n_layers = len(self.W)
+        whole = r0 == 0 and r1 == self.A.rows
         # the first layer's codes stand for x_lo + x_scale * code; behind a hidden layer the
         # codes are read as pure scales (x_lo = 0)
         x_lo = float(x_range[0])
@@ -409,7 +453,8 @@ class QuantGNN:
             r = ranges[l]
             last = l == n_layers - 1
             agg_ep, ep, z_scale, x_next = self._layer_eps(l, x_lo, x_scale, r.agg_hi, r.out_hi, last)
-            ep.tuning = self.tuning
+            tuning = self._run_tuning(l, whole)
+            ep.tuning = tuning
             if not last:
                 if self.batchnorm[l] is not None:
                     ep.col_scale, ep.col_shift = self._bn_fold(l, z_scale)
@@ -417,7 +462,7 @@ class QuantGNN:
                                   out=self._x_rows((l + 1) & 1, self.dims[l][1], r0, r1))
                 x_lo, x_scale = 0.0, x_next
             elif want_int:
-                B.qgtc_layer(A, tmap, xb, W, agg_ep, B.Epilogue(mode=B.OUT_I32, tuning=self.tuning), workspace,
+                B.qgtc_layer(A, tmap, xb, W, agg_ep, B.Epilogue(mode=B.OUT_I32, tuning=tuning), workspace,
                              out=out)
             else:
                 # row_i = None: the layer takes the row sums of its own requantized Y

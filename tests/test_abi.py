@@ -210,6 +210,12 @@ def test_selector_and_scalar_helpers_on_the_host():
     assert plan["fused"] == 0 and plan["update_path"] == 1 and plan["tile_kbits"] == 128
     assert b.qgtc_plan_layer(8192, 2000, 64, 8, 8)["fused"] == 0
     assert b.qgtc_plan_layer(100, 64, 64, 8, 8, n_tile_rows=7)["ksplit"] == 4         # few tile rows: split the lists
+    # independent runs: two for a short launch over a batch of subgraphs, one otherwise
+    assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024, subgraphs=64)["runs"] == 2
+    assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024)["runs"] == 1            # one graph
+    assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024, subgraphs=8)["runs"] == 1
+    assert b.qgtc_plan_layer(262144, 512, 16, 8, 8, n_tile_rows=16384, a_cols=2048, subgraphs=128)["runs"] == 1   # long launch
+    assert b.qgtc_plan_layer(65536, 64, 64, 16, 16, n_tile_rows=4096, a_cols=1024, subgraphs=64)["runs"] == 1     # not fused
     with pytest.raises(b.QgtcError):
         b.qgtc_plan_layer(10, 0, 4, 8, 8)
     # the scalars of a layer: the hand-worked 2-layer network of tests/golden

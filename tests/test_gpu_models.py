@@ -56,8 +56,9 @@ def run_model(w, tile_kbits=128):
     # independent runs of subgraphs on several streams give the same bytes
     if w.storage == "compact":
         nb = w.graph.n_blocks
-        for k in (2, 3, [nb - nb // 4, nb // 4], [1, nb - 1]):     # equal and uneven runs
-            if not isinstance(k, int) and min(k) < 1:
+        assert net.auto_runs() in (1, 2)                           # the selector's own choice
+        for k in ("auto", 2, 3, [nb - nb // 4, nb // 4], [1, nb - 1]):     # equal and uneven runs
+            if isinstance(k, list) and min(k) < 1:
                 continue
             again = net.forward(X, xr, ranges, streams=k)
             torch.cuda.synchronize()
@@ -124,6 +125,20 @@ def test_update_first_order(cfg, bits, nb):
 def test_config4_gin_five_layers(nb):
     w = make_workload(4, n_blocks=nb)
     run_model(w)
+
+
+def test_selector_runs_on_the_bench_configurations():
+    """The full-size batches as bench.py issues them: config 4 (short launches, equal
+    subgraphs) as two independent runs, config 5 (long launches, hubs first) as one."""
+    from paper_2111_09547_amd.model import QuantGNN
+    for cfg, want in ((4, 2), (5, 1)):
+        w = make_workload(cfg)
+        g = w.graph
+        net = QuantGNN(dev(g.dense_compact()), [dev(W) for W in w.W], w.s, w.t, w.model == "gin",
+                       block_rows=g.block)
+        assert net.auto_runs() == want, cfg
+        del net
+        torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("bits,nb,kb", [(1, 4, 128), (2, 4, 64), (4, 4, 32), (8, 4, 128), (8, None, 128), (4, None, 32),
