@@ -275,12 +275,24 @@ enum { QGTC_OUT_I32 = 0, QGTC_OUT_F32 = 1, QGTC_OUT_BITS = 2 };
  *                 aggregate and update as two kernels.
  *   layer_ksplit  waves of a workgroup of the fused kernel that split one tile list:
  *                 0 = automatic (more when the grid is small), 1, 2 or 4.
+ *   zero_words    zero-word jumping inside the tiles the map keeps: the aggregation's unit
+ *                 of work is one row of a tile times one 32-bit word, and the word of a row
+ *                 is wave-uniform, so rows whose word is zero can be jumped over (the
+ *                 paper's zero-tile jumping, Section 4.3, at the granularity of the vector
+ *                 ALUs instead of the Tensor-Core tile).  Results are the same either way.
+ *                 0 = automatic: on when a tile map is passed (a sparse adjacency) and X
+ *                 has at least 3 planes; 1 = visit every word of a kept tile (faster when
+ *                 most words hold a bit: a row that is present costs one scalar branch
+ *                 more in the jumping form); 2 = jump whenever X has at least 3 planes.
+ *                 qgtc_plan_layer says which from the statistics of the adjacency.
  * Values outside these ranges: QGTC_ERR_UNSUPPORTED. */
 typedef struct qgtc_tuning {
   int32_t update_path;
   int32_t agg_xcd_run;
   int32_t layer_path;
   int32_t layer_ksplit;
+  int32_t zero_words;
+  int32_t reserved;
 } qgtc_tuning;
 
 typedef struct qgtc_epilogue {
@@ -368,9 +380,14 @@ qgtc_status qgtc_layer_static(const qgtc_bits* A, const qgtc_tile_map* map,
  * the packed adjacency (the second kind of zero tiles of the paper's Section 6.3, gaps
  * inside a subgraph, shows as fewer non-zero tiles at narrower widths):
  *   counts[0..2] = number of non-zero 16 x 32, 16 x 64 and 16 x 128 tiles,
- *   counts[3]    = number of rows of tiles, ceil(A.rows / 16).
- * counts: device, 4 x int32, written by the call (no need to clear it).  The host reads
- * it when it plans (qgtc_plan_layer), once per adjacency.
+ *   counts[3]    = number of rows of tiles, ceil(A.rows / 16),
+ *   counts[4..5] = low and high half of the 64-bit number of (row, 32-bit word) pairs of
+ *                  A that hold a bit: the work zero-word jumping really visits
+ *                  (qgtc_tuning.zero_words), and the selector's measure of how sparse the
+ *                  kept tiles are,
+ *   counts[6..7] = 0.
+ * counts: device, 8 x int32, 8-byte aligned, written by the call (no need to clear it).
+ * The host reads it when it plans (qgtc_plan_layer), once per adjacency.
  * ------------------------------------------------------------------------- */
 qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void* stream);
 
@@ -383,7 +400,8 @@ qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void* stream);
  *   in:  rows (nodes), in_cols (D), out_cols (H), s, t,
  *        nnz_tiles[3] from qgtc_tile_stats (all zero: unknown, 128-bit tiles assumed,
  *        every tile of a row counted), n_tile_rows, a_cols (columns of A as stored),
- *        subgraphs (diagonal blocks of a batched adjacency, Section 4.1; 0: unknown or one)
+ *        subgraphs (diagonal blocks of a batched adjacency, Section 4.1; 0: unknown or one),
+ *        nnz_row_words from qgtc_tile_stats (0: unknown)
  *   out: tile_kbits     32, 64 or 128: least executed work, tiles x width x cost per bit
  *                       (a narrower tile must win by 2 %)
  *        fused          1: qgtc_layer runs as one kernel (s, t <= 8, D <= 1024, H <= 256)
@@ -396,6 +414,13 @@ qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void* stream);
  *                       overlaps the other run's work (measured on config 4: 434 against
  *                       464 us for five layers).  A run is then launched with the K split of
  *                       the whole batch (qgtc_tuning.layer_ksplit = ksplit)
+ *        zero_words     the qgtc_tuning.zero_words to pass: 2 (jump over zero words inside
+ *                       kept tiles) when X has at least 3 planes and fewer than 70 % of the
+ *                       (row, word) pairs of the kept tiles hold a bit - a present row costs
+ *                       about one instruction pair more in that form, so it pays below
+ *                       12 - 14 present rows out of 16 -, 1 (visit all) otherwise; 0 when
+ *                       nnz_row_words is unknown (the library then assumes a sparse
+ *                       adjacency whenever a tile map is passed)
  *        est_us_aggregate_first, est_us_update_first
  *                       rough times of (A.X).W and A.(X.W) from the measured rates; the two
  *                       orders are different quantized networks (the requantization sits
@@ -408,6 +433,7 @@ typedef struct qgtc_plan_in {
   int32_t a_cols;
   int32_t subgraphs;
   int64_t nnz_tiles[3];
+  int64_t nnz_row_words;
 } qgtc_plan_in;
 
 typedef struct qgtc_plan_out {
@@ -418,7 +444,7 @@ typedef struct qgtc_plan_out {
   double est_us_aggregate_first;
   double est_us_update_first;
   int32_t runs;
-  int32_t reserved;
+  int32_t zero_words;
 } qgtc_plan_out;
 
 qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* out);

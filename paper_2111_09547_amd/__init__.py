@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     qgtc_pack_bits, qgtc_unpack_bits, qgtc_build_tile_map, qgtc_aggregate,
     qgtc_update, qgtc_layer, qgtc_layer_static, LAYER_STATIC_MAX_BYTES, qgtc_row_sums, qgtc_col_sums,
     Tuning, LAYER_FUSED, LAYER_TWO_KERNELS, UPDATE_AUTO, UPDATE_POPCOUNT, UPDATE_MATRIX_CORES,
-    qgtc_tile_stats, qgtc_plan_layer, qgtc_quant_inv_scale, qgtc_layer_epilogues, qgtc_fold_batchnorm, qgtc_device_info,
+    ZERO_WORDS_AUTO, ZERO_WORDS_VISIT, ZERO_WORDS_SKIP,
+    qgtc_tile_stats, tile_stats_numbers, qgtc_plan_layer, qgtc_quant_inv_scale, qgtc_layer_epilogues, qgtc_fold_batchnorm, qgtc_device_info,
     qgtc_probe_popcount, qgtc_prof_enable, qgtc_prof_reset, qgtc_prof_read, qgtc_version,
 )

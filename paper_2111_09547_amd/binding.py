@@ -49,7 +49,8 @@ class _TileMapC(C.Structure):
 
 class _TuningC(C.Structure):
     _fields_ = [("update_path", C.c_int32), ("agg_xcd_run", C.c_int32),
-                ("layer_path", C.c_int32), ("layer_ksplit", C.c_int32)]
+                ("layer_path", C.c_int32), ("layer_ksplit", C.c_int32),
+                ("zero_words", C.c_int32), ("reserved", C.c_int32)]
 
 
 class _EpilogueC(C.Structure):
@@ -65,13 +66,14 @@ class _EpilogueC(C.Structure):
 class _PlanInC(C.Structure):
     _fields_ = [("rows", C.c_int32), ("in_cols", C.c_int32), ("out_cols", C.c_int32),
                 ("s", C.c_int32), ("t", C.c_int32), ("n_tile_rows", C.c_int32),
-                ("a_cols", C.c_int32), ("subgraphs", C.c_int32), ("nnz_tiles", C.c_int64 * 3)]
+                ("a_cols", C.c_int32), ("subgraphs", C.c_int32), ("nnz_tiles", C.c_int64 * 3),
+                ("nnz_row_words", C.c_int64)]
 
 
 class _PlanOutC(C.Structure):
     _fields_ = [("tile_kbits", C.c_int32), ("fused", C.c_int32), ("update_path", C.c_int32),
                 ("ksplit", C.c_int32), ("est_us_aggregate_first", C.c_double),
-                ("est_us_update_first", C.c_double), ("runs", C.c_int32), ("reserved", C.c_int32)]
+                ("est_us_update_first", C.c_double), ("runs", C.c_int32), ("zero_words", C.c_int32)]
 
 
 class _LayerSpecC(C.Structure):
@@ -203,6 +205,7 @@ class Tuning:
     agg_xcd_run: int = 0
     layer_path: int = 0       # LAYER_FUSED / LAYER_TWO_KERNELS
     layer_ksplit: int = 0
+    zero_words: int = 0       # ZERO_WORDS_AUTO / ZERO_WORDS_VISIT / ZERO_WORDS_SKIP
 
 
 @dataclass
@@ -240,7 +243,7 @@ class Epilogue:
         tn = None
         if self.tuning is not None:
             t = self.tuning
-            tn = C.pointer(_TuningC(t.update_path, t.agg_xcd_run, t.layer_path, t.layer_ksplit))
+            tn = C.pointer(_TuningC(t.update_path, t.agg_xcd_run, t.layer_path, t.layer_ksplit, t.zero_words, 0))
         # (the structure keeps the pointed-to tuning alive)
         return _EpilogueC(self.mode, int(self.relu), int(self.self_term), self.rq_nbits,
                           self.rq_lo, self.rq_inv_scale, self.cc, self.rs, self.l0a,
@@ -398,23 +401,33 @@ def qgtc_layer_static(A: Bits, tmap: TileMap | None, X: Bits, W: Bits, agg_ep: E
 
 LAYER_FUSED, LAYER_TWO_KERNELS = 0, 1
 UPDATE_AUTO, UPDATE_POPCOUNT, UPDATE_MATRIX_CORES = 0, 1, 2
+ZERO_WORDS_AUTO, ZERO_WORDS_VISIT, ZERO_WORDS_SKIP = 0, 1, 2
 
 
 def qgtc_tile_stats(A: Bits, out: torch.Tensor | None = None) -> torch.Tensor:
-    """Device int32[4]: non-zero tiles of A at 16 x 32, 16 x 64, 16 x 128, and its rows of tiles."""
+    """Device int32[8]: non-zero tiles of A at 16 x 32, 16 x 64, 16 x 128, its rows of tiles,
+    and (two words, low half first) its (row, 32-bit word) pairs that hold a bit; see
+    tile_stats_numbers."""
     if out is None:
-        out = torch.empty(4, dtype=torch.int32, device=A.words.device)
-    assert out.dtype == torch.int32 and out.is_contiguous() and out.numel() >= 4
+        out = torch.empty(8, dtype=torch.int32, device=A.words.device)
+    assert out.dtype == torch.int32 and out.is_contiguous() and out.numel() >= 8
     _check(lib().qgtc_tile_stats(C.byref(A.c), C.c_void_p(out.data_ptr()), _stream()), "qgtc_tile_stats")
     return out
 
 
+def tile_stats_numbers(counts: torch.Tensor) -> dict:
+    """The numbers of qgtc_tile_stats on the host (this synchronizes)."""
+    c = [int(v) for v in counts.cpu()]
+    return {"nnz_tiles": c[:3], "n_tile_rows": c[3],
+            "nnz_row_words": (c[4] & 0xFFFFFFFF) | ((c[5] & 0xFFFFFFFF) << 32)}
+
+
 def qgtc_plan_layer(rows: int, in_cols: int, out_cols: int, s: int, t: int, n_tile_rows: int = 0,
-                    a_cols: int = 0, nnz_tiles=(0, 0, 0), subgraphs: int = 0) -> dict:
+                    a_cols: int = 0, nnz_tiles=(0, 0, 0), subgraphs: int = 0, nnz_row_words: int = 0) -> dict:
     """The library's selector for one layer (host-only); nnz_tiles: the first three numbers
     of qgtc_tile_stats."""
     pin = _PlanInC(rows, in_cols, out_cols, s, t, n_tile_rows, a_cols, int(subgraphs),
-                   (C.c_int64 * 3)(*[int(v) for v in nnz_tiles]))
+                   (C.c_int64 * 3)(*[int(v) for v in nnz_tiles]), int(nnz_row_words))
     pout = _PlanOutC()
     _check(lib().qgtc_plan_layer(C.byref(pin), C.byref(pout)), "qgtc_plan_layer")
     return {k: getattr(pout, k) for k, _ in _PlanOutC._fields_}

@@ -65,7 +65,7 @@ __device__ __forceinline__ void pack_rows_fast(const uint32_t (&q)[16], uint32_t
 }
 
 // TW: words per tile (1, 2, 4); KS: K slices per wave (1, 2, 4; KS <= TW).
-template <int S, bool MULTI, int TW, int KS>
+template <int S, bool MULTI, int TW, int KS, bool SKIP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_per_simd(S)))) void aggregate_kernel(const AggParams p) {
   extern __shared__ uint32_t lds[];   // [ksplit][16][64] partial sums when ksplit > 1
 
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
     const int plane0 = chunk * S;
     uint32_t acc[16][S];
     zero_acc<S>(acc);
-    agg_loop_uniform<S, TW, KS, MULTI>(acc, p, ra, va_off, rx, xoff, ci, n, wave, p.ksplit, kw_base, kw_max,
+    agg_loop_uniform<S, TW, KS, MULTI, SKIP>(acc, p, ra, va_off, rx, xoff, ci, n, wave, p.ksplit, kw_base, kw_max,
                                        plane0);
     // shift-and-add of the per-plane popcounts (Algorithm 1, elementwise reduction)
 #pragma unroll
@@ -244,7 +244,13 @@ template <int S, bool MULTI, int TW, int KS>
 qgtc_status launch_one(const AggParams& p, hipStream_t stream) {
   const unsigned grid = xcd_deal_grid(p.nblocks, p.chunk_shift);
   const size_t lds = p.ksplit > 1 ? (size_t)p.ksplit * 16 * 64 * sizeof(uint32_t) : 0;
-  hipLaunchKernelGGL((aggregate_kernel<S, MULTI, TW, KS>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
+  if constexpr (S >= kSkipMinPlanes) {
+    if (p.skip_words) {
+      hipLaunchKernelGGL((aggregate_kernel<S, MULTI, TW, KS, true>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
+      return launch_status();
+    }
+  }
+  hipLaunchKernelGGL((aggregate_kernel<S, MULTI, TW, KS, false>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
   return launch_status();
 }
 
@@ -308,6 +314,7 @@ extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* m
   // one subgraph over all XCDs, so a subgraph that holds far more tiles than the
   // others (the hubs of a power-law graph) does not leave seven XCDs idle.
   agg_set_dealing(&p, p.n_cg, ep->tuning ? ep->tuning->agg_xcd_run : 0);
+  p.skip_words = agg_skip_words(p.s > 8 ? 8 : p.s, ep->tuning ? ep->tuning->zero_words : 0, map != nullptr);
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_AGGREGATE, s);

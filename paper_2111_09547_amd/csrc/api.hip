@@ -153,6 +153,7 @@ qgtc_status check_tuning(const qgtc_tuning* t) {
   if (t->layer_ksplit != 0 && t->layer_ksplit != 1 && t->layer_ksplit != 2 && t->layer_ksplit != 4)
     return QGTC_ERR_UNSUPPORTED;
   if (t->agg_xcd_run > 4096) return QGTC_ERR_UNSUPPORTED;
+  if (t->zero_words < 0 || t->zero_words > 2) return QGTC_ERR_UNSUPPORTED;
   return QGTC_OK;
 }
 

@@ -38,6 +38,24 @@ def block(S, r0, R, first):
             "\n      : " + ", ".join(ins) + ");\n")
 
 
+def row_block(S, r):
+    """One row of a tile by itself (all S planes): the unit the zero-word test skips."""
+    items = [(r, i) for i in range(S)]
+    lines = []
+    for k in range(0, len(items), 2):
+        pair = items[k:k + 2]
+        for n, (_, i) in enumerate(pair):
+            lines.append(f"v_and_b32_dpp %[t{n}], %[a], %[x{i}] row_newbcast:{r} "
+                         "row_mask:0xf bank_mask:0xf bound_ctrl:1")
+        for n, (_, i) in enumerate(pair):
+            lines.append(f"v_bcnt_u32_b32 %[c{i}], %[t{n}], %[c{i}]")
+    text = "\n".join(f'      "{l}\\n\\t"' for l in lines)
+    outs = ['[t0] "=&v"(t0)', '[t1] "=&v"(t1)'] + [f'[c{i}] "+v"(acc[{i}])' for i in range(S)]
+    ins = ['[a] "v"(a)'] + [f'[x{i}] "v"(x[{i}])' for i in range(S)]
+    return ("    asm volatile(\n" + text + "\n      : " + ", ".join(outs) +
+            "\n      : " + ", ".join(ins) + ");\n")
+
+
 def lane_pack(S, wpp):
     """Gathers the ballot words of one output row into lanes: plane i's word k
     goes to lane L0 + k of ow[i].  v_writelane_b32 reads its data operand on the
@@ -101,6 +119,16 @@ def main():
         for r0 in range(0, ROWS, R):
             print(block(S, r0, R, r0 == 0), end="")
         print("  }\n};")
+    print("// popc_row<S, R>::run(a, x, acc): the same for row R alone, acc[i] += popcount(A_word(row R) & x[i]).")
+    print("template <int S, int R> struct popc_row;")
+    for S in range(1, 9):
+        for r in range(ROWS):
+            print(f"template <> struct popc_row<{S}, {r}> {{")
+            print("  static __device__ __forceinline__ void run(uint32_t a, "
+                  f"const uint32_t (&x)[{S}], uint32_t (&acc)[{S}]) {{")
+            print("    uint32_t t0, t1;")
+            print(row_block(S, r), end="")
+            print("  }\n};")
     print("// lane_pack<S, WPP>::run<L0>(w, ow): ow[i] lane L0+k = w[i][k] for k < WPP.")
     print("template <int S, int WPP> struct lane_pack;")
     for S in range(1, 9):

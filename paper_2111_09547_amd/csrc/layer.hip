@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256) void weight_bytes_kernel(const uint32_t* W, in
 typedef const __attribute__((address_space(4))) LayerParams* LateParams;
 #define QGTC_LATE(ptr) asm volatile("" : "+s"(ptr))
 
-template <int S, int TW, int KS>
+template <int S, int TW, int KS, bool SKIP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_per_simd(S)))) void layer_kernel(const LayerParams p) {
   extern __shared__ uint32_t lds[];
   __builtin_amdgcn_s_setprio(2);
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
     // takes the next tile row.
     __builtin_amdgcn_s_setprio(0);
     if (cg_ok)
-      agg_loop_uniform<S, TW, KS, false>(acc, a, ra, va_off, rx, xoff, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
+      agg_loop_uniform<S, TW, KS, false, SKIP>(acc, a, ra, va_off, rx, xoff, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
     __builtin_amdgcn_s_setprio(2);
     // shift-and-add of the per-plane popcounts (Algorithm 1, elementwise reduction)
     uint32_t y[16];
@@ -412,20 +412,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
   }
 }
 
-template <int S>
-qgtc_status launch(const LayerParams& p, unsigned nw, size_t lds_bytes, hipStream_t stream) {
+template <int S, bool SKIP>
+qgtc_status launch_form(const LayerParams& p, unsigned nw, size_t lds_bytes, hipStream_t stream) {
   const unsigned grid = xcd_deal_grid(p.a.nblocks, p.a.chunk_shift);
   const dim3 g(grid), b(64 * nw);
   switch (p.a.tile_words * 8 + p.a.kslices) {
-    case 4 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 4, 1>), g, b, lds_bytes, stream, p); break;
-    case 4 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 4, 2>), g, b, lds_bytes, stream, p); break;
-    case 4 * 8 + 4: hipLaunchKernelGGL((layer_kernel<S, 4, 4>), g, b, lds_bytes, stream, p); break;
-    case 2 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 2, 1>), g, b, lds_bytes, stream, p); break;
-    case 2 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 2, 2>), g, b, lds_bytes, stream, p); break;
-    case 1 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 1, 1>), g, b, lds_bytes, stream, p); break;
+    case 4 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 4, 1, SKIP>), g, b, lds_bytes, stream, p); break;
+    case 4 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 4, 2, SKIP>), g, b, lds_bytes, stream, p); break;
+    case 4 * 8 + 4: hipLaunchKernelGGL((layer_kernel<S, 4, 4, SKIP>), g, b, lds_bytes, stream, p); break;
+    case 2 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 2, 1, SKIP>), g, b, lds_bytes, stream, p); break;
+    case 2 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 2, 2, SKIP>), g, b, lds_bytes, stream, p); break;
+    case 1 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 1, 1, SKIP>), g, b, lds_bytes, stream, p); break;
     default: return QGTC_ERR_UNSUPPORTED;
   }
   return launch_status();
+}
+
+template <int S>
+qgtc_status launch(const LayerParams& p, unsigned nw, size_t lds_bytes, hipStream_t stream) {
+  if constexpr (S >= kSkipMinPlanes) {
+    if (p.a.skip_words) return launch_form<S, true>(p, nw, lds_bytes, stream);
+  }
+  return launch_form<S, false>(p, nw, lds_bytes, stream);
 }
 
 }  // namespace
@@ -485,6 +493,7 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   }
   const unsigned nw = (unsigned)(p.cgw * a.ksplit);
   agg_set_dealing(&a, 1, tn ? tn->agg_xcd_run : 0);
+  a.skip_words = agg_skip_words(a.s, tn ? tn->zero_words : 0, map != nullptr);
 
   p.h = W->cols;
   p.n_nt_w = cdiv(W->cols, 16);

@@ -197,9 +197,12 @@ __global__ __launch_bounds__(256) void degree_kernel(const MapParams p) {
 // a bit there; the three counts follow from the four answers.
 __global__ __launch_bounds__(256) void tile_stats_kernel(const MapParams p, int32_t* counts) {
   __shared__ int part[3];
+  __shared__ unsigned long long part_rw;
   const int lane = threadIdx.x & 63;
   if (threadIdx.x < 3) part[threadIdx.x] = 0;
+  if (threadIdx.x == 3) part_rw = 0ull;
   __syncthreads();
+  unsigned long long rw = 0ull;                   // (row, 32-bit word) pairs that hold a bit
   const int n128 = (p.n_words + 3) >> 2;          // rows are padded to 128 bits with zeros
   const int g = lane >> 4;
   int c32 = 0, c64 = 0, c128 = 0;
@@ -223,6 +226,8 @@ __global__ __launch_bounds__(256) void tile_stats_kernel(const MapParams p, int3
         const unsigned long long my = __builtin_amdgcn_ballot_w64(v[u].y != 0u);
         const unsigned long long mz = __builtin_amdgcn_ballot_w64(v[u].z != 0u);
         const unsigned long long mw = __builtin_amdgcn_ballot_w64(v[u].w != 0u);
+        rw += (unsigned long long)(__builtin_popcountll(mx) + __builtin_popcountll(my) +
+                                   __builtin_popcountll(mz) + __builtin_popcountll(mw));
 #pragma unroll
         for (int k = 0; k < 4; ++k) {             // wave-uniform arithmetic
           const int bx = ((mx >> (16 * k)) & 0xffffull) != 0ull, by = ((my >> (16 * k)) & 0xffffull) != 0ull;
@@ -238,15 +243,17 @@ __global__ __launch_bounds__(256) void tile_stats_kernel(const MapParams p, int3
     atomicAdd(&part[0], c32);
     atomicAdd(&part[1], c64);
     atomicAdd(&part[2], c128);
+    atomicAdd(&part_rw, rw);
   }
   __syncthreads();
   if (threadIdx.x < 3 && part[threadIdx.x] != 0) atomicAdd(&counts[threadIdx.x], part[threadIdx.x]);
+  if (threadIdx.x == 3 && part_rw != 0ull)
+    atomicAdd(reinterpret_cast<unsigned long long*>(counts + 4), part_rw);    // counts[4], counts[5]: one 64-bit number
 }
 
-// Start values of the four counters (a kernel, so that the call can be recorded into a HIP graph).
+// Start values of the counters (a kernel, so that the call can be recorded into a HIP graph).
 __global__ void tile_stats_init_kernel(int32_t* counts, int32_t n_tile_rows) {
-  if (threadIdx.x < 3) counts[threadIdx.x] = 0;
-  if (threadIdx.x == 3) counts[3] = n_tile_rows;
+  if (threadIdx.x < 8) counts[threadIdx.x] = threadIdx.x == 3 ? n_tile_rows : 0;
 }
 
 bool tile_shape_ok(int tile_rows, int tile_kbits) {
@@ -341,7 +348,7 @@ extern "C" qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void
   if (!A || !counts) return QGTC_ERR_NULL;
   qgtc_status st = check_adjacency(A);
   if (st != QGTC_OK) return st;
-  if (((uintptr_t)counts & 3u) != 0) return QGTC_ERR_ALIGN;
+  if (((uintptr_t)counts & 7u) != 0) return QGTC_ERR_ALIGN;
   MapParams p{};
   p.A = A->data;
   p.lda = A->ld_words;

@@ -35,15 +35,23 @@ class BatchNorm:
     eps: float = 1e-5
 
 
+def plan_adjacency(A: "B.Bits", d: int = 64, h: int = 64, s: int = 8, t: int = 8) -> dict:
+    """The library's selector on a packed adjacency: one pass over A counts its non-zero
+    tiles at the three widths and its non-zero (row, word) pairs (qgtc_tile_stats), the host
+    reads the numbers back once (this synchronizes) and qgtc_plan_layer picks the tile width
+    with the least executed work and says whether jumping over the zero words inside kept
+    tiles pays.  Narrow tiles skip more zeros (the paper's second kind of zero tiles, gaps
+    inside a subgraph, Section 6.3) but cost more per bit."""
+    st = B.tile_stats_numbers(B.qgtc_tile_stats(A))
+    plan = B.qgtc_plan_layer(A.rows, d, h, s, t, n_tile_rows=st["n_tile_rows"], a_cols=A.cols,
+                             nnz_tiles=st["nnz_tiles"], nnz_row_words=st["nnz_row_words"])
+    plan.update(st)
+    return plan
+
+
 def choose_tile_kbits(A: "B.Bits", d: int = 64, h: int = 64, s: int = 8, t: int = 8) -> int:
-    """Tile width for the zero-tile map of a packed adjacency, by the library's selector:
-    one pass over A counts its non-zero tiles at the three widths (qgtc_tile_stats), the
-    host reads the four numbers back once (this synchronizes) and qgtc_plan_layer picks the
-    width with the least executed work.  Narrow tiles skip more zeros (the paper's second
-    kind of zero tiles, gaps inside a subgraph, Section 6.3) but cost more per bit."""
-    counts = [int(v) for v in B.qgtc_tile_stats(A).cpu()]
-    plan = B.qgtc_plan_layer(A.rows, d, h, s, t, n_tile_rows=counts[3], a_cols=A.cols, nnz_tiles=counts[:3])
-    return plan["tile_kbits"]
+    """Tile width for the zero-tile map of a packed adjacency (plan_adjacency)."""
+    return plan_adjacency(A, d, h, s, t)["tile_kbits"]
 
 
 def fused_layer_applies(d: int, h: int, s: int, t: int) -> bool:
@@ -89,10 +97,19 @@ class QuantGNN:
             self.A_src = A_src
             self.A = B.alloc_bits(A_src.shape[0], A_src.shape[1], 1, B.LEFT, block_rows)
         self.map = None
-        if tile_kbits == "auto":            # needs the packed adjacency: pack it now, choose once
+        # The selector's choices that depend on the adjacency (tile width when "auto", zero-word
+        # jumping unless the caller's tuning says which): pack A now, read its statistics once.
+        self.plan = None
+        if tile_kbits == "auto" or tuning is None or tuning.zero_words == 0:
             if self.A_src is not None:
                 B.qgtc_pack_bits(self.A_src, 1, B.LEFT, out=self.A)
-            self.tile_kbits = choose_tile_kbits(self.A, self.dims[0][0], self.dims[0][1], s, t)
+            self.plan = plan_adjacency(self.A, self.dims[0][0], self.dims[0][1], s, t)
+            if tile_kbits == "auto":
+                self.tile_kbits = self.plan["tile_kbits"]
+            base = tuning or B.Tuning()
+            self.tuning = B.Tuning(update_path=base.update_path, agg_xcd_run=base.agg_xcd_run,
+                                   layer_path=base.layer_path, layer_ksplit=base.layer_ksplit,
+                                   zero_words=self.plan["zero_words"])
         # Weights are cached in the form their layer's kernel reads: bytes in
         # matrix-core operand order where the fused layer kernel applies, bit planes
         # for the two-kernel path.
@@ -271,9 +288,11 @@ class QuantGNN:
                 if not want_int:
                     # codes read as pure scales (no zero points): out = z_scale * (A.Pq)
                     _, agg_ep, _, _ = self._layer_eps(l, 0.0, x_scale, p_hi, None, last=True)
+                    agg_ep.tuning = self.tuning
                     B.qgtc_aggregate(self.A, self.map, pb, agg_ep, out=out)
                 return out
             _, agg_ep, _, x_scale = self._layer_eps(l, 0.0, x_scale, p_hi, out_hi, last=False)
+            agg_ep.tuning = self.tuning
             xl = B.qgtc_aggregate(self.A, self.map, pb, agg_ep, out=self._xl_view((l + 1) & 1, h))
 
     def _bn_fold(self, l: int, value_scale: float):
@@ -439,7 +458,7 @@ class QuantGNN:
                               a_cols=self.A.cols)["ksplit"]
         base = self.tuning or B.Tuning()
         return B.Tuning(update_path=base.update_path, agg_xcd_run=base.agg_xcd_run, layer_path=base.layer_path,
-                        layer_ksplit=k)
+                        layer_ksplit=k, zero_words=base.zero_words)
 
     def _run_layers(self, r0, r1, A, tmap, deg, xb, x_range, ranges, out, want_int, workspace):
         """All layers on rows [r0, r1) (whole subgraphs), on the current stream."""

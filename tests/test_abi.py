@@ -166,7 +166,7 @@ def test_tuning_is_range_checked_before_any_launch():
     Y = _fake_bits(b, 64, 64, 4, b.LEFT)
     W = _fake_bits(b, 64, 16, 4, b.RIGHT)
     for bad in (b._TuningC(3, 0, 0, 0), b._TuningC(0, 5000, 0, 0), b._TuningC(0, 0, 2, 0), b._TuningC(0, 0, 0, 3),
-                b._TuningC(-1, 0, 0, 0)):
+                b._TuningC(-1, 0, 0, 0), b._TuningC(0, 0, 0, 0, 3, 0), b._TuningC(0, 0, 0, 0, -1, 0)):
         ep = b.Epilogue(mode=b.OUT_I32).to_c()
         ep.tuning = C.pointer(bad)
         assert l.qgtc_update(C.byref(Y), C.byref(W), C.byref(ep), C.c_void_p(0x20000), 16, None) == 7
@@ -210,6 +210,12 @@ def test_selector_and_scalar_helpers_on_the_host():
     assert plan["fused"] == 0 and plan["update_path"] == 1 and plan["tile_kbits"] == 128
     assert b.qgtc_plan_layer(8192, 2000, 64, 8, 8)["fused"] == 0
     assert b.qgtc_plan_layer(100, 64, 64, 8, 8, n_tile_rows=7)["ksplit"] == 4         # few tile rows: split the lists
+    # zero-word jumping: from 3 planes, when fewer than 70 % of the (row, word) pairs of the kept tiles hold a bit
+    kw = dict(n_tile_rows=4096, a_cols=1024, nnz_tiles=(131072, 65536, 32768))
+    assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, nnz_row_words=480000, **kw)["zero_words"] == 2
+    assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, nnz_row_words=2000000, **kw)["zero_words"] == 1      # 95 % present
+    assert b.qgtc_plan_layer(65536, 64, 64, 2, 2, nnz_row_words=480000, **kw)["zero_words"] == 1        # too few planes
+    assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, **kw)["zero_words"] == 0                              # unknown
     # independent runs: two for a short launch over a batch of subgraphs, one otherwise
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024, subgraphs=64)["runs"] == 2
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024)["runs"] == 1            # one graph

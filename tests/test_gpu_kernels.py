@@ -138,7 +138,13 @@ def test_tile_stats_match_the_oracle_at_three_widths(shape):
     Ab = pack_adjacency(A)
     got = q.qgtc_tile_stats(Ab).cpu().numpy().tolist()
     want = [sum(len(l) for l in qgnn.tile_map(A, 16, kb)[0]) for kb in (32, 64, 128)]
-    assert got == want + [-(-n // 16)]
+    # (row, 32-bit word) pairs that hold a bit: brute force on the dense matrix
+    pad = np.zeros((n, -(-k // 32) * 32), dtype=np.uint8)
+    pad[:, :k] = A
+    row_words = int(pad.reshape(n, -1, 32).any(axis=2).sum())
+    assert got == want + [-(-n // 16), row_words, 0, 0, 0]
+    assert q.tile_stats_numbers(q.qgtc_tile_stats(Ab)) == dict(nnz_tiles=want, n_tile_rows=-(-n // 16),
+                                                               nnz_row_words=row_words)
     for i, kb in enumerate((32, 64, 128)):
         assert int(q.qgtc_build_tile_map(Ab, 16, kb).nnz_tiles.cpu()[0]) == want[i]
     # a second call into the same buffer starts from zero again
@@ -153,7 +159,8 @@ def test_tile_stats_on_block_diagonal_storage():
     got = q.qgtc_tile_stats(Ab).cpu().numpy().tolist()
     compact = g.dense_compact()
     want = [sum(len(l) for l in qgnn.tile_map(compact, 16, kb)[0]) for kb in (32, 64, 128)]
-    assert got == want + [g.n_nodes // 16]
+    row_words = int(compact.reshape(g.n_nodes, -1, 32).any(axis=2).sum())
+    assert got == want + [g.n_nodes // 16, row_words, 0, 0, 0]
     assert want[0] > want[1] > want[2]
 
 
@@ -674,6 +681,41 @@ def test_update_matrix_core_path_equals_popcount_and_oracle(st, shape):
         assert (bits == bp.pack(qgnn.requantize(Z, 0, inv, 5, relu=True), 5, bp.RIGHT)).all(), path
         ref = qgnn.dequantize(Z, row_i=rs, row_l=rs, col_i=cs, **kw)
         assert_fp32_close(f, ref, str(path))
+
+
+# ------------------------------------------------------------ zero-word jumping
+@pytest.mark.parametrize("s", [3, 4, 8, 11])
+@pytest.mark.parametrize("shape,p_edge", [((300, 64), 0.01), ((300, 64), 0.6), ((130, 20), 0.03), ((257, 130), 0.002),
+                                          ((64, 16), 1.0), ((515, 300), 0.0)])
+def test_zero_word_jumping_gives_the_same_integers(s, shape, p_edge):
+    """The aggregation with every word of a kept tile visited and with the zero words
+    jumped over (qgtc_tuning.zero_words), with and without a map, at the three tile widths,
+    stand-alone and inside the fused layer: the same integers as the oracle."""
+    n, d = shape
+    rng = np.random.default_rng([83, s, n, d, int(p_edge * 1000)])
+    A = rand_graph(rng, n, n, p_edge)
+    if n > 100:
+        A[33:70, :] = 0                                     # rows of tiles without a bit
+        A[:, 64:160] = 0                                    # whole word columns without a bit
+    Xq = rng.integers(0, 2 ** s, size=(n, d), dtype=np.uint64).astype(np.uint32)
+    Y = qgnn.aggregate(A, Xq, True)
+    Ab = pack_adjacency(A)
+    Xb = q.qgtc_pack_bits(dev(Xq.view(np.int32)), s, q.RIGHT)
+    h, t = 24, 5
+    Wq = rng.integers(0, 2 ** t, size=(d, h)).astype(np.uint32)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    rq_bits = min(s, 8)
+    inv = qgnn.inv_scale(0.0, float(max(1, qgnn.as_signed(Y).max())), rq_bits)
+    Z = qgnn.update(qgnn.requantize(Y, 0, inv, rq_bits), Wq)
+    for kb in (None, 32, 64, 128):
+        m = q.qgtc_build_tile_map(Ab, 16, kb) if kb else None
+        for zw in (q.ZERO_WORDS_AUTO, q.ZERO_WORDS_VISIT, q.ZERO_WORDS_SKIP):
+            tn = q.Tuning(zero_words=zw)
+            got = q.qgtc_aggregate(Ab, m, Xb, q.Epilogue(mode=q.OUT_I32, self_term=True, tuning=tn))
+            assert (as_u32(got) == Y).all(), (kb, zw)
+            agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=rq_bits, rq_inv_scale=float(inv), self_term=True)
+            got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32, tuning=tn))
+            assert (as_u32(got) == Z).all(), (kb, zw)
 
 
 # ------------------------------------------------------------ seeded random shapes
