@@ -63,6 +63,16 @@ def timeit(fn, n=20, warm=3, reps=5):
     return sorted(ts)[len(ts) // 2]
 
 
+def _planned(ab, d, s_bits, mode=None):
+    """An int32-output epilogue with the tuning the selector gives for this adjacency (a user
+    would plan once per adjacency: these sweeps use dense random matrices, where visiting
+    every word of a tile beats jumping over the few zero ones)."""
+    st = q.tile_stats_numbers(q.qgtc_tile_stats(ab))
+    plan = q.qgtc_plan_layer(ab.rows, d, d, min(s_bits, 8), 8, n_tile_rows=st["n_tile_rows"], a_cols=ab.cols,
+                             nnz_tiles=st["nnz_tiles"], nnz_row_words=st["nnz_row_words"])
+    return q.Epilogue(mode=q.OUT_I32 if mode is None else mode, tuning=q.Tuning(zero_words=plan["zero_words"]))
+
+
 def table3():
     rows = []
     gen = torch.Generator(device="cuda").manual_seed(3)
@@ -76,7 +86,7 @@ def table3():
             for s in (1, 2, 3, 4):
                 x = torch.randint(0, 2 ** s, (n, d), dtype=torch.int32, device="cuda", generator=gen)
                 xb = q.qgtc_pack_bits(x, s, q.RIGHT)
-                ep = q.Epilogue(mode=q.OUT_I32)
+                ep = _planned(ab, d, s)
                 out = q.qgtc_aggregate(ab, tmap, xb, ep)
                 t = timeit(lambda: q.qgtc_aggregate(ab, tmap, xb, ep, out=out))
                 rec[f"us_{s}bit"] = round(t, 2)
@@ -169,7 +179,7 @@ def sizes():
         tmap = q.qgtc_build_tile_map(ab, 16, 128)
         for d in ds:
             xb = _random_bits(n, d, 1, q.RIGHT, gen)
-            ep = q.Epilogue(mode=q.OUT_I32)
+            ep = _planned(ab, d, 1)
             out = q.qgtc_aggregate(ab, tmap, xb, ep)
             t = timeit(lambda: q.qgtc_aggregate(ab, tmap, xb, ep, out=out), n=10 if n >= 8192 else 20)
             rec = {"sweep": "sizes", "N": n, "D": d, "us": round(t, 2),
@@ -194,7 +204,7 @@ def reuse():
     for n in (1024, 2048, 4096, 8192):
         ab = _random_bits(n, n, 1, q.LEFT, gen)
         tmap = q.qgtc_build_tile_map(ab, 16, 128)
-        ep = q.Epilogue(mode=q.OUT_I32)
+        ep = _planned(ab, d, 8)
         x1 = _random_bits(n, d, 1, q.RIGHT, gen)
         out = q.qgtc_aggregate(ab, tmap, x1, ep)
         t1 = timeit(lambda: q.qgtc_aggregate(ab, tmap, x1, ep, out=out), n=10)
@@ -413,12 +423,50 @@ def tiles():
         print(f"| {r['config']} | 16 x {r['tile_kbits']} | {r['nonzero_tiles']} | {r['us_layers']} | {r['cost_relative_to_128']} |")
 
 
+def zero_words():
+    """The aggregation with every word of the kept tiles visited against zero-word jumping,
+    over the share of (row, word) pairs that hold a bit: the measurement behind the
+    selector's 70 % rule.  N = 16384 nodes in 16 diagonal blocks of 1024, D = 64, int32 out."""
+    gen = torch.Generator(device="cuda").manual_seed(16)
+    n, blk, d = 16384, 1024, 64
+    rows = []
+    for p_edge in (0.002, 0.008, 0.02, 0.04, 0.07, 0.12, 0.3):
+        a = (torch.rand((n, blk), device="cuda", generator=gen) < p_edge).to(torch.uint8)
+        ab = q.qgtc_pack_bits(a, 1, q.LEFT, block_rows=blk)
+        tmap = q.qgtc_build_tile_map(ab, 16, 128)
+        st = q.tile_stats_numbers(q.qgtc_tile_stats(ab))
+        share = st["nnz_row_words"] / (16.0 * st["nnz_tiles"][2] * 4)
+        for s_bits in (3, 4, 8):
+            x = torch.randint(0, 2 ** s_bits, (n, d), dtype=torch.int32, device="cuda", generator=gen)
+            xb = q.qgtc_pack_bits(x, s_bits, q.RIGHT)
+            out = torch.empty((n, d), dtype=torch.int32, device="cuda")
+            t = {}
+            for name, zw in (("visit", q.ZERO_WORDS_VISIT), ("jump", q.ZERO_WORDS_SKIP)):
+                ep = q.Epilogue(mode=q.OUT_I32, tuning=q.Tuning(zero_words=zw))
+                t[name] = _kernel_us(lambda: q.qgtc_aggregate(ab, tmap, xb, ep, out=out), q.KERNEL_AGGREGATE, n=10, warm=3)
+            plan = q.qgtc_plan_layer(n, d, d, s_bits, 8, n_tile_rows=st["n_tile_rows"], a_cols=blk,
+                                     nnz_tiles=st["nnz_tiles"], nnz_row_words=st["nnz_row_words"])
+            rec = {"sweep": "zero_words", "p_edge": p_edge, "pairs_present": round(share, 3), "bits": s_bits,
+                   "us_visit_all": round(t["visit"], 1), "us_jump": round(t["jump"], 1),
+                   "selector": "jump" if plan["zero_words"] == q.ZERO_WORDS_SKIP else "visit all"}
+            print(json.dumps(rec), flush=True)
+            rows.append(rec)
+            del x, xb, out
+        del a, ab, tmap
+        torch.cuda.empty_cache()
+    print("\n| edge probability | (row, word) pairs present in kept tiles | bits | visit all us | jump us | selector |")
+    print("|---|---|---|---|---|---|")
+    for r in rows:
+        print(f"| {r['p_edge']} | {r['pairs_present']} | {r['bits']} | {r['us_visit_all']} | {r['us_jump']} | {r['selector']} |")
+
+
 def main():
     torch.cuda.set_device(0)
-    which = sys.argv[1:] or ["table3", "config3", "config5", "sizes", "reuse", "transfer", "gate", "streaming", "tiles"]
+    which = sys.argv[1:] or ["table3", "config3", "config5", "sizes", "reuse", "transfer", "gate", "streaming", "tiles", "zero_words"]
     for name in which:
         {"table3": table3, "config3": config3, "config5": config5, "sizes": sizes, "reuse": reuse,
-         "transfer": transfer, "gate": gate, "streaming": streaming, "tiles": tiles}[name]()
+         "transfer": transfer, "gate": gate, "streaming": streaming, "tiles": tiles,
+         "zero_words": zero_words}[name]()
 
 
 if __name__ == "__main__":
