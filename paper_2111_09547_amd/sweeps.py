@@ -142,8 +142,9 @@ def _model_sweep(cfg, bit_list, kb=128, update_first=False):
         del net, a_src, x
         torch.cuda.empty_cache()
     print(f"\nconfig {cfg}, {rows[0]['order']}, tiles of 16 x {kb}:")
-    print(f"\n| s = t | forward (pack X + {rows[0]['layers']} layer(s)) us | executed Tbit-op/s | "
-          "aggregation bit-ops / forward time, fraction of the vector-ALU ceiling |")
+    print(f"\n| s = t | forward (pack X + {rows[0]['layers']} layer(s)) us | Tbit-op/s of the kept tiles | "
+          "kept-tile aggregation bit-ops / forward time over the vector-ALU ceiling (from 3 bits on the kernels "
+          "jump over zero words inside kept tiles and visit only part of them) |")
     print("|---|---|---|---|")
     for r in rows:
         print(f"| {r['bits']} | {r['us_forward']} | {r['tbitops_executed']} | {r['agg_frac_valu']} |")
