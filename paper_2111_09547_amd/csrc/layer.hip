@@ -482,8 +482,9 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   a.n_cg = cdiv(X->cols, 64);
   a.nblocks = (uint32_t)a.n_tile_rows;
   // waves side by side over the column groups, and waves that split each tile list
+  a.skip_words = agg_skip_words(a.s, tn ? tn->zero_words : 0, map != nullptr);
   int cgw = 1, ksplit = 1;
-  plan_layer_shape(a.n_tile_rows, X->cols, X->nbits, &cgw, &ksplit);
+  plan_layer_shape(a.n_tile_rows, X->cols, X->nbits, a.skip_words != 0, &cgw, &ksplit);
   p.cgw = cgw;
   p.n_pass = cdiv(a.n_cg, p.cgw);
   a.ksplit = ksplit;
@@ -493,7 +494,6 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   }
   const unsigned nw = (unsigned)(p.cgw * a.ksplit);
   agg_set_dealing(&a, 1, tn ? tn->agg_xcd_run : 0);
-  a.skip_words = agg_skip_words(a.s, tn ? tn->zero_words : 0, map != nullptr);
 
   p.h = W->cols;
   p.n_nt_w = cdiv(W->cols, 16);

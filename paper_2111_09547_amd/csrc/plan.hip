@@ -33,7 +33,7 @@ int plan_update_path(int s, int t) {
   return (s >= 1 && s <= 8 && t >= 1 && t <= 8) ? 2 : 1;
 }
 
-void plan_layer_shape(int n_tile_rows, int in_cols, int s, int* cgw, int* ksplit) {
+void plan_layer_shape(int n_tile_rows, int in_cols, int s, bool jumping, int* cgw, int* ksplit) {
   const int n_cg = cdiv(in_cols, 64);
   const int w = n_cg <= 4 ? n_cg : (n_cg % 3 == 0 ? 3 : 4);
   // Waves that split each tile list: as many as it takes to fill the wave slots of the
@@ -44,7 +44,9 @@ void plan_layer_shape(int n_tile_rows, int in_cols, int s, int* cgw, int* ksplit
   const int64_t slots = (int64_t)device_compute_units() * 4 * per_simd;
   int k = 1;
   while ((int64_t)n_tile_rows * w * k < slots && w * k * 2 <= 4) k *= 2;
-  if (w == 2 && k == 1) k = 2;
+  // (not in the form that jumps over zero words: its waves are bound by latency, and the
+  // exchange of partial sums only adds to it - 252 against 263 us on config 4's five layers)
+  if (w == 2 && k == 1 && !jumping) k = 2;
   *cgw = w;
   *ksplit = k;
 }
@@ -76,14 +78,6 @@ extern "C" qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* ou
 
   out->fused = plan_fused_applies(in->in_cols, in->out_cols, in->s, in->t) ? 1 : 0;
   out->update_path = plan_update_path(in->s, in->t);
-  int cgw = 1, ksplit = 1;
-  plan_layer_shape(in->n_tile_rows, in->in_cols, in->s, &cgw, &ksplit);
-  out->ksplit = ksplit;
-  // Independent runs: a short fused launch (at most two rounds of the wave slots) leaves
-  // the device part empty while it drains; two runs of whole subgraphs on two streams
-  // overlap one run's drain with the other's work.  Runs of at least eight subgraphs, so
-  // that the XCD dealing inside a run still has one subgraph per XCD.
-  out->runs = 1;
   // zero-word jumping: pays while fewer than 70 % of the (row, word) pairs of the kept tiles
   // hold a bit (measured: a present row costs about two issue slots more in that form)
   out->zero_words = 0;
@@ -92,6 +86,16 @@ extern "C" qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* ou
     const bool sparse = (double)in->nnz_row_words < 0.7 * pairs;
     out->zero_words = (in->s >= 3 && sparse) ? 2 : 1;
   }
+  // without the statistic the library jumps whenever it gets a tile map and 3 planes or more
+  const bool jumping = out->zero_words == 2 || (out->zero_words == 0 && in->s >= 3);
+  int cgw = 1, ksplit = 1;
+  plan_layer_shape(in->n_tile_rows, in->in_cols, in->s, jumping, &cgw, &ksplit);
+  out->ksplit = ksplit;
+  // Independent runs: a short fused launch (at most two rounds of the wave slots) leaves
+  // the device part empty while it drains; two runs of whole subgraphs on two streams
+  // overlap one run's drain with the other's work.  Runs of at least eight subgraphs, so
+  // that the XCD dealing inside a run still has one subgraph per XCD.
+  out->runs = 1;
   if (out->fused && in->subgraphs >= 16 && in->subgraphs % 2 == 0) {
     const int planes = in->s > 8 ? 8 : in->s;
     const int per_simd = planes >= 5 ? 3 : (planes >= 3 ? 4 : 5);

@@ -98,7 +98,7 @@ size_t layer_fused_workspace_bytes(int32_t in_cols, int32_t out_cols);
 // The selector's rules (plan.hip), shared by qgtc_plan_layer and the entry points.
 bool plan_fused_applies(int in_cols, int out_cols, int s, int t);
 int plan_update_path(int s, int t);                 // 1 popcount, 2 matrix cores
-void plan_layer_shape(int n_tile_rows, int in_cols, int s, int* cgw, int* ksplit);
+void plan_layer_shape(int n_tile_rows, int in_cols, int s, bool jumping, int* cgw, int* ksplit);
 // Range check of a caller's tuning (NULL is fine).
 qgtc_status check_tuning(const qgtc_tuning* t);
 

@@ -454,8 +454,10 @@ class QuantGNN:
         if whole_batch or (self.tuning is not None and self.tuning.layer_ksplit):
             return self.tuning
         d, h = self.dims[l]
+        st = self.plan or {}
         k = B.qgtc_plan_layer(self.A.rows, d, h, self.s, self.t, n_tile_rows=-(-self.A.rows // 16),
-                              a_cols=self.A.cols)["ksplit"]
+                              a_cols=self.A.cols, nnz_tiles=st.get("nnz_tiles", (0, 0, 0)),
+                              nnz_row_words=st.get("nnz_row_words", 0))["ksplit"]
         base = self.tuning or B.Tuning()
         return B.Tuning(update_path=base.update_path, agg_xcd_run=base.agg_xcd_run, layer_path=base.layer_path,
                         layer_ksplit=k, zero_words=base.zero_words)
