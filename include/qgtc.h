@@ -285,6 +285,12 @@ enum { QGTC_OUT_I32 = 0, QGTC_OUT_F32 = 1, QGTC_OUT_BITS = 2 };
  *                 most words hold a bit: a row that is present costs one scalar branch
  *                 more in the jumping form); 2 = jump whenever X has at least 3 planes.
  *                 qgtc_plan_layer says which from the statistics of the adjacency.
+ *                 From 5 planes on, and while a row of A (of a diagonal block, for block
+ *                 storage), rounded up to whole tiles, has at most 2047 words of 32 bits, the
+ *                 jumping form keeps two rows of a tile per accumulator register, 16 bits
+ *                 each (no count can reach 65536), which lets a fourth wave per SIMD run;
+ *                 wider adjacencies take the same form with full-width accumulators.  The
+ *                 caller sees no difference but the speed.
  * Values outside these ranges: QGTC_ERR_UNSUPPORTED. */
 typedef struct qgtc_tuning {
   int32_t update_path;
@@ -411,14 +417,17 @@ qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void* stream);
  *                       each (1 or 2): subgraphs share no edge, so a batch can be cut between
  *                       them; 2 when the fused launch is short (at most two rounds of the
  *                       device's wave slots), where the drain of one run's launch then
- *                       overlaps the other run's work (measured on config 4: 434 against
- *                       464 us for five layers).  A run is then launched with the K split of
+ *                       overlaps the other run's work (measured on config 4, five layers:
+ *                       434 against 464 us visiting every word, 247 against 251 us with
+ *                       zero-word jumping).  A run is then launched with the K split of
  *                       the whole batch (qgtc_tuning.layer_ksplit = ksplit)
  *        zero_words     the qgtc_tuning.zero_words to pass: 2 (jump over zero words inside
  *                       kept tiles) when X has at least 3 planes and fewer than 70 % of the
- *                       (row, word) pairs of the kept tiles hold a bit - a present row costs
- *                       about one instruction pair more in that form, so it pays below
- *                       12 - 14 present rows out of 16 -, 1 (visit all) otherwise; 0 when
+ *                       (row, word) pairs of the kept tiles hold a bit (60 % from 5 planes
+ *                       on) - a present row costs about one instruction pair more in that
+ *                       form, and from 5 planes on half of the rows a third instruction per
+ *                       plane, so it pays below 10 - 12 present rows out of 16 -, 1 (visit
+ *                       all) otherwise; 0 when
  *                       nnz_row_words is unknown (the library then assumes a sparse
  *                       adjacency whenever a tile map is passed)
  *        est_us_aggregate_first, est_us_update_first

@@ -65,8 +65,9 @@ __device__ __forceinline__ void pack_rows_fast(const uint32_t (&q)[16], uint32_t
 }
 
 // TW: words per tile (1, 2, 4); KS: K slices per wave (1, 2, 4; KS <= TW).
-template <int S, bool MULTI, int TW, int KS, bool SKIP>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_per_simd(S)))) void aggregate_kernel(const AggParams p) {
+// PK: the jumping form with two rows per accumulator register (agg_core.inc).
+template <int S, bool MULTI, int TW, int KS, bool SKIP, bool PK = false>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack16Waves : agg_waves_per_simd(S)))) void aggregate_kernel(const AggParams p) {
   extern __shared__ uint32_t lds[];   // [ksplit][16][64] partial sums when ksplit > 1
 
   const unsigned bid = agg_logical_id(p);
@@ -101,18 +102,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
   const int n_chunks = MULTI ? (p.s + S - 1) / S : 1;
   for (int chunk = 0; chunk < n_chunks; ++chunk) {
     const int plane0 = chunk * S;
-    uint32_t acc[16][S];
-    zero_acc<S>(acc);
-    agg_loop_uniform<S, TW, KS, MULTI, SKIP>(acc, p, ra, va_off, rx, xoff, ci, n, wave, p.ksplit, kw_base, kw_max,
-                                       plane0);
-    // shift-and-add of the per-plane popcounts (Algorithm 1, elementwise reduction)
+    constexpr int AR = PK ? 8 : 16;
+    uint32_t acc[AR][S];
+    zero_acc<S, AR>(acc);
+    agg_loop_uniform<S, TW, KS, MULTI, SKIP, AR>(acc, p, ra, va_off, rx, xoff, ci, n, wave, p.ksplit, kw_base, kw_max,
+                                                 plane0);
+    uint32_t v[16];
+    agg_shift_add<S>(acc, v);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      uint32_t v = 0u;
-#pragma unroll
-      for (int i = 0; i < S; ++i) v += acc[j][i] << i;
-      y[j] += v << plane0;
-    }
+    for (int j = 0; j < 16; ++j) y[j] += v[j] << plane0;
   }
   if constexpr (KS > 1) {
 #pragma unroll
@@ -244,6 +242,12 @@ template <int S, bool MULTI, int TW, int KS>
 qgtc_status launch_one(const AggParams& p, hipStream_t stream) {
   const unsigned grid = xcd_deal_grid(p.nblocks, p.chunk_shift);
   const size_t lds = p.ksplit > 1 ? (size_t)p.ksplit * 16 * 64 * sizeof(uint32_t) : 0;
+  if constexpr (S >= kPack16MinPlanes && !MULTI) {
+    if (p.skip_words && p.pack16) {
+      hipLaunchKernelGGL((aggregate_kernel<S, MULTI, TW, KS, true, true>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
+      return launch_status();
+    }
+  }
   if constexpr (S >= kSkipMinPlanes) {
     if (p.skip_words) {
       hipLaunchKernelGGL((aggregate_kernel<S, MULTI, TW, KS, true>), dim3(grid), dim3(64 * p.ksplit), lds, stream, p);
@@ -315,6 +319,7 @@ extern "C" qgtc_status qgtc_aggregate(const qgtc_bits* A, const qgtc_tile_map* m
   // others (the hubs of a power-law graph) does not leave seven XCDs idle.
   agg_set_dealing(&p, p.n_cg, ep->tuning ? ep->tuning->agg_xcd_run : 0);
   p.skip_words = agg_skip_words(p.s > 8 ? 8 : p.s, ep->tuning ? ep->tuning->zero_words : 0, map != nullptr);
+  p.pack16 = agg_pack16(p.skip_words, p.s, p.n_tile_cols, p.tile_words);
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   ProfScope prof(QGTC_KERNEL_AGGREGATE, s);

@@ -56,6 +56,27 @@ def row_block(S, r):
             "\n      : " + ", ".join(ins) + ");\n")
 
 
+def row_block_hi(S, r):
+    """Row r (8..15) of a tile into the upper 16 bits of the accumulators of row r - 8
+    (two rows share a register where counts stay below 65536): popcount into a temporary,
+    then one shift-and-add."""
+    lines = []
+    for k in range(0, S, 2):
+        pair = list(range(k, min(S, k + 2)))
+        for n, i in enumerate(pair):
+            lines.append(f"v_and_b32_dpp %[t{n}], %[a], %[x{i}] row_newbcast:{r} "
+                         "row_mask:0xf bank_mask:0xf bound_ctrl:1")
+        for n, i in enumerate(pair):
+            lines.append(f"v_bcnt_u32_b32 %[t{n}], %[t{n}], 0")
+        for n, i in enumerate(pair):
+            lines.append(f"v_lshl_add_u32 %[c{i}], %[t{n}], 16, %[c{i}]")
+    text = "\n".join(f'      "{l}\\n\\t"' for l in lines)
+    outs = ['[t0] "=&v"(t0)', '[t1] "=&v"(t1)'] + [f'[c{i}] "+v"(acc[{i}])' for i in range(S)]
+    ins = ['[a] "v"(a)'] + [f'[x{i}] "v"(x[{i}])' for i in range(S)]
+    return ("    asm volatile(\n" + text + "\n      : " + ", ".join(outs) +
+            "\n      : " + ", ".join(ins) + ");\n")
+
+
 def lane_pack(S, wpp):
     """Gathers the ballot words of one output row into lanes: plane i's word k
     goes to lane L0 + k of ow[i].  v_writelane_b32 reads its data operand on the
@@ -128,6 +149,16 @@ def main():
                   f"const uint32_t (&x)[{S}], uint32_t (&acc)[{S}]) {{")
             print("    uint32_t t0, t1;")
             print(row_block(S, r), end="")
+            print("  }\n};")
+    print("// popc_row_hi<S, R>::run(a, x, acc): row R (8..15) into the upper halves: acc[i] += popcount(A_word(row R) & x[i]) << 16.")
+    print("template <int S, int R> struct popc_row_hi;")
+    for S in range(5, 9):
+        for r in range(8, ROWS):
+            print(f"template <> struct popc_row_hi<{S}, {r}> {{")
+            print("  static __device__ __forceinline__ void run(uint32_t a, "
+                  f"const uint32_t (&x)[{S}], uint32_t (&acc)[{S}]) {{")
+            print("    uint32_t t0, t1;")
+            print(row_block_hi(S, r), end="")
             print("  }\n};")
     print("// lane_pack<S, WPP>::run<L0>(w, ow): ow[i] lane L0+k = w[i][k] for k < WPP.")
     print("template <int S, int WPP> struct lane_pack;")

@@ -96,8 +96,10 @@ __global__ __launch_bounds__(256) void weight_bytes_kernel(const uint32_t* W, in
 typedef const __attribute__((address_space(4))) LayerParams* LateParams;
 #define QGTC_LATE(ptr) asm volatile("" : "+s"(ptr))
 
-template <int S, int TW, int KS, bool SKIP>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_per_simd(S)))) void layer_kernel(const LayerParams p) {
+// PK: the jumping form with two rows per accumulator register (agg_core.inc): 64 instead of
+// 128 accumulator registers at 8 planes, four waves per SIMD instead of three.
+template <int S, int TW, int KS, bool SKIP, bool PK = false>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack16Waves : agg_waves_per_simd(S)))) void layer_kernel(const LayerParams p) {
   extern __shared__ uint32_t lds[];
   __builtin_amdgcn_s_setprio(2);
   const AggParams& a = p.a;
@@ -143,25 +145,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
     uint32_t va_off, xoff;
     agg_lane_offsets<TW, KS>(a, lane, col4, &va_off, &xoff);
 
-    uint32_t acc[16][S];
-    zero_acc<S>(acc);
+    constexpr int AR = PK ? 8 : 16;                  // accumulator rows (two tile rows per register when PK)
+    uint32_t acc[AR][S];
+    zero_acc<S, AR>(acc);
     // The tile loop runs at the lowest issue priority, everything around it (short chains
     // of dependent loads, LDS traffic and matrix instructions) above it: those sections
     // have few instructions, and the sooner they are through, the sooner the wave's slot
     // takes the next tile row.
     __builtin_amdgcn_s_setprio(0);
     if (cg_ok)
-      agg_loop_uniform<S, TW, KS, false, SKIP>(acc, a, ra, va_off, rx, xoff, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
+      agg_loop_uniform<S, TW, KS, false, SKIP, AR>(acc, a, ra, va_off, rx, xoff, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
     __builtin_amdgcn_s_setprio(2);
-    // shift-and-add of the per-plane popcounts (Algorithm 1, elementwise reduction)
     uint32_t y[16];
+    agg_shift_add<S>(acc, y);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      uint32_t v = 0u;
-#pragma unroll
-      for (int i = 0; i < S; ++i) v += acc[j][i] << i;
-      y[j] = agg_slice_sum<KS>(v);
-    }
+    for (int j = 0; j < 16; ++j) y[j] = agg_slice_sum<KS>(y[j]);
 
     // (the same for the wave-uniform row tests below: computed up front they are kept as
     // sixteen SGPR pairs across the loop and spilled)
@@ -224,13 +222,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
       const int ys = k2->ys;
       // with the usual range [0, hi) the integer part of the rule is max(c, 0), with or without ReLU
       const bool from_zero = rq_lo == 0;                              // wave-uniform
+      uint8_t* yrow = yb + cg * 64 + lane;
+      if (from_zero && a.ksplit == 1) {
+        // the common case on its own: no test per row, one form of the rule
+        if (cg_ok) {
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        if ((j & km2) != kpart2) continue;
-        uint32_t q = from_zero ? requantize_code_relu0(y[j], rq_inv, qmaxf)
-                               : requantize_code_small(y[j], relu_floor, rq_lo, rq_inv, qmaxf);
-        q = (c_ok && j < rows_left) ? q : 0u;
-        if (cg_ok) yb[j * ys + cg * 64 + lane] = (uint8_t)q;   // zeros from the lanes past the last column
+          for (int j = 0; j < 16; ++j) {
+            const uint32_t q = requantize_code_relu0(y[j], rq_inv, qmaxf);
+            yrow[j * ys] = (uint8_t)((c_ok && j < rows_left) ? q : 0u);   // zeros from the lanes past the last column
+          }
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          if ((j & km2) != kpart2) continue;
+          uint32_t q = from_zero ? requantize_code_relu0(y[j], rq_inv, qmaxf)
+                                 : requantize_code_small(y[j], relu_floor, rq_lo, rq_inv, qmaxf);
+          q = (c_ok && j < rows_left) ? q : 0u;
+          if (cg_ok) yrow[j * ys] = (uint8_t)q;
+        }
       }
     }
   }
@@ -412,17 +422,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(agg_waves_p
   }
 }
 
-template <int S, bool SKIP>
+template <int S, bool SKIP, bool PK = false>
 qgtc_status launch_form(const LayerParams& p, unsigned nw, size_t lds_bytes, hipStream_t stream) {
   const unsigned grid = xcd_deal_grid(p.a.nblocks, p.a.chunk_shift);
   const dim3 g(grid), b(64 * nw);
   switch (p.a.tile_words * 8 + p.a.kslices) {
-    case 4 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 4, 1, SKIP>), g, b, lds_bytes, stream, p); break;
-    case 4 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 4, 2, SKIP>), g, b, lds_bytes, stream, p); break;
-    case 4 * 8 + 4: hipLaunchKernelGGL((layer_kernel<S, 4, 4, SKIP>), g, b, lds_bytes, stream, p); break;
-    case 2 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 2, 1, SKIP>), g, b, lds_bytes, stream, p); break;
-    case 2 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 2, 2, SKIP>), g, b, lds_bytes, stream, p); break;
-    case 1 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 1, 1, SKIP>), g, b, lds_bytes, stream, p); break;
+    case 4 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 4, 1, SKIP, PK>), g, b, lds_bytes, stream, p); break;
+    case 4 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 4, 2, SKIP, PK>), g, b, lds_bytes, stream, p); break;
+    case 4 * 8 + 4: hipLaunchKernelGGL((layer_kernel<S, 4, 4, SKIP, PK>), g, b, lds_bytes, stream, p); break;
+    case 2 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 2, 1, SKIP, PK>), g, b, lds_bytes, stream, p); break;
+    case 2 * 8 + 2: hipLaunchKernelGGL((layer_kernel<S, 2, 2, SKIP, PK>), g, b, lds_bytes, stream, p); break;
+    case 1 * 8 + 1: hipLaunchKernelGGL((layer_kernel<S, 1, 1, SKIP, PK>), g, b, lds_bytes, stream, p); break;
     default: return QGTC_ERR_UNSUPPORTED;
   }
   return launch_status();
@@ -430,6 +440,9 @@ qgtc_status launch_form(const LayerParams& p, unsigned nw, size_t lds_bytes, hip
 
 template <int S>
 qgtc_status launch(const LayerParams& p, unsigned nw, size_t lds_bytes, hipStream_t stream) {
+  if constexpr (S >= kPack16MinPlanes) {
+    if (p.a.skip_words && p.a.pack16) return launch_form<S, true, true>(p, nw, lds_bytes, stream);
+  }
   if constexpr (S >= kSkipMinPlanes) {
     if (p.a.skip_words) return launch_form<S, true>(p, nw, lds_bytes, stream);
   }
@@ -483,6 +496,7 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
   a.nblocks = (uint32_t)a.n_tile_rows;
   // waves side by side over the column groups, and waves that split each tile list
   a.skip_words = agg_skip_words(a.s, tn ? tn->zero_words : 0, map != nullptr);
+  a.pack16 = agg_pack16(a.skip_words, a.s, a.n_tile_cols, a.tile_words);
   int cgw = 1, ksplit = 1;
   plan_layer_shape(a.n_tile_rows, X->cols, X->nbits, a.skip_words != 0, &cgw, &ksplit);
   p.cgw = cgw;

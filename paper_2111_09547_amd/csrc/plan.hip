@@ -33,15 +33,22 @@ int plan_update_path(int s, int t) {
   return (s >= 1 && s <= 8 && t >= 1 && t <= 8) ? 2 : 1;
 }
 
+// Wave slots of the device for the aggregation loop: waves per SIMD by the planes a lane
+// accumulates (the register budget), four in the jumping form from five planes on, where
+// two rows share an accumulator register.
+static int64_t plan_wave_slots(int s, bool jumping) {
+  const int planes = s > 8 ? 8 : s;
+  const int per_simd = planes >= 5 ? (jumping ? 4 : 3) : (planes >= 3 ? 4 : 5);
+  return (int64_t)device_compute_units() * 4 * per_simd;
+}
+
 void plan_layer_shape(int n_tile_rows, int in_cols, int s, bool jumping, int* cgw, int* ksplit) {
   const int n_cg = cdiv(in_cols, 64);
   const int w = n_cg <= 4 ? n_cg : (n_cg % 3 == 0 ? 3 : 4);
   // Waves that split each tile list: as many as it takes to fill the wave slots of the
   // device when there are few tile rows; with two column groups, workgroups of four
   // waves measured faster than pairs, so the lists are split in two there as well.
-  const int planes = s > 8 ? 8 : s;
-  const int per_simd = planes >= 5 ? 3 : (planes >= 3 ? 4 : 5);
-  const int64_t slots = (int64_t)device_compute_units() * 4 * per_simd;
+  const int64_t slots = plan_wave_slots(s, jumping);
   int k = 1;
   while ((int64_t)n_tile_rows * w * k < slots && w * k * 2 <= 4) k *= 2;
   // (not in the form that jumps over zero words: its waves are bound by latency, and the
@@ -79,11 +86,13 @@ extern "C" qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* ou
   out->fused = plan_fused_applies(in->in_cols, in->out_cols, in->s, in->t) ? 1 : 0;
   out->update_path = plan_update_path(in->s, in->t);
   // zero-word jumping: pays while fewer than 70 % of the (row, word) pairs of the kept tiles
-  // hold a bit (measured: a present row costs about two issue slots more in that form)
+  // hold a bit (measured: a present row costs about two issue slots more in that form), 60 %
+  // from five planes on, where half of the present rows cost a third instruction per plane
+  // (two rows per accumulator register)
   out->zero_words = 0;
   if (in->nnz_row_words > 0 && known) {
     const double pairs = 16.0 * (double)in->nnz_tiles[best] * (kTileBits[best] / 32);
-    const bool sparse = (double)in->nnz_row_words < 0.7 * pairs;
+    const bool sparse = (double)in->nnz_row_words < (in->s >= 5 ? 0.6 : 0.7) * pairs;
     out->zero_words = (in->s >= 3 && sparse) ? 2 : 1;
   }
   // without the statistic the library jumps whenever it gets a tile map and 3 planes or more
@@ -97,9 +106,7 @@ extern "C" qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* ou
   // that the XCD dealing inside a run still has one subgraph per XCD.
   out->runs = 1;
   if (out->fused && in->subgraphs >= 16 && in->subgraphs % 2 == 0) {
-    const int planes = in->s > 8 ? 8 : in->s;
-    const int per_simd = planes >= 5 ? 3 : (planes >= 3 ? 4 : 5);
-    const int64_t slots = (int64_t)device_compute_units() * 4 * per_simd;
+    const int64_t slots = plan_wave_slots(in->s, jumping);
     if ((int64_t)in->n_tile_rows * cgw * ksplit <= 2 * slots) out->runs = 2;
   }
 

@@ -210,11 +210,14 @@ def test_selector_and_scalar_helpers_on_the_host():
     assert plan["fused"] == 0 and plan["update_path"] == 1 and plan["tile_kbits"] == 128
     assert b.qgtc_plan_layer(8192, 2000, 64, 8, 8)["fused"] == 0
     assert b.qgtc_plan_layer(100, 64, 64, 8, 8, n_tile_rows=7)["ksplit"] == 4         # few tile rows: split the lists
-    # zero-word jumping: from 3 planes, when fewer than 70 % of the (row, word) pairs of the kept tiles hold a bit
+    # zero-word jumping: from 3 planes, when fewer than 70 % (60 % from 5 planes) of the (row, word) pairs of the
+    # kept tiles hold a bit
     kw = dict(n_tile_rows=4096, a_cols=1024, nnz_tiles=(131072, 65536, 32768))
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, nnz_row_words=480000, **kw)["zero_words"] == 2
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, nnz_row_words=2000000, **kw)["zero_words"] == 1      # 95 % present
     assert b.qgtc_plan_layer(65536, 64, 64, 2, 2, nnz_row_words=480000, **kw)["zero_words"] == 1        # too few planes
+    assert b.qgtc_plan_layer(65536, 64, 64, 4, 4, nnz_row_words=1363149, **kw)["zero_words"] == 2       # 65 % present
+    assert b.qgtc_plan_layer(65536, 64, 64, 5, 5, nnz_row_words=1363149, **kw)["zero_words"] == 1
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, **kw)["zero_words"] == 0                              # unknown
     # independent runs: two for a short launch over a batch of subgraphs, one otherwise
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024, subgraphs=64)["runs"] == 2

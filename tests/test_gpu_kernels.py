@@ -718,6 +718,45 @@ def test_zero_word_jumping_gives_the_same_integers(s, shape, p_edge):
             assert (as_u32(got) == Z).all(), (kb, zw)
 
 
+@pytest.mark.parametrize("s", [5, 6, 8])
+@pytest.mark.parametrize("k_words", [2047, 2048, 2049])
+def test_jumping_with_counts_at_the_16_bit_limit(s, k_words):
+    """From five planes on the jumping form keeps two rows of a tile in one register, 16 bits
+    each, while a row of A has at most 2047 words (a count is at most 65504); one word more
+    and a count could be 65536, which takes the form with full-width accumulators.  Rows of
+    ones against columns of ones reach the largest count on both sides of that limit, in a
+    lower and an upper row of a tile, next to sparse rows."""
+    k = 32 * k_words
+    n, d, h, t = 40, 20, 24, 4
+    rng = np.random.default_rng([97, s, k_words])
+    A = (rng.random((n, k)) < 0.002).astype(np.uint8)
+    A[3, :] = 1                                             # lower half of a tile (rows 0 - 7)
+    A[12, :] = 1                                            # upper half (rows 8 - 15): the shifted counts
+    A[27, :] = 1
+    A[21, : k // 2] = 1
+    A[16:20, :] = 0
+    Xq = rng.integers(0, 2 ** s, size=(k, d), dtype=np.uint64).astype(np.uint32)
+    Xq[:, 0] = 2 ** s - 1                                   # every plane: a count of k
+    Xq[:, 7] = 2 ** (s - 1)
+    Y = qgnn.aggregate(A, Xq, False)
+    assert Y[12, 0] == k * (2 ** s - 1)
+    Wq = rng.integers(0, 2 ** t, size=(d, h)).astype(np.uint32)
+    inv = qgnn.inv_scale(0.0, float(Y.max()), s)
+    Z = qgnn.update(qgnn.requantize(Y, 0, inv, s), Wq)
+    Ab = pack_adjacency(A)
+    Xb = q.qgtc_pack_bits(dev(Xq.view(np.int32)), s, q.RIGHT)
+    Wb = q.qgtc_pack_bits(dev(Wq.view(np.int32)), t, q.RIGHT)
+    for kb in (32, 64, 128):
+        m = q.qgtc_build_tile_map(Ab, 16, kb)
+        for zw in (q.ZERO_WORDS_SKIP, q.ZERO_WORDS_VISIT):
+            tn = q.Tuning(zero_words=zw)
+            got = q.qgtc_aggregate(Ab, m, Xb, q.Epilogue(mode=q.OUT_I32, tuning=tn))
+            assert (as_u32(got) == Y).all(), (kb, zw)
+            agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=s, rq_inv_scale=float(inv))
+            got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32, tuning=tn))
+            assert (as_u32(got) == Z).all(), (kb, zw)
+
+
 # ------------------------------------------------------------ seeded random shapes
 @pytest.mark.parametrize("seed", range(48))
 def test_layer_on_random_shapes(seed):
