@@ -12,6 +12,7 @@ namespace qgtc {
 // as much (one word step per tile leaves less to overlap the tile fetch with).
 static const double kTileCost[3] = {1.3, 1.0, 1.0};   // 32, 64, 128 bits
 static const int kTileBits[3] = {32, 64, 128};
+static const double kJumpTileSteps = 5.8;             // cost of a tile in word steps, zero-word jumping form
 
 // Sustained rates the time estimates use (MI355X, measured): the aggregation at 0.70 of
 // the vector-ALU AND + popcount ceiling (0.45 with 16 or fewer columns, where the lanes
@@ -80,21 +81,35 @@ extern "C" qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* ou
                     : (double)in->n_tile_rows * (double)cdiv(in->a_cols, 128) * 128.0 * (k == 2 ? 1.0 : 2.0);
   for (int k = 1; k >= 0; --k)
     if (work[k] < 0.98 * work[best]) best = k;
-  out->tile_kbits = kTileBits[best];
-  const double tiles = known ? (double)in->nnz_tiles[best] : (double)in->n_tile_rows * cdiv(in->a_cols, 128);
-
   out->fused = plan_fused_applies(in->in_cols, in->out_cols, in->s, in->t) ? 1 : 0;
   out->update_path = plan_update_path(in->s, in->t);
   // zero-word jumping: pays while fewer than 70 % of the (row, word) pairs of the kept tiles
   // hold a bit (measured: a present row costs about two issue slots more in that form), 60 %
   // from five planes on, where half of the present rows cost a third instruction per plane
   // (two rows per accumulator register)
+  auto sparse_at = [&](int k) {
+    const double pairs = 16.0 * (double)in->nnz_tiles[k] * (kTileBits[k] / 32);
+    return (double)in->nnz_row_words < (in->s >= 5 ? 0.6 : 0.7) * pairs;
+  };
   out->zero_words = 0;
   if (in->nnz_row_words > 0 && known) {
-    const double pairs = 16.0 * (double)in->nnz_tiles[best] * (kTileBits[best] / 32);
-    const bool sparse = (double)in->nnz_row_words < (in->s >= 5 ? 0.6 : 0.7) * pairs;
-    out->zero_words = (in->s >= 3 && sparse) ? 2 : 1;
+    out->zero_words = (in->s >= 3 && sparse_at(best)) ? 2 : 1;
+    if (out->zero_words == 2) {
+      // The jumping form visits the same non-zero (row, word) pairs at every tile width;
+      // what differs is the word steps it tests (tiles x words per tile) and the tiles it
+      // fetches, one of which costs about as much as kJumpTileSteps word steps (fitted to
+      // config 5, where 64-bit tiles measure 2 - 4 % ahead of both other widths from 3 to
+      // 8 bits; config 4 keeps its 128-bit tiles).  The wider tile stays unless a narrower
+      // one wins by 2 %; any width at least as wide as the visit-all choice is still sparse.
+      int bj = 2;
+      auto steps = [&](int k) { return (double)in->nnz_tiles[k] * (kTileBits[k] / 32 + kJumpTileSteps); };
+      for (int k = 1; k >= 0; --k)
+        if (steps(k) < 0.98 * steps(bj)) bj = k;
+      if (sparse_at(bj)) best = bj;
+    }
   }
+  out->tile_kbits = kTileBits[best];
+  const double tiles = known ? (double)in->nnz_tiles[best] : (double)in->n_tile_rows * cdiv(in->a_cols, 128);
   // without the statistic the library jumps whenever it gets a tile map and 3 planes or more
   const bool jumping = out->zero_words == 2 || (out->zero_words == 0 && in->s >= 3);
   int cgw = 1, ksplit = 1;

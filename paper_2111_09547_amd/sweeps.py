@@ -4,7 +4,7 @@
            (N in {2048, 4096, 8192}, D in {32, 64}, s = 1..4), every tile non-zero,
            as full-precision-equivalent TFLOP/s = 2 N^2 D / t (the paper's unit)
   config3  one layer per bit width (s = t in 1..8, 16, 32) on the 8 x 1024 batch
-  config5  the 2-layer GCN on the power-law graph for s = t in {1, 2, 4, 8}, with 128- and
+  config5  the 2-layer GCN on the power-law graph for s = t in {1, 2, 4, 8}, with 128-, 64- and
            32-bit tiles, and in the update-first order A.(X.W)
 
   sizes    the 1-bit x 1-bit aggregation over N in {128 .. 32768} and D in {16 .. 1024}
@@ -155,7 +155,7 @@ def config3():
 
 
 def config5():
-    for kb in (128, 32):
+    for kb in (128, 64, 32):
         _model_sweep(5, (1, 2, 4, 8), kb=kb)
     _model_sweep(5, (1, 2, 4, 8), kb=128, update_first=True)
 

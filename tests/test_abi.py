@@ -219,6 +219,14 @@ def test_selector_and_scalar_helpers_on_the_host():
     assert b.qgtc_plan_layer(65536, 64, 64, 4, 4, nnz_row_words=1363149, **kw)["zero_words"] == 2       # 65 % present
     assert b.qgtc_plan_layer(65536, 64, 64, 5, 5, nnz_row_words=1363149, **kw)["zero_words"] == 1
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, **kw)["zero_words"] == 0                              # unknown
+    # tile width under zero-word jumping: the same (row, word) pairs are visited at every width, so fewer, wider tiles
+    # weigh less than in the visit-all rule (tiles x (words per tile + 5.8)); a power-law batch like config 5
+    kw5 = dict(n_tile_rows=16384, a_cols=2048, nnz_tiles=(42346, 34753, 29175), nnz_row_words=361800)
+    plan = b.qgtc_plan_layer(262144, 512, 16, 8, 8, **kw5)
+    assert (plan["zero_words"], plan["tile_kbits"]) == (2, 64)
+    plan = b.qgtc_plan_layer(262144, 512, 16, 2, 2, **kw5)
+    assert (plan["zero_words"], plan["tile_kbits"]) == (1, 32)                  # too few planes to jump: least visited bits
+    assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, nnz_row_words=480000, **kw)["tile_kbits"] == 128     # all tiles kept
     # independent runs: two for a short launch over a batch of subgraphs, one otherwise
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024, subgraphs=64)["runs"] == 2
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024)["runs"] == 1            # one graph

@@ -129,14 +129,19 @@ def test_config4_gin_five_layers(nb):
 
 def test_selector_runs_on_the_bench_configurations():
     """The full-size batches as bench.py issues them: config 4 (short launches, equal
-    subgraphs) as two independent runs, config 5 (long launches, hubs first) as one."""
-    from paper_2111_09547_amd.model import QuantGNN
-    for cfg, want in ((4, 2), (5, 1)):
+    subgraphs) as two independent runs on 128-bit tiles, config 5 (long launches, hubs first)
+    as one run on 64-bit tiles (32-bit tiles at 2 bits, where every word of a kept tile is
+    visited and the width with the fewest kept bits wins)."""
+    from paper_2111_09547_amd.model import QuantGNN, choose_tile_kbits
+    for cfg, want, kb in ((4, 2, 128), (5, 1, 64)):
         w = make_workload(cfg)
         g = w.graph
         net = QuantGNN(dev(g.dense_compact()), [dev(W) for W in w.W], w.s, w.t, w.model == "gin",
-                       block_rows=g.block)
+                       block_rows=g.block, tile_kbits="auto")
         assert net.auto_runs() == want, cfg
+        assert net.tile_kbits == kb, cfg
+        if cfg == 5:
+            assert choose_tile_kbits(net.A, 512, 16, 2, 2) == 32
         del net
         torch.cuda.empty_cache()
 
@@ -255,16 +260,21 @@ def test_host_packed_batch_in_one_transfer(cfg, nb):
 
 
 def test_tile_width_is_chosen_from_the_zero_tile_maps():
-    """tile_kbits="auto": dense subgraphs keep 128-bit tiles, the power-law graph (gaps inside
-    the subgraphs) gets 32-bit tiles; the output does not depend on the choice."""
+    """tile_kbits="auto": dense subgraphs keep 128-bit tiles; so do the first eight subgraphs of
+    the power-law graph (its hubs) at 8 bits, where the kernels jump over zero words and a
+    tile's own cost counts, while at 2 bits, where every word of a kept tile is visited, the
+    gaps inside the subgraphs make 32-bit tiles the least work; the output does not depend on
+    the choice."""
     from paper_2111_09547_amd.model import choose_tile_kbits
-    for cfg, nb, want in ((4, 2, 128), (5, 8, 32)):
+    for cfg, nb, want in ((4, 2, 128), (5, 8, 128)):
         w = make_workload(cfg, n_blocks=nb)
         g = w.graph
         Ws = [dev(W) for W in w.W]
         auto = QuantGNN(dev(g.dense_compact()), Ws, w.s, w.t, w.model == "gin", tile_kbits="auto",
                         block_rows=g.block)
         assert auto.tile_kbits == want == choose_tile_kbits(auto.A)
+        if cfg == 5:
+            assert choose_tile_kbits(auto.A, s=2, t=2) == 32
         assert auto.map.c.tile_kbits == want
         ref = QuantGNN(dev(g.dense_compact()), Ws, w.s, w.t, w.model == "gin", tile_kbits=128,
                        block_rows=g.block)
