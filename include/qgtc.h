@@ -408,8 +408,12 @@ qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void* stream);
  *        every tile of a row counted), n_tile_rows, a_cols (columns of A as stored),
  *        subgraphs (diagonal blocks of a batched adjacency, Section 4.1; 0: unknown or one),
  *        nnz_row_words from qgtc_tile_stats (0: unknown)
- *   out: tile_kbits     32, 64 or 128: least executed work, tiles x width x cost per bit
- *                       (a narrower tile must win by 2 %)
+ *   out: tile_kbits     32, 64 or 128: least executed work.  Where every word of a kept tile
+ *                       is visited: tiles x width x cost per bit.  Where the kernels jump
+ *                       over zero words (zero_words = 2 below) the same non-zero words are
+ *                       visited at every width, and the word steps to test and the tiles to
+ *                       fetch decide: tiles x (words per tile + 5.8).  A narrower tile must
+ *                       win by 2 %
  *        fused          1: qgtc_layer runs as one kernel (s, t <= 8, D <= 1024, H <= 256)
  *        update_path    1 popcount, 2 int8 matrix cores: the stand-alone update's kernel
  *        ksplit         waves of a fused workgroup that split a tile list (1, 2, 4)
