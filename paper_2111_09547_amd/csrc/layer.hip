@@ -259,31 +259,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
     const int64_t wb_part = k3->wb_part;
     const int n_units = n_nt * k3->n_kc;
     // The wave's (unit, K step) pairs one after the other; the weights of the next pair are
-    // requested before the matrix instructions of the current one.
+    // requested before the matrix instructions of the current one, into the other of two
+    // operand buffers (the loop body is written out twice, so no buffer is ever copied).
     auto load_b = [&](int u, int ks, v4u& b7, v4u& bb) {
       const int nt = u % n_nt;
-      b7 = (v4u){0u, 0u, 0u, 0u};
-      bb = (v4u){0u, 0u, 0u, 0u};
-      if (nt >= n_nt_w) {                            // the tile whose column 0 sums the rows of Y
-        if (ln == 0) b7 = (v4u){0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
+      if (nt >= n_nt_w) {                            // the tile whose column 0 sums the rows of Y (bb is not read)
+        const uint32_t one = ln == 0 ? 0x01010101u : 0u;
+        b7 = (v4u){one, one, one, one};
       } else {
         const uint8_t* src = wb + ((int64_t)(nt * n_ks + ks) * 64 + lane) * 16;
         b7 = *reinterpret_cast<const v4u*>(src);
-        if (split_w) bb = *reinterpret_cast<const v4u*>(src + wb_part);
+        if (split_w) bb = *reinterpret_cast<const v4u*>(src + wb_part);   // read only when split_w
       }
     };
     int u = wave;
     int ks = (u / n_nt) * ks_per;
-    v4u b7 = b7_first, bb = bb_first;                // fetched early for unit `wave` when it is a tile of W, step 0
-    if (u < n_units && !(u < n_nt_w && ks == 0)) load_b(u, ks, b7, bb);
+    v4u b7a = b7_first, bba = bb_first;              // fetched early for unit `wave` when it is a tile of W, step 0
+    v4u b7b = {0u, 0u, 0u, 0u}, bbb = {0u, 0u, 0u, 0u};
+    if (u < n_units && !(u < n_nt_w && ks == 0)) load_b(u, ks, b7a, bba);
     v4i acc1 = {0, 0, 0, 0}, acc7 = {0, 0, 0, 0}, acc14 = {0, 0, 0, 0};
-    while (u < n_units) {
+    // one pair with the operands (b7, bb), the next pair's into (nb7, nbb); false after the last
+    auto pair = [&](const v4u& b7, const v4u& bb, v4u& nb7, v4u& nbb) -> bool {
       const int nt = u % n_nt;
       const int ks1 = min((u / n_nt) * ks_per + ks_per, n_ks);
       const bool ones = nt >= n_nt_w;
       int nu = u, nks = ks + 1;
       if (nks >= ks1) { nu = u + nw; nks = (nu / n_nt) * ks_per; }
-      v4u nb7 = {0u, 0u, 0u, 0u}, nbb = {0u, 0u, 0u, 0u};
       if (nu < n_units) load_b(nu, nks, nb7, nbb);
       const v4u av = *reinterpret_cast<const v4u*>(yb + ln * ys + ks * 64 + g * 16);
       v4u a7 = av, ab = {0u, 0u, 0u, 0u};
@@ -308,10 +309,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
         acc7 = (v4i){0, 0, 0, 0};
         acc14 = (v4i){0, 0, 0, 0};
       }
-      b7 = nb7;
-      bb = nbb;
       u = nu;
       ks = nks;
+      return u < n_units;
+    };
+    if (u < n_units) {
+      while (true) {
+        if (!pair(b7a, bba, b7b, bbb)) break;
+        if (!pair(b7b, bbb, b7a, bba)) break;
+      }
     }
   }
   __syncthreads();
