@@ -498,6 +498,10 @@ def main():
                                 "inside the same kernel runs on the matrix cores and is not counted; launch "
                                 "durations are taken with the launches one after the other on one stream",
                      "frac_in_step": sum(visited) / (ms_layers * 1e-3) / PEAK_BITOPS,
+                     # the work of the kept tiles (what a kernel without zero-word jumping executes, and
+                     # what `frac` counted before that existed) over the same launch time: above 1 when
+                     # the jumping form skips more than the vector ALUs could have done
+                     "frac_kept_tile_work": agg_rate / PEAK_BITOPS * (sum(agg_ops) / sum(visited)),
                      "visit_all_form": visit_all,
                      "measured_peak": measured_peak / 1e12,
                      "frac_of_measured_peak": agg_rate / measured_peak,
