@@ -86,7 +86,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
 
   int n = p.row_cnt ? p.row_cnt[tr] : p.n_tile_cols;
   n = __builtin_amdgcn_readfirstlane(n);
-  const int32_t* ci = p.col_idx ? p.col_idx + (int64_t)tr * p.n_tile_cols : nullptr;
+  // (a list that holds every tile of the row is not read: one dependent load less before the first tile)
+  const int32_t* ci = (p.col_idx && n < p.n_tile_cols) ? p.col_idx + (int64_t)tr * p.n_tile_cols : nullptr;
 
   uint32_t kw_base = 0u;
   if (p.block_rows > 0) kw_base = (uint32_t)((tr * 16) / p.block_rows) * (uint32_t)(p.block_rows >> 5);

@@ -122,7 +122,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
   const __amdgpu_buffer_rsrc_t ra = agg_row_tile_rsrc(a, tr);
   constexpr int CW = 64 / KS;                        // columns per wave (K slices: see agg_core.inc)
   n = __builtin_amdgcn_readfirstlane(n);
-  const int32_t* ci = a.col_idx ? a.col_idx + (int64_t)tr * a.n_tile_cols : nullptr;
+  // (a list that holds every tile of the row is not read: one dependent load less before the first tile)
+  const int32_t* ci = (a.col_idx && n < a.n_tile_cols) ? a.col_idx + (int64_t)tr * a.n_tile_cols : nullptr;
   uint32_t kw_base = 0u;
   if (a.block_rows > 0) kw_base = (uint32_t)(out_row0 / a.block_rows) * (uint32_t)(a.block_rows >> 5);
   const uint32_t kw_max = (uint32_t)(a.x_kwords - 1);
