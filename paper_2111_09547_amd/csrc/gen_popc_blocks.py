@@ -7,7 +7,11 @@ of row j sits in lane j of every 16-lane DPP row of `a`; `row_newbcast:j`
 broadcasts it to the 16 lanes of the row inside the v_and itself, so a
 (row, plane) pair costs exactly one v_and_b32_dpp and one v_bcnt_u32_b32 (which
 adds the popcount to its accumulator operand).  Rows are grouped into asm
-statements as large as the 30-operand limit allows.
+statements as large as the 30-operand limit allows.  For the kernels that jump
+over zero words the same pairs also come one row per function (popc_row), and
+for two rows per accumulator register a form that adds the count of rows 8..15
+to the upper 16 bits (popc_row_hi: v_bcnt with a zero addend, then
+v_lshl_add_u32 by 16).
 
 Run from this directory:  python3 gen_popc_blocks.py > popc_blocks.inc
 """
