@@ -147,6 +147,7 @@ def test_selector_runs_on_the_bench_configurations():
 
 
 @pytest.mark.parametrize("bits,nb,kb", [(1, 4, 128), (2, 4, 64), (4, 4, 32), (8, 4, 128), (8, None, 128), (4, None, 32),
+                                        (8, None, "auto"),
                                         (1, None, 128), (2, None, 128), (2, None, 32), (1, None, 32)])
 def test_config5_gcn_two_layers(bits, nb, kb):
     w = make_workload(5, bits=bits, n_blocks=nb)
