@@ -433,7 +433,8 @@ def main():
     if visited != agg_ops:
         keep = net.tuning
         net.tuning = q.Tuning(update_path=keep.update_path, agg_xcd_run=keep.agg_xcd_run, layer_path=keep.layer_path,
-                              layer_ksplit=keep.layer_ksplit, zero_words=q.ZERO_WORDS_VISIT)
+                              layer_ksplit=keep.layer_ksplit, zero_words=q.ZERO_WORDS_VISIT,
+                              even_progress=keep.even_progress)
         for _ in range(3):
             step()
         prof_v = kernel_events(step, args.steps)

@@ -291,6 +291,16 @@ enum { QGTC_OUT_I32 = 0, QGTC_OUT_F32 = 1, QGTC_OUT_BITS = 2 };
  *                 each (no count can reach 65536), which lets a fourth wave per SIMD run;
  *                 wider adjacencies take the same form with full-width accumulators.  The
  *                 caller sees no difference but the speed.
+ *   even_progress issue priority inside the fused kernel's tile loop by the share of the
+ *                 tile list that is left, so that the waves of a SIMD move through their
+ *                 lists side by side instead of the oldest finishing long before the
+ *                 youngest (which then runs alone).  It pays when every wave of the launch
+ *                 is resident from the start - at most one wave per wave slot of the device -
+ *                 and costs when there are more, because then the oldest waves should
+ *                 finish first and hand their slots on.  0 = automatic: on when this
+ *                 launch alone has at most one wave per slot; 1 = off; 2 = on.  A caller
+ *                 that runs several launches side by side (runs of a batch on several
+ *                 streams) passes what qgtc_plan_layer says for the whole batch.
  * Values outside these ranges: QGTC_ERR_UNSUPPORTED. */
 typedef struct qgtc_tuning {
   int32_t update_path;
@@ -298,7 +308,7 @@ typedef struct qgtc_tuning {
   int32_t layer_path;
   int32_t layer_ksplit;
   int32_t zero_words;
-  int32_t reserved;
+  int32_t even_progress;
 } qgtc_tuning;
 
 typedef struct qgtc_epilogue {
@@ -419,12 +429,17 @@ qgtc_status qgtc_tile_stats(const qgtc_bits* A, int32_t* counts, void* stream);
  *        ksplit         waves of a fused workgroup that split a tile list (1, 2, 4)
  *        runs           independent runs of whole subgraphs to issue the layer as, one stream
  *                       each (1 or 2): subgraphs share no edge, so a batch can be cut between
- *                       them; 2 when the fused launch is short (at most two rounds of the
- *                       device's wave slots), where the drain of one run's launch then
- *                       overlaps the other run's work (measured on config 4, five layers:
- *                       434 against 464 us visiting every word, 247 against 251 us with
- *                       zero-word jumping).  A run is then launched with the K split of
- *                       the whole batch (qgtc_tuning.layer_ksplit = ksplit)
+ *                       them; 2 when the fused launch takes more than one and at most two
+ *                       rounds of the device's wave slots, where the drain of one run's
+ *                       launch then overlaps the other run's work (measured on config 4,
+ *                       five layers, visiting every word - 4096 waves on 3072 slots: 434
+ *                       against 464 us); 1 otherwise (with zero-word jumping the same
+ *                       batch is one round of 4096 slots, and one run with even_progress
+ *                       measures 230 against 233 us for two).  A run is then launched with
+ *                       the K split and the even_progress of the whole batch
+ *                       (qgtc_tuning.layer_ksplit = ksplit, .even_progress = even_progress)
+ *        even_progress  the qgtc_tuning.even_progress to pass: 2 when the whole batch's
+ *                       fused launch has at most one wave per wave slot, 1 otherwise
  *        zero_words     the qgtc_tuning.zero_words to pass: 2 (jump over zero words inside
  *                       kept tiles) when X has at least 3 planes and fewer than 70 % of the
  *                       (row, word) pairs of the kept tiles hold a bit (60 % from 5 planes
@@ -458,6 +473,8 @@ typedef struct qgtc_plan_out {
   double est_us_update_first;
   int32_t runs;
   int32_t zero_words;
+  int32_t even_progress;
+  int32_t reserved;
 } qgtc_plan_out;
 
 qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* out);

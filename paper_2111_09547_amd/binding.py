@@ -50,7 +50,7 @@ class _TileMapC(C.Structure):
 class _TuningC(C.Structure):
     _fields_ = [("update_path", C.c_int32), ("agg_xcd_run", C.c_int32),
                 ("layer_path", C.c_int32), ("layer_ksplit", C.c_int32),
-                ("zero_words", C.c_int32), ("reserved", C.c_int32)]
+                ("zero_words", C.c_int32), ("even_progress", C.c_int32)]
 
 
 class _EpilogueC(C.Structure):
@@ -73,7 +73,8 @@ class _PlanInC(C.Structure):
 class _PlanOutC(C.Structure):
     _fields_ = [("tile_kbits", C.c_int32), ("fused", C.c_int32), ("update_path", C.c_int32),
                 ("ksplit", C.c_int32), ("est_us_aggregate_first", C.c_double),
-                ("est_us_update_first", C.c_double), ("runs", C.c_int32), ("zero_words", C.c_int32)]
+                ("est_us_update_first", C.c_double), ("runs", C.c_int32), ("zero_words", C.c_int32),
+                ("even_progress", C.c_int32), ("reserved", C.c_int32)]
 
 
 class _LayerSpecC(C.Structure):
@@ -206,6 +207,7 @@ class Tuning:
     layer_path: int = 0       # LAYER_FUSED / LAYER_TWO_KERNELS
     layer_ksplit: int = 0
     zero_words: int = 0       # ZERO_WORDS_AUTO / ZERO_WORDS_VISIT / ZERO_WORDS_SKIP
+    even_progress: int = 0    # 0 automatic, 1 off, 2 on (issue priority by remaining work in the fused kernel's tile loop)
 
 
 @dataclass
@@ -243,7 +245,7 @@ class Epilogue:
         tn = None
         if self.tuning is not None:
             t = self.tuning
-            tn = C.pointer(_TuningC(t.update_path, t.agg_xcd_run, t.layer_path, t.layer_ksplit, t.zero_words, 0))
+            tn = C.pointer(_TuningC(t.update_path, t.agg_xcd_run, t.layer_path, t.layer_ksplit, t.zero_words, t.even_progress))
         # (the structure keeps the pointed-to tuning alive)
         return _EpilogueC(self.mode, int(self.relu), int(self.self_term), self.rq_nbits,
                           self.rq_lo, self.rq_inv_scale, self.cc, self.rs, self.l0a,

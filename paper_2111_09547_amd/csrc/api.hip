@@ -154,6 +154,7 @@ qgtc_status check_tuning(const qgtc_tuning* t) {
     return QGTC_ERR_UNSUPPORTED;
   if (t->agg_xcd_run > 4096) return QGTC_ERR_UNSUPPORTED;
   if (t->zero_words < 0 || t->zero_words > 2) return QGTC_ERR_UNSUPPORTED;
+  if (t->even_progress < 0 || t->even_progress > 2) return QGTC_ERR_UNSUPPORTED;
   return QGTC_OK;
 }
 

@@ -101,7 +101,7 @@ typedef const __attribute__((address_space(4))) LayerParams* LateParams;
 template <int S, int TW, int KS, bool SKIP, bool PK = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack16Waves : agg_waves_per_simd(S)))) void layer_kernel(const LayerParams p) {
   extern __shared__ uint32_t lds[];
-  __builtin_amdgcn_s_setprio(2);
+  __builtin_amdgcn_s_setprio(3);
   const AggParams& a = p.a;
   int tr, n;                                         // tile row of this workgroup, its tile count
   if (!agg_pick_tile_row(a, &tr, &n)) return;        // whole workgroup leaves together
@@ -155,8 +155,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
     // takes the next tile row.
     __builtin_amdgcn_s_setprio(0);
     if (cg_ok)
-      agg_loop_uniform<S, TW, KS, false, SKIP, AR>(acc, a, ra, va_off, rx, xoff, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
-    __builtin_amdgcn_s_setprio(2);
+      agg_loop_uniform<S, TW, KS, false, SKIP, AR, true>(acc, a, ra, va_off, rx, xoff, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
+    __builtin_amdgcn_s_setprio(3);
     uint32_t y[16];
     agg_shift_add<S>(acc, y);
 #pragma unroll
@@ -514,6 +514,13 @@ qgtc_status layer_fused(const qgtc_bits* A, const qgtc_tile_map* map, const qgtc
     while (p.cgw * a.ksplit > 4 && a.ksplit > 1) a.ksplit >>= 1;
   }
   const unsigned nw = (unsigned)(p.cgw * a.ksplit);
+  {
+    // one round of waves at most: all of them are resident from the start
+    const int per_simd = (a.skip_words && a.pack16) ? kPack16Waves : agg_waves_per_simd(a.s);
+    const int64_t slots = (int64_t)device_compute_units() * 4 * per_simd;
+    a.even_progress = (int64_t)a.n_tile_rows * nw <= slots ? 1 : 0;
+    if (tn && tn->even_progress) a.even_progress = tn->even_progress == 2 ? 1 : 0;   // the caller knows what runs beside it
+  }
   agg_set_dealing(&a, 1, tn ? tn->agg_xcd_run : 0);
 
   p.h = W->cols;

@@ -115,15 +115,20 @@ extern "C" qgtc_status qgtc_plan_layer(const qgtc_plan_in* in, qgtc_plan_out* ou
   int cgw = 1, ksplit = 1;
   plan_layer_shape(in->n_tile_rows, in->in_cols, in->s, jumping, &cgw, &ksplit);
   out->ksplit = ksplit;
-  // Independent runs: a short fused launch (at most two rounds of the wave slots) leaves
-  // the device part empty while it drains; two runs of whole subgraphs on two streams
-  // overlap one run's drain with the other's work.  Runs of at least eight subgraphs, so
-  // that the XCD dealing inside a run still has one subgraph per XCD.
+  // A launch of at most one wave per wave slot has all its waves resident from the start:
+  // the tile loop then gives the waves that are behind the higher issue priority
+  // (qgtc_tuning.even_progress).  Independent runs: a fused launch of more than one and at
+  // most two rounds of the wave slots leaves the device part empty while it drains; two
+  // runs of whole subgraphs on two streams overlap one run's drain with the other's work.
+  // Runs of at least eight subgraphs, so that the XCD dealing inside a run still has one
+  // subgraph per XCD.
+  const int64_t slots = plan_wave_slots(in->s, jumping);
+  const int64_t waves = (int64_t)in->n_tile_rows * cgw * ksplit;
+  out->even_progress = waves <= slots ? 2 : 1;
+  out->reserved = 0;
   out->runs = 1;
-  if (out->fused && in->subgraphs >= 16 && in->subgraphs % 2 == 0) {
-    const int64_t slots = plan_wave_slots(in->s, jumping);
-    if ((int64_t)in->n_tile_rows * cgw * ksplit <= 2 * slots) out->runs = 2;
-  }
+  if (out->fused && in->subgraphs >= 16 && in->subgraphs % 2 == 0 && waves > slots && waves <= 2 * slots)
+    out->runs = 2;
 
   // rough times of the two orders of the products
   const double bits = 16.0 * kTileBits[best] * kTileCost[best] * tiles;   // adjacency bits visited, weighted

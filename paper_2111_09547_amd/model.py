@@ -109,7 +109,8 @@ class QuantGNN:
             base = tuning or B.Tuning()
             self.tuning = B.Tuning(update_path=base.update_path, agg_xcd_run=base.agg_xcd_run,
                                    layer_path=base.layer_path, layer_ksplit=base.layer_ksplit,
-                                   zero_words=self.plan["zero_words"])
+                                   zero_words=base.zero_words or self.plan["zero_words"],
+                                   even_progress=base.even_progress)
         # Weights are cached in the form their layer's kernel reads: bytes in
         # matrix-core operand order where the fused layer kernel applies, bit planes
         # for the two-kernel path.
@@ -424,19 +425,21 @@ class QuantGNN:
         return graph
 
     def auto_runs(self) -> int:
-        """Independent runs of subgraphs to issue a forward pass as (the selector's `runs`,
-        the largest over the layers), 1 unless the adjacency is stored block-diagonally and
-        the two halves of the batch hold the same work within 15 % (the tile counts are read
-        back once: this synchronizes; call it at set-up)."""
+        """Independent runs of subgraphs to issue a forward pass as: the selector's `runs` of
+        the layers that hold most of the aggregation work (each layer's answer weighted by the
+        columns it aggregates), 1 unless the adjacency is stored block-diagonally and the two
+        halves of the batch hold the same work within 15 % (the tile counts are read back
+        once: this synchronizes; call it at set-up)."""
         if getattr(self, "_auto_runs", None) is not None:
             return self._auto_runs
         runs = 1
         br = self.A.c.block_rows
         if br > 0 and br % 32 == 0 and self.map is not None and not self.update_first:
             n_blocks = -(-self.A.rows // br)
-            n_tr = -(-self.A.rows // 16)
-            runs = max(B.qgtc_plan_layer(self.A.rows, d, h, self.s, self.t, n_tile_rows=n_tr, a_cols=self.A.cols,
-                                         subgraphs=n_blocks)["runs"] for d, h in self.dims)
+            votes = {1: 0, 2: 0}
+            for l, (d, _) in enumerate(self.dims):
+                votes[self._batch_plan(l, n_blocks)["runs"]] += d
+            runs = 2 if votes[2] > votes[1] else 1
             if runs > 1:
                 cnt = self.map.row_cnt.cpu().to(torch.int64) + 1       # a tile row: its tiles plus a fixed part
                 half = (n_blocks // 2) * br // 16
@@ -446,21 +449,36 @@ class QuantGNN:
         self._auto_runs = runs
         return runs
 
-    def _run_tuning(self, l: int, whole_batch: bool):
-        """Tuning of layer l.  A run that covers part of the batch shares the device with the
-        other runs: it takes the K split the whole batch would get from the selector, not the
-        one its own (smaller) number of tile rows suggests - that one would split the tile
-        lists to fill a device the other runs are already filling."""
-        if whole_batch or (self.tuning is not None and self.tuning.layer_ksplit):
-            return self.tuning
+    def _batch_plan(self, l: int, subgraphs: int = 0) -> dict:
+        """The selector on layer l over the whole batch, with the adjacency's statistics when
+        the constructor read them."""
         d, h = self.dims[l]
         st = self.plan or {}
-        k = B.qgtc_plan_layer(self.A.rows, d, h, self.s, self.t, n_tile_rows=-(-self.A.rows // 16),
-                              a_cols=self.A.cols, nnz_tiles=st.get("nnz_tiles", (0, 0, 0)),
-                              nnz_row_words=st.get("nnz_row_words", 0))["ksplit"]
+        tiles = st.get("nnz_tiles", (0, 0, 0))
+        row_words = st.get("nnz_row_words", 0)
+        if self.tuning is not None and self.tuning.zero_words == B.ZERO_WORDS_VISIT and row_words:
+            # the caller fixed the form that visits every word: plan as for an adjacency whose
+            # words all hold a bit
+            row_words = 16 * max(tiles[0], 2 * tiles[1], 4 * tiles[2])
+        return B.qgtc_plan_layer(self.A.rows, d, h, self.s, self.t, n_tile_rows=-(-self.A.rows // 16),
+                                 a_cols=self.A.cols, nnz_tiles=tiles, nnz_row_words=row_words, subgraphs=subgraphs)
+
+    def _run_tuning(self, l: int, whole_batch: bool):
+        """Tuning of layer l.  A run that covers part of the batch shares the device with the
+        other runs: it takes the K split and the issue-priority choice the whole batch would
+        get from the selector, not the ones its own (smaller) number of tile rows suggests -
+        those would split the tile lists to fill a device the other runs are already filling,
+        and treat a launch as alone on the device that is not."""
+        if whole_batch or (self.tuning is not None and self.tuning.layer_ksplit):
+            return self.tuning
+        plan = self._batch_plan(l)
         base = self.tuning or B.Tuning()
+        # (the selector's wave-slot count assumes its own choice of kernel form: where the
+        # caller fixed another one, the priority scheme stays off)
+        same_form = plan["zero_words"] == 0 or base.zero_words in (0, plan["zero_words"])
         return B.Tuning(update_path=base.update_path, agg_xcd_run=base.agg_xcd_run, layer_path=base.layer_path,
-                        layer_ksplit=k, zero_words=base.zero_words)
+                        layer_ksplit=plan["ksplit"], zero_words=base.zero_words,
+                        even_progress=base.even_progress or (plan["even_progress"] if same_form else 1))
 
     def _run_layers(self, r0, r1, A, tmap, deg, xb, x_range, ranges, out, want_int, workspace):
         """All layers on rows [r0, r1) (whole subgraphs), on the current stream."""

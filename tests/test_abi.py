@@ -166,7 +166,8 @@ def test_tuning_is_range_checked_before_any_launch():
     Y = _fake_bits(b, 64, 64, 4, b.LEFT)
     W = _fake_bits(b, 64, 16, 4, b.RIGHT)
     for bad in (b._TuningC(3, 0, 0, 0), b._TuningC(0, 5000, 0, 0), b._TuningC(0, 0, 2, 0), b._TuningC(0, 0, 0, 3),
-                b._TuningC(-1, 0, 0, 0), b._TuningC(0, 0, 0, 0, 3, 0), b._TuningC(0, 0, 0, 0, -1, 0)):
+                b._TuningC(-1, 0, 0, 0), b._TuningC(0, 0, 0, 0, 3, 0), b._TuningC(0, 0, 0, 0, -1, 0),
+                b._TuningC(0, 0, 0, 0, 0, 3), b._TuningC(0, 0, 0, 0, 0, -1)):
         ep = b.Epilogue(mode=b.OUT_I32).to_c()
         ep.tuning = C.pointer(bad)
         assert l.qgtc_update(C.byref(Y), C.byref(W), C.byref(ep), C.c_void_p(0x20000), 16, None) == 7
@@ -227,8 +228,15 @@ def test_selector_and_scalar_helpers_on_the_host():
     plan = b.qgtc_plan_layer(262144, 512, 16, 2, 2, **kw5)
     assert (plan["zero_words"], plan["tile_kbits"]) == (1, 32)                  # too few planes to jump: least visited bits
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, nnz_row_words=480000, **kw)["tile_kbits"] == 128     # all tiles kept
-    # independent runs: two for a short launch over a batch of subgraphs, one otherwise
-    assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024, subgraphs=64)["runs"] == 2
+    # independent runs: two for a launch of more than one and at most two rounds of the wave slots over a batch of
+    # subgraphs, one otherwise; issue priority by remaining work when the launch has at most one wave per slot
+    # (256 compute units: 3072 slots at 8 planes visiting every word, 4096 with zero-word jumping)
+    plan = b.qgtc_plan_layer(65536, 64, 64, 8, 8, subgraphs=64, nnz_row_words=2000000, **kw)      # 4096 waves, visit all
+    assert (plan["runs"], plan["even_progress"]) == (2, 1)
+    plan = b.qgtc_plan_layer(65536, 64, 64, 8, 8, subgraphs=64, nnz_row_words=480000, **kw)       # jumping: one round
+    assert (plan["runs"], plan["even_progress"]) == (1, 2)
+    plan = b.qgtc_plan_layer(65536, 128, 64, 8, 8, subgraphs=64, nnz_row_words=480000, **kw)      # 8192 waves: two rounds
+    assert (plan["runs"], plan["even_progress"]) == (2, 1)
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024)["runs"] == 1            # one graph
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024, subgraphs=8)["runs"] == 1
     assert b.qgtc_plan_layer(262144, 512, 16, 8, 8, n_tile_rows=16384, a_cols=2048, subgraphs=128)["runs"] == 1   # long launch

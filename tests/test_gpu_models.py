@@ -128,12 +128,13 @@ def test_config4_gin_five_layers(nb):
 
 
 def test_selector_runs_on_the_bench_configurations():
-    """The full-size batches as bench.py issues them: config 4 (short launches, equal
-    subgraphs) as two independent runs on 128-bit tiles, config 5 (long launches, hubs first)
-    as one run on 64-bit tiles (32-bit tiles at 2 bits, where every word of a kept tile is
-    visited and the width with the fewest kept bits wins)."""
+    """The full-size batches as bench.py issues them: config 4 on 128-bit tiles as one run
+    (with zero-word jumping four of its five launches are exactly one round of the wave
+    slots) and as two runs when every word is visited (1.33 rounds); config 5 (long launches,
+    hubs first) as one run on 64-bit tiles (32-bit tiles at 2 bits, where every word of a kept
+    tile is visited and the width with the fewest kept bits wins)."""
     from paper_2111_09547_amd.model import QuantGNN, choose_tile_kbits
-    for cfg, want, kb in ((4, 2, 128), (5, 1, 64)):
+    for cfg, want, kb in ((4, 1, 128), (5, 1, 64)):
         w = make_workload(cfg)
         g = w.graph
         net = QuantGNN(dev(g.dense_compact()), [dev(W) for W in w.W], w.s, w.t, w.model == "gin",
@@ -142,6 +143,11 @@ def test_selector_runs_on_the_bench_configurations():
         assert net.tile_kbits == kb, cfg
         if cfg == 5:
             assert choose_tile_kbits(net.A, 512, 16, 2, 2) == 32
+        else:
+            visit = QuantGNN(net.A, [dev(W) for W in w.W], w.s, w.t, True, block_rows=g.block, tile_kbits="auto",
+                             tuning=q.Tuning(zero_words=q.ZERO_WORDS_VISIT))
+            assert visit.tuning.zero_words == q.ZERO_WORDS_VISIT and visit.auto_runs() == 2
+            del visit
         del net
         torch.cuda.empty_cache()
 
