@@ -129,12 +129,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
   const uint32_t kw_max = (uint32_t)(a.x_kwords - 1);
   __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.X, 0, (int)a.x_bytes, 0x00020000);
   const int km = a.ksplit - 1;                       // ksplit is 1, 2 or 4
+  const bool self_term = a.ep.self_term != 0;
 
   // B operands of the first matrix instruction of this wave, fetched while the Y tile
   // is still being finished
   const int ln = lane & 15;                          // row of Y / column of W inside a tile
   const int g = lane >> 4;                           // K sub-block, and row group of the result
   v4u b7_first, bb_first;                            // set in the last pass
+  // Short form of phase 3 (one K step, at most four output tiles per wave - every layer of up to
+  // 64 input columns): the operands of all the wave's tiles are requested at once
+  v4u bq7[4], bqb[4];
+  // (not below three planes: those kernels need fewer registers than this form, and a wave per
+  // SIMD more is worth more to them)
+  const bool short3 = S >= 3 && a.n_cg == 1 && p.n_nt_w <= 4 * nw;      // one column group: one pass below
 
   // ---- 1 + 2: aggregate, requantize, bytes into the Y tile ---------------------
   for (int pass = 0; pass < p.n_pass; ++pass) {
@@ -157,6 +164,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
     if (cg_ok)
       agg_loop_uniform<S, TW, KS, false, SKIP, AR, true>(acc, a, ra, va_off, rx, xoff, ci, n, kpart, a.ksplit, kw_base, kw_max, 0);
     __builtin_amdgcn_s_setprio(3);
+    // GIN self term: the 16 bits (row0 % 32 ..) of word row (row0 / 32) of every plane of X
+    // are this lane's codes of the 16 rows, bit-transposed; requested here, used behind the
+    // shift-and-add, so that their way through the memory system is not waited for (the
+    // words are left unset without a self term: set to zero on that path, the two paths would
+    // meet in a copy that waits for the loads)
+    uint32_t f[8];
+    if (self_term) {
+      const uint32_t srow = min((uint32_t)(out_row0 >> 5), kw_max);
+      const uint32_t voff = srow * a.ldx4 + col4;
+#pragma unroll
+      for (int i = 0; i < S; ++i) f[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff, (uint32_t)i * a.psx4, 0);
+    }
     uint32_t y[16];
     agg_shift_add<S>(acc, y);
 #pragma unroll
@@ -164,8 +183,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
 
     // (the same for the wave-uniform row tests below: computed up front they are kept as
     // sixteen SGPR pairs across the loop and spilled)
+    // (the sums take part in the same statement: whatever is fetched through k2 below is
+    // requested behind the shift-and-add, when the accumulators' registers are free)
     LateParams k2 = kp;
-    QGTC_LATE(k2);
+    asm volatile("" : "+s"(k2), "+v"(y[0]), "+v"(y[1]), "+v"(y[2]), "+v"(y[3]), "+v"(y[4]), "+v"(y[5]), "+v"(y[6]),
+                 "+v"(y[7]), "+v"(y[8]), "+v"(y[9]), "+v"(y[10]), "+v"(y[11]), "+v"(y[12]), "+v"(y[13]),
+                 "+v"(y[14]), "+v"(y[15]));
     int km2 = km, kpart2 = kpart, rows_left = a.rows - out_row0;
     asm volatile("" : "+s"(km2), "+s"(kpart2), "+s"(rows_left));
     if (pass == p.n_pass - 1) {
@@ -192,18 +215,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
       }
     }
 
-    // GIN self term: the 16 bits (row0 % 32 ..) of word row (row0 / 32) of every
-    // plane of X are this lane's codes of the 16 rows, bit-transposed
-    if (k2->a.ep.self_term != 0) {
-      const uint32_t srow = min((uint32_t)(out_row0 >> 5), kw_max);
-      const uint32_t voff = srow * a.ldx4 + col4;
+    if (self_term) {
       const int bit0 = out_row0 & 31;
-      uint32_t f[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        f[i] = 0u;
-        if (i < S) f[i] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff, (uint32_t)i * a.psx4, 0) >> bit0;
-      }
+      for (int i = 0; i < 8; ++i) f[i] = i < S ? f[i] >> bit0 : 0u;
       uint32_t lo0 = (f[0] & 0xffu) | ((f[1] & 0xffu) << 8) | ((f[2] & 0xffu) << 16) | (f[3] << 24);
       uint32_t hi0 = (f[4] & 0xffu) | ((f[5] & 0xffu) << 8) | ((f[6] & 0xffu) << 16) | (f[7] << 24);
       uint32_t lo1 = ((f[0] >> 8) & 0xffu) | (f[1] & 0xff00u) | ((f[2] & 0xff00u) << 8) | ((f[3] & 0xff00u) << 16);
@@ -245,6 +260,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
       }
     }
   }
+  if (short3) {
+    // (the first tile's operands are on their way since the end of the tile loop; the others
+    // are requested behind the pass loop: inside it, the compiler keeps their 24 registers
+    // allocated across the tile loop and spills them)
+    LateParams k2 = kp;
+    QGTC_LATE(k2);
+    bq7[0] = b7_first;
+    bqb[0] = bb_first;
+#pragma unroll
+    for (int q = 1; q < 4; ++q) {
+      const int nt = wave + q * nw;                  // wave-uniform
+      if (nt < k2->n_nt_w) {
+        const uint8_t* src = k2->wb + ((int64_t)nt * 64 + lane) * 16;
+        bq7[q] = *reinterpret_cast<const v4u*>(src);
+        bqb[q] = *reinterpret_cast<const v4u*>(src + (k2->split_w ? k2->wb_part : 0));
+      }
+    }
+  }
   __syncthreads();
 
   // ---- 3: Z += Y tile x W on the matrix cores -----------------------------------
@@ -259,6 +292,38 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
     const uint8_t* wb = k3->wb;
     const int64_t wb_part = k3->wb_part;
     const int n_units = n_nt * k3->n_kc;
+    if (short3) {
+      // the Y tile is one operand (16 rows x 64 bytes); every tile of the wave is one to four
+      // independent matrix instructions on it, and each element of Z has one writer
+      const v4u av = *reinterpret_cast<const v4u*>(yb + ln * ys + g * 16);
+      v4u a7 = av, ab = {0u, 0u, 0u, 0u};
+      if (split_y) {
+        a7 = av & 0x7f7f7f7fu;
+        ab = (av >> 7) & 0x01010101u;
+      }
+      const v4i zero = {0, 0, 0, 0};
+#pragma unroll
+      for (int q = 0; q < 5; ++q) {                  // (a fifth tile can only be the one that sums the rows)
+        const int nt = wave + q * nw;
+        if (nt >= n_nt) break;                       // wave-uniform
+        v4u b7 = bq7[q < 4 ? q : 0];
+        const bool ones = nt >= n_nt_w;              // the tile whose column 0 sums the rows of Y
+        if (ones) {
+          const uint32_t one = ln == 0 ? 0x01010101u : 0u;
+          b7 = (v4u){one, one, one, one};
+        }
+        v4i acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)b7, zero, 0, 0, 0);
+        v4i acc7 = zero, acc14 = zero;
+        if (split_y) acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)b7, acc7, 0, 0, 0);
+        if (split_w && !ones) {
+          acc7 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)a7, (v4i)bqb[q < 4 ? q : 0], acc7, 0, 0, 0);
+          if (split_y) acc14 = __builtin_amdgcn_mfma_i32_16x16x64_i8((v4i)ab, (v4i)bqb[q < 4 ? q : 0], acc14, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          z[(4 * g + r) * zs + nt * 16 + ln] = (uint32_t)acc1[r] + ((uint32_t)acc7[r] << 7) + ((uint32_t)acc14[r] << 14);
+      }
+    } else {
     // The wave's (unit, K step) pairs one after the other; the weights of the next pair are
     // requested before the matrix instructions of the current one, into the other of two
     // operand buffers (the loop body is written out twice, so no buffer is ever copied).
@@ -319,6 +384,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
         if (!pair(b7a, bba, b7b, bbb)) break;
         if (!pair(b7b, bbb, b7a, bba)) break;
       }
+    }
     }
   }
   __syncthreads();
