@@ -426,15 +426,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
       const int64_t ld_out = k4->up.ld_out;
       const int want_rowsum = k4->want_rowsum;
       const int sum_col = k4->n_nt_w * 16;
+      // The per-row vectors (degree-like sums) of the 16 rows: one load per wave, lane j holds
+      // row j, and a lane's row loop reads them back lane by lane - instead of 16 loads of
+      // one address each, waited for one after the other.
+      const int rj = out_row0 + min(lane & 15, valid_rows - 1);
+      int32_t ri_lane = 0, rl_lane = 0;
+      if (want_rowsum) ri_lane = (int32_t)z[(lane & 15) * zs + sum_col];
+      else if (e.row_i) ri_lane = e.row_i[rj];
+      if (e.row_l) rl_lane = e.row_l[rj];
+      const double colterm = e.ck + e.cs * (e.col_i ? (double)e.col_i[hc] : 0.0);
+      const float ca = e.col_a ? e.col_a[hc] : 1.0f;
+      const float cb = (e.col_a && e.col_b) ? e.col_b[hc] : 0.0f;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         const int row = out_row0 + j;
-        if (h_ok && j < valid_rows) {
-          double ri = 0.0;
-          if (want_rowsum) ri = (double)z[j * zs + sum_col];
-          else if (e.row_i) ri = (double)e.row_i[row];
-          out[(int64_t)row * ld_out + h] = dequantize_f64_ri(zz[j], ri, row, h, e);
-        }
+        const int32_t rij = __builtin_amdgcn_readlane(ri_lane, j);
+        const double ri = want_rowsum ? (double)(uint32_t)rij : (double)rij;   // a sum of codes, or the caller's int32
+        const double rl = (double)__builtin_amdgcn_readlane(rl_lane, j);
+        // the arithmetic of dequantize_f64_ri, with the row and column terms formed once
+        const double t1 = e.cc * (double)(int32_t)zz[j] + e.rs * ri;
+        const double l0 = e.l0a + e.l0b * rl;
+        double v = t1 + l0 * colterm;
+        if (e.col_a) v = v * (double)ca + (double)cb;
+        if (e.relu && v < 0.0) v = 0.0;
+        if (h_ok && j < valid_rows) out[(int64_t)row * ld_out + h] = (float)v;
       }
     } else {
       const int relu = k4->up.relu;
