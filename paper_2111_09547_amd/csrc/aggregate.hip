@@ -170,12 +170,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PK ? kPack1
       if (c_ok && row < p.rows) reinterpret_cast<int32_t*>(e.out)[(int64_t)row * e.ld_out + c] = o;
     }
   } else if (e.mode == QGTC_OUT_F32) {
+    // the per-row vectors of the 16 rows: one load per wave (lane j holds row j), read back
+    // lane by lane in the row loop
+    const int rj = min(out_row0 + (lane & 15), p.rows - 1);
+    const int32_t ri_lane = e.row_i ? e.row_i[rj] : 0;
+    const int32_t rl_lane = e.row_l ? e.row_l[rj] : 0;
+    const int cc_ = min(c, p.cols - 1);
+    const double colterm = e.ck + e.cs * (e.col_i ? (double)e.col_i[cc_] : 0.0);
+    const float ca = e.col_a ? e.col_a[cc_] : 1.0f;
+    const float cb = (e.col_a && e.col_b) ? e.col_b[cc_] : 0.0f;
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
+      const double ri = (double)__builtin_amdgcn_readlane(ri_lane, j);
+      const double rl = (double)__builtin_amdgcn_readlane(rl_lane, j);
       if ((j & km) != wave) continue;
       const int row = out_row0 + j;
-      if (c_ok && row < p.rows)
-        reinterpret_cast<float*>(e.out)[(int64_t)row * e.ld_out + c] = dequantize_f64(y[j], row, c, e);
+      // the arithmetic of dequantize_f64_ri, with the row and column terms formed once
+      const double t1 = e.cc * (double)(int32_t)y[j] + e.rs * ri;
+      const double l0 = e.l0a + e.l0b * rl;
+      double v = t1 + l0 * colterm;
+      if (e.col_a) v = v * (double)ca + (double)cb;
+      if (e.relu && v < 0.0) v = 0.0;
+      if (c_ok && row < p.rows) reinterpret_cast<float*>(e.out)[(int64_t)row * e.ld_out + c] = (float)v;
     }
   } else {
     const int qbits = e.rq_nbits;
