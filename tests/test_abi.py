@@ -235,7 +235,10 @@ def test_selector_and_scalar_helpers_on_the_host():
     assert (plan["runs"], plan["even_progress"]) == (2, 1)
     plan = b.qgtc_plan_layer(65536, 64, 64, 8, 8, subgraphs=64, nnz_row_words=480000, **kw)       # jumping: one round
     assert (plan["runs"], plan["even_progress"]) == (1, 2)
-    plan = b.qgtc_plan_layer(65536, 128, 64, 8, 8, subgraphs=64, nnz_row_words=480000, **kw)      # 8192 waves: two rounds
+    plan = b.qgtc_plan_layer(65536, 128, 64, 8, 8, subgraphs=64, nnz_row_words=480000, **kw)      # two column groups: one
+    assert (plan["runs"], plan["even_progress"]) == (1, 2)                                        # wave takes both, one round
+    kw6 = dict(n_tile_rows=6144, a_cols=1024, nnz_tiles=(196608, 98304, 49152))
+    plan = b.qgtc_plan_layer(98304, 64, 64, 8, 8, subgraphs=96, nnz_row_words=720000, **kw6)      # 6144 waves: 1.5 rounds
     assert (plan["runs"], plan["even_progress"]) == (2, 1)
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024)["runs"] == 1            # one graph
     assert b.qgtc_plan_layer(65536, 64, 64, 8, 8, n_tile_rows=4096, a_cols=1024, subgraphs=8)["runs"] == 1
