@@ -716,6 +716,11 @@ def test_zero_word_jumping_gives_the_same_integers(s, shape, p_edge):
             agg_ep = q.Epilogue(mode=q.OUT_BITS, rq_nbits=rq_bits, rq_inv_scale=float(inv), self_term=True)
             got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32, tuning=tn))
             assert (as_u32(got) == Z).all(), (kb, zw)
+            # the issue priority inside the tile loop (qgtc_tuning.even_progress) is scheduling only
+            for evp in (1, 2):
+                tn2 = q.Tuning(zero_words=zw, even_progress=evp)
+                got = q.qgtc_layer(Ab, m, Xb, Wb, agg_ep, q.Epilogue(mode=q.OUT_I32, tuning=tn2))
+                assert (as_u32(got) == Z).all(), (kb, zw, evp)
 
 
 @pytest.mark.parametrize("s", [5, 6, 8])
